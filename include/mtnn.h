@@ -1,0 +1,158 @@
+/*
+ * mtnn.h -- C ABI of the MI355X (gfx950) NT-operation library.
+ *
+ * The library computes the NT operation C = A x B^T of the MTNN paper (Shi, Xu, Chu,
+ * "Supervised Learning Based Algorithm Selection for Deep Neural Networks") in the two ways
+ * the paper compares, and selects between them per (m, n, k):
+ *
+ *   NT   one GEMM kernel that reads B as stored                      (Eq. 2)
+ *   TNN  out-of-place transpose of B, then an NN GEMM                (Algorithm 1, Eq. 1)
+ *   MTNN a boosted-tree predictor picks NT (+1) or TNN (-1)          (Algorithm 2)
+ *
+ * Conventions for every call
+ *   - matrices are row-major fp32; leading dimensions are in ELEMENTS;
+ *   - A, B, C, in, out and workspace are DEVICE pointers owned by the caller; the library
+ *     neither allocates nor frees device memory on these calls and keeps no reference to the
+ *     buffers after the enqueued work has run;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); work is enqueued
+ *     on it and the call returns without synchronising;
+ *   - alpha = 1 and there is no beta*C term (Section II): C is overwritten;
+ *   - padding elements (columns at or beyond the logical width when ld > width) are never
+ *     written in outputs and never influence results when present in inputs;
+ *   - the same inputs and shape give bit-identical outputs on every call (no atomics);
+ *   - the return value is MTNN_OK (0) or one of the MTNN_ERR_* codes below.  Arguments are
+ *     validated on the host before any device call, so a call that fails validation has
+ *     touched neither the device nor the outputs.
+ *   - degenerate sizes (the paper is silent): m == 0 or n == 0 is a successful no-op; k == 0
+ *     writes +0.0f to the m x n region of C (the empty sum); a transpose with rows == 0 or
+ *     cols == 0 is a successful no-op.
+ */
+#ifndef MTNN_H
+#define MTNN_H
+
+#include <stddef.h>
+
+#if defined(__GNUC__)
+#define MTNN_API __attribute__((visibility("default")))
+#else
+#define MTNN_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MTNN_OK = 0,
+    MTNN_ERR_DIM = 1,        /* a dimension is negative                                   */
+    MTNN_ERR_NULL = 2,       /* a NULL pointer with a non-empty problem                   */
+    MTNN_ERR_LD = 3,         /* a leading dimension smaller than the logical row length   */
+    MTNN_ERR_ALIAS = 4,      /* an output range overlaps an input range                   */
+    MTNN_ERR_WORKSPACE = 5,  /* workspace missing or too small (mtnn_tnn only)            */
+    MTNN_ERR_LAUNCH = 6,     /* the HIP runtime refused a launch                          */
+    MTNN_ERR_MODEL = 7,      /* model file missing, malformed or of the wrong arity       */
+    MTNN_ERR_ARG = 8,        /* any other invalid argument (bad config id, bad label ...) */
+    MTNN_ERR_NO_DEVICE = 9   /* no usable gfx950 device                                   */
+};
+
+/* ---- dense operations --------------------------------------------------------------- */
+
+/* NT operation, Eq. 2: C[i][j] = sum_l A[i][l] * B[j][l].
+ * A: m x k (lda >= k).  B: n x k (ldb >= k).  C: m x n (ldc >= n), overwritten. */
+MTNN_API int mtnn_nt(void *stream, int m, int n, int k,
+            const float *A, int lda, const float *B, int ldb, float *C, int ldc);
+
+/* NN operation, Eq. 1: C[i][j] = sum_l A[i][l] * B[l][j].
+ * A: m x k (lda >= k).  B: k x n (ldb >= n).  C: m x n (ldc >= n), overwritten. */
+MTNN_API int mtnn_nn(void *stream, int m, int n, int k,
+            const float *A, int lda, const float *B, int ldb, float *C, int ldc);
+
+/* Out-of-place transpose (Section III; the "transposeOnGPU" step of Algorithm 1):
+ * out[c][r] = in[r][c], copied as 32-bit words (bit-exact, NaN payloads and -0 included).
+ * in: rows x cols (ldin >= cols).  out: cols x rows (ldout >= rows). */
+MTNN_API int mtnn_transpose(void *stream, int rows, int cols,
+                   const float *in, int ldin, float *out, int ldout);
+
+/* Bytes of workspace TNN needs for B^T (n*k floats, rounded up to 256 B); 0 if n or k <= 0. */
+MTNN_API size_t mtnn_tnn_workspace_bytes(int n, int k);
+
+/* TNN, Algorithm 1: transpose B into `workspace` (k x n, ld = n), then the NN operation.
+ * Unlike the listing, the B^T buffer is the caller's: no allocation happens inside.
+ * Returns MTNN_ERR_WORKSPACE if workspace is NULL or smaller than mtnn_tnn_workspace_bytes(n, k).
+ * The workspace must not overlap A, B or C. */
+MTNN_API int mtnn_tnn(void *stream, int m, int n, int k,
+             const float *A, int lda, const float *B, int ldb, float *C, int ldc,
+             void *workspace, size_t workspace_bytes);
+
+/* MTNN, Algorithm 2: label = mtnn_select(m, n, k); +1 runs NT, -1 runs TNN.
+ * Memory rule of Section II: when the workspace is NULL or too small, NT runs whatever the
+ * predictor says.  `chosen` (may be NULL) receives +1 or -1 for the path actually run. */
+MTNN_API int mtnn_auto(void *stream, int m, int n, int k,
+              const float *A, int lda, const float *B, int ldb, float *C, int ldc,
+              void *workspace, size_t workspace_bytes, int *chosen);
+
+/* ---- selection (Section IV) ----------------------------------------------------------- */
+
+/* Predicted label for the NT operation of shape (m, n, k): +1 = NT, -1 = TNN; 0 if any of
+ * m, n, k is <= 0.  Host only, pure, O(trees x depth).  The feature vector is
+ * (m, n, k, n*k, m*n, m*k, m*n*k); the margin is the sum of the leaf values reached in each
+ * tree (a node sends x left when x[feature] < threshold) and the label is +1 when the margin
+ * is >= 0.  With no model loaded the answer is +1 (NT needs no extra memory). */
+MTNN_API int mtnn_select(int m, int n, int k);
+
+/* Number of features mtnn_select builds (7) and, into x[0..6], the features themselves. */
+MTNN_API int mtnn_num_features(void);
+MTNN_API int mtnn_features(int m, int n, int k, double *x);
+
+/* Load a model file and make it the current predictor.  On failure the current predictor is
+ * unchanged and MTNN_ERR_MODEL is returned.  mtnn_unload_model() returns to "always NT". */
+MTNN_API int mtnn_load_model(const char *path);
+MTNN_API int mtnn_save_model(const char *path);
+MTNN_API void mtnn_unload_model(void);
+
+/* Fit boosted regression trees on (X, labels) with the settings of Section IV-B and make the
+ * result the current predictor: logistic loss on y = (label == +1), exact greedy CART splits,
+ * `num_trees` rounds, depth <= max_depth, step eta, minimum loss reduction gamma, leaf penalty
+ * lambda, minimum child hessian weight min_child_weight.  X is nrows x nfeat row-major HOST
+ * doubles; labels are +1 / -1.  The paper's configuration is (8, 8, 1.0, 0.0) with the
+ * library defaults lambda = 1, min_child_weight = 1. */
+MTNN_API int mtnn_gbdt_train(int nrows, int nfeat, const double *X, const int *labels,
+                    int num_trees, int max_depth, double eta, double gamma,
+                    double lambda, double min_child_weight);
+
+/* Convenience for the selector itself: rows are (m, n, k) triples, features built internally,
+ * paper settings. */
+MTNN_API int mtnn_train_selector(int nrows, const int *mnk, const int *labels);
+
+/* Inspection of the current predictor (for tests and reports). */
+MTNN_API int mtnn_model_num_trees(void);
+MTNN_API int mtnn_model_num_features(void);
+MTNN_API int mtnn_model_tree_size(int tree);                       /* nodes, or -1 */
+/* node `idx` of `tree`, pre-order; feature = -1 for a leaf. */
+MTNN_API int mtnn_model_node(int tree, int idx, int *feature, double *threshold,
+                    int *left, int *right, double *value);
+/* margin of an arbitrary feature vector under the current predictor */
+MTNN_API int mtnn_model_margin(const double *x, int nfeat, double *margin);
+
+/* ---- tile configurations (tuning, tests) -------------------------------------------------- */
+
+/* The GEMM kernels come in several tile configurations; mtnn_nt / mtnn_nn choose one per shape
+ * with a fixed rule.  These calls run a given configuration (cfg in [0, count)), or the default
+ * choice when cfg == -1.  op: 0 = NN, 1 = NT. */
+MTNN_API int mtnn_gemm_config_count(void);
+MTNN_API const char *mtnn_gemm_config_name(int cfg);
+MTNN_API int mtnn_gemm_default_config(int op, int m, int n, int k);
+MTNN_API int mtnn_gemm_ex(void *stream, int op, int cfg, int m, int n, int k,
+                 const float *A, int lda, const float *B, int ldb, float *C, int ldc);
+
+/* ---- misc ---------------------------------------------------------------------------------- */
+
+MTNN_API const char *mtnn_status_string(int status);
+/* The hipError_t behind the most recent MTNN_ERR_LAUNCH in this process (0 if none); diagnostics. */
+MTNN_API int mtnn_last_hip_error(void);
+MTNN_API int mtnn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MTNN_H */

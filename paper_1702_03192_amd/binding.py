@@ -1,0 +1,270 @@
+"""Thin ctypes binding of libmtnn.so: same names as the C ABI, argument marshalling only.
+
+Device buffers are torch tensors (PyTorch owns device memory and streams); every step of the
+path runs inside the library's HIP kernels.  There is no CPU fallback: if the library has not
+been built the import of any entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmtnn.so")
+DEFAULT_MODEL = os.path.join(HERE, "data", "selector_gfx950.model")
+
+OK = 0
+STATUS_NAMES = {0: "OK", 1: "ERR_DIM", 2: "ERR_NULL", 3: "ERR_LD", 4: "ERR_ALIAS", 5: "ERR_WORKSPACE",
+                6: "ERR_LAUNCH", 7: "ERR_MODEL", 8: "ERR_ARG", 9: "ERR_NO_DEVICE"}
+OP_NN, OP_NT = 0, 1
+
+_c_int = ctypes.c_int
+_c_vp = ctypes.c_void_p
+_c_sz = ctypes.c_size_t
+_c_dbl = ctypes.c_double
+_p_int = ctypes.POINTER(ctypes.c_int)
+_p_dbl = ctypes.POINTER(ctypes.c_double)
+
+_GEMM = [_c_vp, _c_int, _c_int, _c_int, _c_vp, _c_int, _c_vp, _c_int, _c_vp, _c_int]
+
+# name -> (restype, argtypes): every symbol include/mtnn.h declares
+SIGNATURES = {
+    "mtnn_nt": (_c_int, _GEMM),
+    "mtnn_nn": (_c_int, _GEMM),
+    "mtnn_transpose": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_int, _c_vp, _c_int]),
+    "mtnn_tnn_workspace_bytes": (_c_sz, [_c_int, _c_int]),
+    "mtnn_tnn": (_c_int, _GEMM + [_c_vp, _c_sz]),
+    "mtnn_auto": (_c_int, _GEMM + [_c_vp, _c_sz, _p_int]),
+    "mtnn_select": (_c_int, [_c_int, _c_int, _c_int]),
+    "mtnn_num_features": (_c_int, []),
+    "mtnn_features": (_c_int, [_c_int, _c_int, _c_int, _p_dbl]),
+    "mtnn_load_model": (_c_int, [ctypes.c_char_p]),
+    "mtnn_save_model": (_c_int, [ctypes.c_char_p]),
+    "mtnn_unload_model": (None, []),
+    "mtnn_gbdt_train": (_c_int, [_c_int, _c_int, _c_vp, _c_vp, _c_int, _c_int, _c_dbl, _c_dbl, _c_dbl, _c_dbl]),
+    "mtnn_train_selector": (_c_int, [_c_int, _c_vp, _c_vp]),
+    "mtnn_model_num_trees": (_c_int, []),
+    "mtnn_model_num_features": (_c_int, []),
+    "mtnn_model_tree_size": (_c_int, [_c_int]),
+    "mtnn_model_node": (_c_int, [_c_int, _c_int, _p_int, _p_dbl, _p_int, _p_int, _p_dbl]),
+    "mtnn_model_margin": (_c_int, [_c_vp, _c_int, _p_dbl]),
+    "mtnn_gemm_config_count": (_c_int, []),
+    "mtnn_gemm_config_name": (ctypes.c_char_p, [_c_int]),
+    "mtnn_gemm_default_config": (_c_int, [_c_int, _c_int, _c_int, _c_int]),
+    "mtnn_gemm_ex": (_c_int, [_c_vp, _c_int, _c_int] + _GEMM[1:]),
+    "mtnn_status_string": (ctypes.c_char_p, [_c_int]),
+    "mtnn_last_hip_error": (_c_int, []),
+    "mtnn_version": (_c_int, []),
+}
+
+_lib = None
+
+
+class MtnnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({STATUS_NAMES.get(status, '?')})")
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library.  Raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_1702_03192_amd.build` "
+                               "(or __graft_entry__.build()) first; there is no CPU fallback")
+        # torch first: the library shares the HIP runtime torch has loaded (one runtime per
+        # process, so torch's streams and allocations are valid inside the library)
+        import torch  # noqa: F401
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+        if os.path.exists(DEFAULT_MODEL) and not os.environ.get("MTNN_NO_DEFAULT_MODEL"):
+            handle.mtnn_load_model(DEFAULT_MODEL.encode())
+    return _lib
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        if status == 6:
+            where = f"{where} (hipError {lib().mtnn_last_hip_error()})"
+        raise MtnnError(status, where)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _dev(t, name):
+    """(pointer, leading dimension) of a 2-D fp32 device tensor whose rows are contiguous."""
+    import torch
+    if t.dtype != torch.float32 or t.dim() != 2 or not t.is_cuda:
+        raise TypeError(f"{name} must be a 2-D float32 device tensor")
+    if t.shape[1] > 1 and t.stride(1) != 1:
+        raise TypeError(f"{name} must have unit column stride")
+    ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], 1)
+    return t.data_ptr(), int(ld)
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+# ---- dense operations: the tensors' shapes give m, n, k and the leading dimensions -----------
+
+def mtnn_nt(A, B, C, stream=None):
+    """C = A x B^T.  A: m x k, B: n x k, C: m x n."""
+    (pa, lda), (pb, ldb), (pc, ldc) = _dev(A, "A"), _dev(B, "B"), _dev(C, "C")
+    m, k = A.shape
+    n = B.shape[0]
+    if B.shape[1] != k or tuple(C.shape) != (m, n):
+        raise ValueError("shape mismatch")
+    _check(lib().mtnn_nt(_stream(stream), m, n, k, pa, lda, pb, ldb, pc, ldc), "mtnn_nt")
+    return C
+
+
+def mtnn_nn(A, B, C, stream=None):
+    """C = A x B.  A: m x k, B: k x n, C: m x n."""
+    (pa, lda), (pb, ldb), (pc, ldc) = _dev(A, "A"), _dev(B, "B"), _dev(C, "C")
+    m, k = A.shape
+    n = B.shape[1]
+    if B.shape[0] != k or tuple(C.shape) != (m, n):
+        raise ValueError("shape mismatch")
+    _check(lib().mtnn_nn(_stream(stream), m, n, k, pa, lda, pb, ldb, pc, ldc), "mtnn_nn")
+    return C
+
+
+def mtnn_gemm_ex(op, cfg, A, B, C, stream=None):
+    """A given tile configuration of the NN (op 0) or NT (op 1) kernel; cfg -1 = default rule."""
+    (pa, lda), (pb, ldb), (pc, ldc) = _dev(A, "A"), _dev(B, "B"), _dev(C, "C")
+    m, k = A.shape
+    n = B.shape[0] if op == OP_NT else B.shape[1]
+    _check(lib().mtnn_gemm_ex(_stream(stream), op, cfg, m, n, k, pa, lda, pb, ldb, pc, ldc), "mtnn_gemm_ex")
+    return C
+
+
+def mtnn_transpose(X, out, stream=None):
+    """out = X^T, bit-exact.  X: rows x cols, out: cols x rows."""
+    (pi, ldi), (po, ldo) = _dev(X, "in"), _dev(out, "out")
+    rows, cols = X.shape
+    if tuple(out.shape) != (cols, rows):
+        raise ValueError("shape mismatch")
+    _check(lib().mtnn_transpose(_stream(stream), rows, cols, pi, ldi, po, ldo), "mtnn_transpose")
+    return out
+
+
+def mtnn_tnn_workspace_bytes(n: int, k: int) -> int:
+    return int(lib().mtnn_tnn_workspace_bytes(n, k))
+
+
+def mtnn_tnn(A, B, C, workspace, stream=None):
+    """Algorithm 1 with a caller-owned B^T workspace (any device tensor of enough bytes)."""
+    (pa, lda), (pb, ldb), (pc, ldc) = _dev(A, "A"), _dev(B, "B"), _dev(C, "C")
+    m, k = A.shape
+    n = B.shape[0]
+    pw, wb = _ws(workspace)
+    _check(lib().mtnn_tnn(_stream(stream), m, n, k, pa, lda, pb, ldb, pc, ldc, pw, wb), "mtnn_tnn")
+    return C
+
+
+def mtnn_auto(A, B, C, workspace=None, stream=None) -> int:
+    """Algorithm 2.  Returns the label of the path that ran (+1 NT, -1 TNN)."""
+    (pa, lda), (pb, ldb), (pc, ldc) = _dev(A, "A"), _dev(B, "B"), _dev(C, "C")
+    m, k = A.shape
+    n = B.shape[0]
+    pw, wb = _ws(workspace)
+    chosen = ctypes.c_int(0)
+    _check(lib().mtnn_auto(_stream(stream), m, n, k, pa, lda, pb, ldb, pc, ldc, pw, wb, ctypes.byref(chosen)),
+           "mtnn_auto")
+    return chosen.value
+
+
+# ---- selection ----------------------------------------------------------------------------
+
+def mtnn_select(m: int, n: int, k: int) -> int:
+    return int(lib().mtnn_select(m, n, k))
+
+
+def mtnn_features(m: int, n: int, k: int):
+    x = (ctypes.c_double * lib().mtnn_num_features())()
+    _check(lib().mtnn_features(m, n, k, x), "mtnn_features")
+    return list(x)
+
+
+def mtnn_load_model(path: str) -> None:
+    _check(lib().mtnn_load_model(os.fsencode(path)), "mtnn_load_model")
+
+
+def mtnn_save_model(path: str) -> None:
+    _check(lib().mtnn_save_model(os.fsencode(path)), "mtnn_save_model")
+
+
+def mtnn_unload_model() -> None:
+    lib().mtnn_unload_model()
+
+
+def mtnn_gbdt_train(X, labels, num_trees=8, max_depth=8, eta=1.0, gamma=0.0, lam=1.0, min_child_weight=1.0):
+    import numpy as np
+    X = np.ascontiguousarray(X, dtype=np.float64)
+    y = np.ascontiguousarray(labels, dtype=np.int32)
+    _check(lib().mtnn_gbdt_train(X.shape[0], X.shape[1], X.ctypes.data, y.ctypes.data, num_trees, max_depth,
+                                 eta, gamma, lam, min_child_weight), "mtnn_gbdt_train")
+
+
+def mtnn_train_selector(shapes, labels) -> None:
+    import numpy as np
+    mnk = np.ascontiguousarray(shapes, dtype=np.int32).reshape(-1, 3)
+    y = np.ascontiguousarray(labels, dtype=np.int32)
+    _check(lib().mtnn_train_selector(mnk.shape[0], mnk.ctypes.data, y.ctypes.data), "mtnn_train_selector")
+
+
+def model_trees():
+    """The current predictor as lists of (feature, threshold, left, right, value) per tree."""
+    L = lib()
+    out = []
+    for t in range(L.mtnn_model_num_trees()):
+        rows = []
+        for i in range(L.mtnn_model_tree_size(t)):
+            f, l, r = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+            thr, val = ctypes.c_double(), ctypes.c_double()
+            _check(L.mtnn_model_node(t, i, ctypes.byref(f), ctypes.byref(thr), ctypes.byref(l), ctypes.byref(r),
+                                     ctypes.byref(val)), "mtnn_model_node")
+            rows.append((f.value, thr.value, l.value, r.value, val.value))
+        out.append(rows)
+    return out
+
+
+def mtnn_model_margin(x) -> float:
+    import numpy as np
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    out = ctypes.c_double()
+    _check(lib().mtnn_model_margin(x.ctypes.data, x.size, ctypes.byref(out)), "mtnn_model_margin")
+    return out.value
+
+
+def gemm_configs():
+    L = lib()
+    return [L.mtnn_gemm_config_name(i).decode() for i in range(L.mtnn_gemm_config_count())]
+
+
+def mtnn_gemm_default_config(op: int, m: int, n: int, k: int) -> int:
+    return int(lib().mtnn_gemm_default_config(op, m, n, k))
+
+
+def mtnn_status_string(status: int) -> str:
+    return lib().mtnn_status_string(status).decode()
+
+
+def mtnn_version() -> int:
+    return int(lib().mtnn_version())

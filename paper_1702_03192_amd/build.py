@@ -1,0 +1,68 @@
+"""Build libmtnn.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
+
+hipcc cross-compiles without a GPU.  The shared library lands next to this file so that it
+travels with the source tree.
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libmtnn.so")
+
+SOURCES = ["gemm.hip", "transpose.hip", "fc.hip", "api.cpp", "selector.cpp"]
+
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-parameter", "-ffp-contract=off",
+          "-fvisibility=hidden"]
+# packed fp32 VALU forms are switched off for device code (build flags)
+DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def _compile(src: str) -> str:
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+    path = os.path.join(CSRC, src)
+    cmd = ["hipcc"] + COMMON + (DEVICE if src.endswith(".hip") else ["-x", "hip", "--offload-arch=gfx950"]) + \
+          ["-c", path, "-o", obj]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {src}:\n{out}")
+    if out.strip():
+        print(out, file=sys.stderr)
+    return obj
+
+
+def _torch_lib_dir():
+    import importlib.util
+    spec = importlib.util.find_spec("torch")
+    if spec is None or not spec.submodule_search_locations:
+        return None
+    d = os.path.join(list(spec.submodule_search_locations)[0], "lib")
+    return d if os.path.exists(os.path.join(d, "libamdhip64.so")) else None
+
+
+def build(verbose: bool = False) -> str:
+    os.makedirs(OBJ, exist_ok=True)
+    sources = [s for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
+    with ThreadPoolExecutor(max_workers=min(8, len(sources))) as pool:
+        objs = list(pool.map(_compile, sources))
+    # Link against the HIP runtime PyTorch ships (recorded as NEEDED "libamdhip64.so"), so that a
+    # process that has imported torch runs one HIP runtime and torch's stream handles are valid
+    # in the library; without torch the system runtime under /opt/rocm/lib is found by RUNPATH.
+    tdir = _torch_lib_dir()
+    hip_lib_dir = tdir or "/opt/rocm/lib"
+    cmd = ["g++", "-shared", "-fPIC", "-o", LIB] + objs + \
+          ["-L" + hip_lib_dir, "-l:libamdhip64.so", "-Wl,-rpath,/opt/rocm/lib", "-Wl,--no-undefined"]
+    subprocess.run(cmd, check=True)
+    if verbose:
+        print(LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    build(verbose=True)

@@ -1,0 +1,180 @@
+// C ABI of libmtnn: argument validation, Algorithm 1 (TNN) and Algorithm 2 (MTNN) of the paper
+// as host-side compositions of the HIP kernels.  Validation is pure host code and runs before
+// any HIP call, so it behaves the same on a machine without a GPU.
+#include "../../include/mtnn.h"
+#include "mtnn_internal.h"
+#include "selector.h"
+
+#include <stdint.h>
+
+namespace {
+
+int g_last_hip_error = 0;   // last non-zero HIP error a launcher reported (diagnostics only)
+
+int launch_status(int err)
+{
+    if (err == 0) return MTNN_OK;
+    g_last_hip_error = err;
+    return MTNN_ERR_LAUNCH;
+}
+
+struct Range {
+    uintptr_t lo, hi;   // [lo, hi)
+};
+
+// bytes spanned by a rows x cols fp32 matrix with leading dimension ld
+Range span(const void* p, long long rows, long long cols, long long ld)
+{
+    Range r;
+    r.lo = reinterpret_cast<uintptr_t>(p);
+    if (rows <= 0 || cols <= 0) { r.hi = r.lo; return r; }
+    r.hi = r.lo + (uintptr_t)(((rows - 1) * ld + cols) * 4);
+    return r;
+}
+
+bool overlap(const Range& a, const Range& b)
+{
+    return a.lo < a.hi && b.lo < b.hi && a.lo < b.hi && b.lo < a.hi;
+}
+
+int check_gemm(int op, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
+               const float* C, int ldc)
+{
+    if (m < 0 || n < 0 || k < 0) return MTNN_ERR_DIM;
+    if (m == 0 || n == 0) return MTNN_OK;
+    if (!C) return MTNN_ERR_NULL;
+    if (ldc < n) return MTNN_ERR_LD;
+    if (k == 0) return MTNN_OK;
+    if (!A || !B) return MTNN_ERR_NULL;
+    if (lda < k) return MTNN_ERR_LD;
+    const int b_rows = (op == mtnn::OP_NT) ? n : k;
+    const int b_cols = (op == mtnn::OP_NT) ? k : n;
+    if (ldb < b_cols) return MTNN_ERR_LD;
+    const Range rc = span(C, m, n, ldc);
+    if (overlap(rc, span(A, m, k, lda)) || overlap(rc, span(B, b_rows, b_cols, ldb))) return MTNN_ERR_ALIAS;
+    return MTNN_OK;
+}
+
+int run_gemm(void* stream, int op, int cfg, int m, int n, int k, const float* A, int lda,
+             const float* B, int ldb, float* C, int ldc)
+{
+    const int st = check_gemm(op, m, n, k, A, lda, B, ldb, C, ldc);
+    if (st != MTNN_OK) return st;
+    if (m == 0 || n == 0) return MTNN_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int err;
+    if (k == 0) err = mtnn::launch_fill_zero(s, m, n, C, ldc);
+    else err = mtnn::launch_gemm(s, op, cfg, m, n, k, A, lda, B, ldb, C, ldc);
+    return launch_status(err);
+}
+
+int check_transpose(int rows, int cols, const float* in, int ldin, const float* out, int ldout)
+{
+    if (rows < 0 || cols < 0) return MTNN_ERR_DIM;
+    if (rows == 0 || cols == 0) return MTNN_OK;
+    if (!in || !out) return MTNN_ERR_NULL;
+    if (ldin < cols || ldout < rows) return MTNN_ERR_LD;
+    if (overlap(span(in, rows, cols, ldin), span(out, cols, rows, ldout))) return MTNN_ERR_ALIAS;
+    return MTNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mtnn_nt(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
+            float* C, int ldc)
+{
+    return run_gemm(stream, mtnn::OP_NT, -1, m, n, k, A, lda, B, ldb, C, ldc);
+}
+
+int mtnn_nn(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
+            float* C, int ldc)
+{
+    return run_gemm(stream, mtnn::OP_NN, -1, m, n, k, A, lda, B, ldb, C, ldc);
+}
+
+int mtnn_gemm_ex(void* stream, int op, int cfg, int m, int n, int k, const float* A, int lda,
+                 const float* B, int ldb, float* C, int ldc)
+{
+    if ((op != mtnn::OP_NN && op != mtnn::OP_NT) || cfg < -1 || cfg >= mtnn::gemm_config_count())
+        return MTNN_ERR_ARG;
+    return run_gemm(stream, op, cfg, m, n, k, A, lda, B, ldb, C, ldc);
+}
+
+int mtnn_gemm_config_count(void) { return mtnn::gemm_config_count(); }
+const char* mtnn_gemm_config_name(int cfg) { return mtnn::gemm_config_name(cfg); }
+int mtnn_gemm_default_config(int op, int m, int n, int k)
+{
+    if ((op != mtnn::OP_NN && op != mtnn::OP_NT) || m <= 0 || n <= 0 || k <= 0) return -1;
+    return mtnn::gemm_default_config(op, m, n, k);
+}
+
+int mtnn_transpose(void* stream, int rows, int cols, const float* in, int ldin, float* out, int ldout)
+{
+    const int st = check_transpose(rows, cols, in, ldin, out, ldout);
+    if (st != MTNN_OK) return st;
+    if (rows == 0 || cols == 0) return MTNN_OK;
+    const int err = mtnn::launch_transpose(static_cast<hipStream_t>(stream), rows, cols, in, ldin, out, ldout);
+    return launch_status(err);
+}
+
+size_t mtnn_tnn_workspace_bytes(int n, int k)
+{
+    if (n <= 0 || k <= 0) return 0;
+    const size_t bytes = (size_t)n * (size_t)k * 4u;
+    return (bytes + 255u) & ~(size_t)255u;
+}
+
+int mtnn_tnn(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
+             float* C, int ldc, void* workspace, size_t workspace_bytes)
+{
+    int st = check_gemm(mtnn::OP_NT, m, n, k, A, lda, B, ldb, C, ldc);
+    if (st != MTNN_OK) return st;
+    if (m == 0 || n == 0) return MTNN_OK;
+    if (k == 0) return run_gemm(stream, mtnn::OP_NT, -1, m, n, k, A, lda, B, ldb, C, ldc);
+    if (!workspace || workspace_bytes < mtnn_tnn_workspace_bytes(n, k)) return MTNN_ERR_WORKSPACE;
+    float* Bt = static_cast<float*>(workspace);
+    const Range rw = span(Bt, k, n, n);
+    if (overlap(rw, span(A, m, k, lda)) || overlap(rw, span(B, n, k, ldb)) || overlap(rw, span(C, m, n, ldc)))
+        return MTNN_ERR_ALIAS;
+    // Algorithm 1: B (n x k) -> B^T (k x n), then the NN product on the same stream
+    st = mtnn_transpose(stream, n, k, B, ldb, Bt, n);
+    if (st != MTNN_OK) return st;
+    return run_gemm(stream, mtnn::OP_NN, -1, m, n, k, A, lda, Bt, n, C, ldc);
+}
+
+int mtnn_auto(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
+              float* C, int ldc, void* workspace, size_t workspace_bytes, int* chosen)
+{
+    // Algorithm 2.  The memory rule of Section II overrides the predictor.
+    int label = (m > 0 && n > 0 && k > 0) ? mtnn_select(m, n, k) : 1;
+    if (label == -1 && (!workspace || workspace_bytes < mtnn_tnn_workspace_bytes(n, k))) label = 1;
+    if (chosen) *chosen = label;
+    if (label == -1)
+        return mtnn_tnn(stream, m, n, k, A, lda, B, ldb, C, ldc, workspace, workspace_bytes);
+    return mtnn_nt(stream, m, n, k, A, lda, B, ldb, C, ldc);
+}
+
+const char* mtnn_status_string(int status)
+{
+    switch (status) {
+        case MTNN_OK: return "ok";
+        case MTNN_ERR_DIM: return "negative dimension";
+        case MTNN_ERR_NULL: return "null pointer with a non-empty problem";
+        case MTNN_ERR_LD: return "leading dimension smaller than the row length";
+        case MTNN_ERR_ALIAS: return "output overlaps an input";
+        case MTNN_ERR_WORKSPACE: return "workspace missing or too small";
+        case MTNN_ERR_LAUNCH: return "HIP launch failed";
+        case MTNN_ERR_MODEL: return "model file missing or malformed";
+        case MTNN_ERR_ARG: return "invalid argument";
+        case MTNN_ERR_NO_DEVICE: return "no usable gfx950 device";
+        default: return "unknown status";
+    }
+}
+
+int mtnn_last_hip_error(void) { return g_last_hip_error; }
+
+int mtnn_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,387 @@
+// fp32 GEMM kernels for gfx950 on the matrix cores:
+//   NN (Eq. 1 of the MTNN paper):  C[i][j] = sum_l A[i][l] * B[l][j]   A m x k, B k x n
+//   NT (Eq. 2):                    C[i][j] = sum_l A[i][l] * B[j][l]   A m x k, B n x k
+// all row-major, alpha = 1, no beta term (Section II).
+//
+// Design (ours; the paper calls a closed library for both operations):
+//   * one workgroup computes a BM x BN tile of C, stepping through k in slabs of BK;
+//   * each 64-lane wave owns a WM x WN sub-tile built from 32x32 blocks, each block advanced
+//     by v_mfma_f32_32x32x2_f32 (lane l supplies A[l%32][l/32] and B[l/32][l%32]; 16
+//     accumulator registers per block, register r of lane l holding row 8*(r/4)+4*(l/32)+r%4,
+//     column l%32);
+//   * slabs are staged global -> registers -> LDS with two LDS buffers, so the loads of slab
+//     t+1 are in flight while slab t feeds the matrix cores, and one barrier per slab suffices;
+//   * A is kept in LDS as [row][k] with a padded row stride, so a lane fetches four consecutive
+//     k of its row with one 128-bit LDS read.  The order in which k is consumed inside a group
+//     of 8 is permuted (lanes 0-31 take k = 0..3, lanes 32-63 take k = 4..7); A and B use the
+//     same permutation and a sum does not care;
+//   * NT: B rows are k-contiguous exactly like A rows, so B uses the same staging as A.
+//     NN: B rows are n-contiguous; the slab is kept as [k][n] and a lane reads its column
+//     word by word (consecutive lanes -> consecutive words, conflict-free);
+//   * rows of A / B beyond m / n are clamped to the last valid row: they only feed outputs
+//     that are never stored.  Elements beyond k are zero-filled in both operands, so padding
+//     (which may hold NaN) never reaches a sum;
+//   * workgroup ids are remapped so that each XCD (the hardware deals consecutive ids round
+//     robin to its 8 XCDs, each with a private L2) works on one compact band of C tiles.
+//
+// The summation order of every C element is fixed by (configuration, k), never by timing:
+// results are bit-reproducible.
+#include "mtnn_internal.h"
+
+namespace mtnn {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct GemmParams {
+    const float* A;
+    const float* B;
+    float* C;
+    int M, N, K;
+    long lda, ldb, ldc;
+    int tiles_m, tiles_n;
+    int group_m;      // C-tile rows per band (L2 locality)
+    int num_xcd;      // 8 on MI355X
+};
+
+// ---- guarded global loads -------------------------------------------------------------------
+
+// Four consecutive k of one row.  FAST: the caller guarantees kidx + 3 < K (interior slab), so
+// the load is unconditional and the k loop stays free of divergent branches; otherwise elements
+// at or beyond K read as zero.
+template <bool VEC, bool FAST>
+__device__ __forceinline__ f32x4 load_k4(const float* __restrict__ row, int kidx, int K)
+{
+    if (FAST || kidx + 3 < K) {
+        if (VEC) return *reinterpret_cast<const f32x4*>(row + kidx);
+        f32x4 v;
+        v.x = row[kidx]; v.y = row[kidx + 1]; v.z = row[kidx + 2]; v.w = row[kidx + 3];
+        return v;
+    }
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (kidx < K) v.x = row[kidx];
+    if (kidx + 1 < K) v.y = row[kidx + 1];
+    if (kidx + 2 < K) v.z = row[kidx + 2];
+    return v;
+}
+
+// Four consecutive n of one k-row of B (NN).  FAST: krow < K and nidx + 3 < N are guaranteed.
+// Otherwise columns beyond N are clamped (they feed only outputs that are never stored) and
+// rows at or beyond K read as zero.
+template <bool VEC, bool FAST>
+__device__ __forceinline__ f32x4 load_n4(const float* __restrict__ B, long ldb, int krow, int K, int nidx, int N)
+{
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (!FAST && krow >= K) return v;
+    const float* row = B + (size_t)krow * ldb;
+    if (FAST || nidx + 3 < N) {
+        if (VEC) return *reinterpret_cast<const f32x4*>(row + nidx);
+        v.x = row[nidx]; v.y = row[nidx + 1]; v.z = row[nidx + 2]; v.w = row[nidx + 3];
+        return v;
+    }
+    const int last = N - 1;
+    v.x = row[min(nidx, last)];
+    v.y = row[min(nidx + 1, last)];
+    v.z = row[min(nidx + 2, last)];
+    v.w = row[min(nidx + 3, last)];
+    return v;
+}
+
+// ---- workgroup id -> C tile -------------------------------------------------------------------
+
+__device__ __forceinline__ void tile_of_block(const GemmParams& p, int& tm, int& tn)
+{
+    const int total = p.tiles_m * p.tiles_n;
+    int pid = blockIdx.x;
+    // undo the round-robin deal to XCDs: XCD x receives ids x, x+X, x+2X, ...; give it the
+    // contiguous range of logical ids [start(x), start(x+1))
+    const int X = p.num_xcd;
+    if (X > 1 && total >= X) {
+        const int per = (total + X - 1) / X;
+        const int tall = total - (per - 1) * X;        // XCDs that get `per` ids (1..X)
+        const int x = pid % X;
+        const int local = pid / X;
+        pid = (x < tall) ? x * per + local
+                         : tall * per + (x - tall) * (per - 1) + local;
+    }
+    // bands of group_m tile rows, walked column by column inside a band
+    const int band_sz = p.group_m * p.tiles_n;
+    const int band = pid / band_sz;
+    const int first_m = band * p.group_m;
+    const int rows_here = min(p.tiles_m - first_m, p.group_m);
+    const int in_band = pid - band * band_sz;
+    tm = first_m + in_band % rows_here;
+    tn = in_band / rows_here;
+}
+
+// ---- the kernel ------------------------------------------------------------------------------
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, bool VEC>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(GemmParams p)
+{
+    constexpr int NTH = WAVES_M * WAVES_N * 64;
+    constexpr int WM = BM / WAVES_M;
+    constexpr int WN = BN / WAVES_N;
+    constexpr int TM = WM / 32;
+    constexpr int TN = WN / 32;
+    constexpr int KQ = BK / 4;                       // float4 groups along k
+    constexpr int SA = BK + 4;                       // LDS row stride of a [row][k] tile
+    constexpr int SBN = BN + 8;                      // LDS row stride of the [k][n] tile (NN)
+    constexpr int A_WORDS = BM * SA;
+    constexpr int B_WORDS = NT ? BN * SA : BK * SBN;
+    constexpr int A_VECS = BM * KQ;                  // float4 groups in an A slab
+    constexpr int B_VECS = NT ? BN * KQ : BK * (BN / 4);
+    constexpr int A_LOADS = (A_VECS + NTH - 1) / NTH;
+    constexpr int B_LOADS = (B_VECS + NTH - 1) / NTH;
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be built from 32x32 blocks");
+    static_assert(BK % 8 == 0, "k slab must be a multiple of 8");
+    static_assert(A_VECS % NTH == 0 || A_VECS < NTH, "A slab: whole passes, or a single partial one");
+    static_assert(B_VECS % NTH == 0 || B_VECS < NTH, "B slab: whole passes, or a single partial one");
+    const bool a_on = (A_VECS >= NTH) || ((int)threadIdx.x < A_VECS);   // thread takes part in staging A
+    const bool b_on = (B_VECS >= NTH) || ((int)threadIdx.x < B_VECS);
+
+    // dynamic LDS: [2][A_WORDS] then [2][B_WORDS]; the large tiles need more than the 64 KB a
+    // kernel may declare statically
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    float(*As)[A_WORDS] = reinterpret_cast<float(*)[A_WORDS]>(lds);
+    float(*Bs)[B_WORDS] = reinterpret_cast<float(*)[B_WORDS]>(lds + 2 * A_WORDS);
+
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = t >> 6;
+    const int lr = lane & 31;
+    const int lh = lane >> 5;
+    const int wm0 = (wave / WAVES_N) * WM;
+    const int wn0 = (wave % WAVES_N) * WN;
+
+    int tm, tn;
+    tile_of_block(p, tm, tn);
+    const int m0 = tm * BM;
+    const int n0 = tn * BN;
+    const int M = p.M, N = p.N, K = p.K;
+
+    // per-thread staging geometry
+    const float* a_row[A_LOADS];
+    int a_kq[A_LOADS], a_lds[A_LOADS];
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) {
+        const int f = a_on ? t + i * NTH : 0;
+        const int row = f / KQ;
+        a_kq[i] = (f % KQ) * 4;
+        a_row[i] = p.A + (size_t)min(m0 + row, M - 1) * p.lda;
+        a_lds[i] = row * SA + a_kq[i];
+    }
+    const float* b_row[B_LOADS];
+    int b_off[B_LOADS], b_lds[B_LOADS], b_krow[B_LOADS];
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) {
+        const int f = b_on ? t + i * NTH : 0;
+        if (NT) {
+            const int row = f / KQ;
+            b_off[i] = (f % KQ) * 4;
+            b_row[i] = p.B + (size_t)min(n0 + row, N - 1) * p.ldb;
+            b_lds[i] = row * SA + b_off[i];
+            b_krow[i] = 0;
+        } else {
+            b_krow[i] = f / (BN / 4);
+            b_off[i] = n0 + (f % (BN / 4)) * 4;
+            b_row[i] = p.B;
+            b_lds[i] = b_krow[i] * SBN + (f % (BN / 4)) * 4;
+        }
+    }
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    f32x4 a_st[A_LOADS], b_st[B_LOADS];
+    // interior slabs (the whole slab below K and, for the [k][n] tile of NN, the whole tile left
+    // of N) load without guards; only the last, ragged slab takes the guarded path
+    const bool n_interior = NT || (n0 + BN <= N);
+    auto fetch = [&](int k0) {
+        if (k0 + BK <= K && n_interior) {
+#pragma unroll
+            for (int i = 0; i < A_LOADS; ++i)
+                if (a_on) a_st[i] = load_k4<VEC, true>(a_row[i], k0 + a_kq[i], K);
+#pragma unroll
+            for (int i = 0; i < B_LOADS; ++i) {
+                if (!b_on) continue;
+                if (NT) b_st[i] = load_k4<VEC, true>(b_row[i], k0 + b_off[i], K);
+                else b_st[i] = load_n4<VEC, true>(b_row[i], p.ldb, k0 + b_krow[i], K, b_off[i], N);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < A_LOADS; ++i)
+                if (a_on) a_st[i] = load_k4<VEC, false>(a_row[i], k0 + a_kq[i], K);
+#pragma unroll
+            for (int i = 0; i < B_LOADS; ++i) {
+                if (!b_on) continue;
+                if (NT) b_st[i] = load_k4<VEC, false>(b_row[i], k0 + b_off[i], K);
+                else b_st[i] = load_n4<VEC, false>(b_row[i], p.ldb, k0 + b_krow[i], K, b_off[i], N);
+            }
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i)
+            if (a_on) *reinterpret_cast<f32x4*>(&As[buf][a_lds[i]]) = a_st[i];
+#pragma unroll
+        for (int i = 0; i < B_LOADS; ++i)
+            if (b_on) *reinterpret_cast<f32x4*>(&Bs[buf][b_lds[i]]) = b_st[i];
+    };
+
+    const int num_slabs = (K + BK - 1) / BK;
+    fetch(0);
+    stash(0);
+    __syncthreads();
+
+    for (int s = 0; s < num_slabs; ++s) {
+        const int buf = s & 1;
+        const bool more = (s + 1 < num_slabs);
+        if (more) fetch((s + 1) * BK);
+
+        const float* as = As[buf];
+        const float* bs = Bs[buf];
+#pragma unroll
+        for (int kk = 0; kk < BK / 8; ++kk) {
+            f32x4 af[TM], bf[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                af[i] = *reinterpret_cast<const f32x4*>(&as[(wm0 + i * 32 + lr) * SA + kk * 8 + lh * 4]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if (NT) {
+                    bf[j] = *reinterpret_cast<const f32x4*>(&bs[(wn0 + j * 32 + lr) * SA + kk * 8 + lh * 4]);
+                } else {
+                    const float* col = &bs[(kk * 8 + lh * 4) * SBN + wn0 + j * 32 + lr];
+                    bf[j].x = col[0];
+                    bf[j].y = col[SBN];
+                    bf[j].z = col[2 * SBN];
+                    bf[j].w = col[3 * SBN];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][q], bf[j][q], acc[i][j], 0, 0, 0);
+        }
+
+        if (more) stash(buf ^ 1);
+        __syncthreads();
+    }
+
+    // store: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its block
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn0 + j * 32 + lr;
+            if (col < N) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + wm0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
+                    if (row < M) p.C[(size_t)row * p.ldc + col] = acc[i][j][r];
+                }
+            }
+        }
+    }
+}
+
+// ---- configurations ---------------------------------------------------------------------------
+
+struct Config {
+    const char* name;
+    int bm, bn, bk;
+    void (*kern[2][2])(GemmParams);   // [op][vec]
+    int threads;
+    // LDS bytes: two buffers of an A slab and a B slab (layouts as in the kernel)
+    size_t lds_bytes(int op) const
+    {
+        const size_t a = (size_t)bm * (bk + 4);
+        const size_t b = (op == OP_NT) ? (size_t)bn * (bk + 4) : (size_t)bk * (bn + 8);
+        return 2 * (a + b) * sizeof(float);
+    }
+};
+
+#define MTNN_CFG(BM, BN, BK, WMV, WNV)                                                        \
+    {                                                                                         \
+        #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV, BM, BN, BK,                                   \
+            {{gemm_kernel<BM, BN, BK, WMV, WNV, false, false>,                                \
+              gemm_kernel<BM, BN, BK, WMV, WNV, false, true>},                                \
+             {gemm_kernel<BM, BN, BK, WMV, WNV, true, false>,                                 \
+              gemm_kernel<BM, BN, BK, WMV, WNV, true, true>}},                                \
+            WMV * WNV * 64                                                                    \
+    }
+
+static const Config kConfigs[] = {
+    MTNN_CFG(256, 256, 16, 2, 4),   // 0: 8 waves, wave tile 128 x 64
+    MTNN_CFG(128, 128, 16, 2, 2),   // 1: 4 waves, wave tile 64 x 64
+    MTNN_CFG(64, 64, 16, 2, 2),     // 2: 4 waves, wave tile 32 x 32
+    MTNN_CFG(256, 128, 16, 4, 2),   // 3: 8 waves, wave tile 64 x 64
+    MTNN_CFG(128, 256, 16, 2, 4),   // 4: 8 waves, wave tile 64 x 64
+    MTNN_CFG(32, 256, 16, 1, 4),    // 5: 4 waves, wave tile 32 x 64 (small m)
+    MTNN_CFG(256, 32, 16, 4, 1),    // 6: 4 waves, wave tile 64 x 32 (small n)
+};
+constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
+
+int gemm_config_count() { return kNumConfigs; }
+const char* gemm_config_name(int cfg) { return (cfg >= 0 && cfg < kNumConfigs) ? kConfigs[cfg].name : nullptr; }
+
+int gemm_default_config(int /*op*/, int m, int n, int /*k*/)
+{
+    auto tiles = [&](int c) {
+        return (long long)((m + kConfigs[c].bm - 1) / kConfigs[c].bm) * ((n + kConfigs[c].bn - 1) / kConfigs[c].bn);
+    };
+    if (m <= 32) return 5;
+    if (n <= 32) return 6;
+    if (tiles(0) >= 256) return 0;
+    if (tiles(1) >= 128) return 1;
+    if (m <= 64 || n <= 64 || tiles(1) < 32) return 2;
+    return 1;
+}
+
+int launch_gemm(hipStream_t s, int op, int cfg, int m, int n, int k,
+                const float* A, long lda, const float* B, long ldb, float* C, long ldc)
+{
+    if (cfg < 0) cfg = gemm_default_config(op, m, n, k);
+    if (cfg >= kNumConfigs || (op != OP_NN && op != OP_NT)) return (int)hipErrorInvalidValue;
+    const Config& c = kConfigs[cfg];
+    GemmParams p;
+    p.A = A; p.B = B; p.C = C;
+    p.M = m; p.N = n; p.K = k;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.tiles_m = (m + c.bm - 1) / c.bm;
+    p.tiles_n = (n + c.bn - 1) / c.bn;
+    p.group_m = p.tiles_m < 8 ? p.tiles_m : 8;
+    p.num_xcd = 8;
+    const long long total = (long long)p.tiles_m * p.tiles_n;
+    if (total > 0x7fffffffLL) return (int)hipErrorInvalidValue;
+    const bool vec = (lda % 4 == 0) && (ldb % 4 == 0) &&
+                     ((reinterpret_cast<uintptr_t>(A) & 15) == 0) &&
+                     ((reinterpret_cast<uintptr_t>(B) & 15) == 0);
+    auto kern = c.kern[op][vec ? 1 : 0];
+    const size_t lds = c.lds_bytes(op);
+    if (lds > 64 * 1024) {
+        // opt in to the large LDS carve-out once per kernel and device
+        static bool raised[kNumConfigs][2][2][16] = {};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return (int)hipGetLastError();
+        if (dev < 0 || dev >= 16 || !raised[cfg][op][vec ? 1 : 0][dev]) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return (int)e;
+            if (dev >= 0 && dev < 16) raised[cfg][op][vec ? 1 : 0][dev] = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(c.threads), lds, s, p);
+    return (int)hipGetLastError();
+}
+
+}  // namespace mtnn

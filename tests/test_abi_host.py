@@ -1,0 +1,107 @@
+"""Host-side tests of the C ABI: the library loads without a GPU, exports every declared symbol,
+and rejects bad arguments before any device call (so fake pointers are safe here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1702_03192_amd import binding as mt
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    return mt.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mtnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mtnn_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound(L):
+    names = declared_symbols()
+    assert len(names) >= 20 and {"mtnn_nt", "mtnn_nn", "mtnn_transpose", "mtnn_select"} <= set(names)
+    for name in names:
+        assert hasattr(L, name), name
+        assert name in mt.SIGNATURES, f"{name} has no binding signature"
+    assert sorted(mt.SIGNATURES) == names
+
+
+def test_version_and_status_strings(L):
+    assert mt.mtnn_version() >= 100
+    seen = {mt.mtnn_status_string(s) for s in range(10)}
+    assert len(seen) == 10 and "ok" in seen
+    assert mt.mtnn_status_string(1234) == "unknown status"
+
+
+A, B, C, W = 0x100000, 0x200000, 0x300000, 0x400000   # fake device addresses, never dereferenced
+
+
+def test_gemm_validation_codes(L):
+    for fn in (L.mtnn_nt, L.mtnn_nn):
+        assert fn(None, -1, 4, 4, A, 4, B, 4, C, 4) == 1
+        assert fn(None, 4, 4, -2, A, 4, B, 4, C, 4) == 1
+        assert fn(None, 4, 4, 4, None, 4, B, 4, C, 4) == 2
+        assert fn(None, 4, 4, 4, A, 4, None, 4, C, 4) == 2
+        assert fn(None, 4, 4, 4, A, 4, B, 4, None, 4) == 2
+        assert fn(None, 4, 4, 8, A, 7, B, 8, C, 4) == 3      # lda < k
+        assert fn(None, 4, 6, 4, A, 4, B, 8, C, 5) == 3      # ldc < n
+        assert fn(None, 4, 4, 4, A, 4, B, 4, A + 16, 4) == 4  # C overlaps A
+        assert fn(None, 4, 4, 4, A, 4, B, 4, B, 4) == 4       # C is B
+        # empty problems succeed without touching anything (NULL pointers allowed)
+        assert fn(None, 0, 4, 4, None, 4, None, 4, None, 4) == 0
+        assert fn(None, 4, 0, 4, None, 4, None, 4, None, 4) == 0
+    assert L.mtnn_nt(None, 4, 6, 8, A, 8, B, 7, C, 6) == 3    # NT: ldb < k
+    assert L.mtnn_nn(None, 4, 6, 8, A, 8, B, 5, C, 6) == 3    # NN: ldb < n
+    assert L.mtnn_nn(None, 4, 6, 8, A, 8, B, 6, C, 6) != 3
+
+
+def test_ranges_use_leading_dimensions(L):
+    # C starts right after the last logical element of A (A is 4 x 4 with lda 4 -> 64 bytes)
+    assert L.mtnn_nt(None, 4, 4, 4, A, 4, B, 4, A + 60, 4) == 4
+    # with lda = 8 the last row of A ends at byte (3*8+4)*4 = 112
+    assert L.mtnn_nt(None, 4, 4, 4, A, 8, B, 4, A + 108, 4) == 4
+
+
+def test_gemm_ex_arguments(L):
+    n = L.mtnn_gemm_config_count()
+    assert n >= 3
+    assert L.mtnn_gemm_ex(None, 2, 0, 4, 4, 4, A, 4, B, 4, C, 4) == 8
+    assert L.mtnn_gemm_ex(None, 1, n, 4, 4, 4, A, 4, B, 4, C, 4) == 8
+    assert L.mtnn_gemm_ex(None, 1, -2, 4, 4, 4, A, 4, B, 4, C, 4) == 8
+    assert L.mtnn_gemm_ex(None, 1, 0, 4, 4, 4, A, 3, B, 4, C, 4) == 3
+    names = mt.gemm_configs()
+    assert len(set(names)) == n
+    for op in (0, 1):
+        for shape in [(256, 256, 256), (1024, 4096, 4096), (32, 8192, 8192), (8192, 32, 8192), (1000, 1000, 1000)]:
+            assert 0 <= mt.mtnn_gemm_default_config(op, *shape) < n
+    assert mt.mtnn_gemm_default_config(0, 0, 4, 4) == -1
+
+
+def test_transpose_validation_codes(L):
+    assert L.mtnn_transpose(None, -1, 4, A, 4, B, 4) == 1
+    assert L.mtnn_transpose(None, 4, 6, None, 6, B, 4) == 2
+    assert L.mtnn_transpose(None, 4, 6, A, 5, B, 4) == 3     # ldin < cols
+    assert L.mtnn_transpose(None, 4, 6, A, 6, B, 3) == 3     # ldout < rows
+    assert L.mtnn_transpose(None, 4, 6, A, 6, A, 4) == 4     # in place is not supported
+    assert L.mtnn_transpose(None, 0, 6, None, 6, None, 1) == 0
+    assert L.mtnn_transpose(None, 4, 0, None, 1, None, 4) == 0
+
+
+def test_tnn_workspace_rules(L):
+    assert mt.mtnn_tnn_workspace_bytes(0, 5) == 0 and mt.mtnn_tnn_workspace_bytes(5, -1) == 0
+    assert mt.mtnn_tnn_workspace_bytes(3, 5) == 256                 # 60 B rounded up
+    assert mt.mtnn_tnn_workspace_bytes(8192, 8192) == 8192 * 8192 * 4
+    assert mt.mtnn_tnn_workspace_bytes(65536, 65536) == 65536 * 65536 * 4   # no 32-bit overflow
+    need = mt.mtnn_tnn_workspace_bytes(6, 8)
+    assert L.mtnn_tnn(None, 4, 6, 8, A, 8, B, 8, C, 6, None, 0) == 5
+    assert L.mtnn_tnn(None, 4, 6, 8, A, 8, B, 8, C, 6, W, need - 1) == 5
+    assert L.mtnn_tnn(None, 4, 6, 8, A, 8, B, 8, C, 6, B + 8, need) == 4     # workspace overlaps B
+    assert L.mtnn_tnn(None, 4, 6, 8, A, 7, B, 8, C, 6, W, need) == 3         # argument checks come first
+    assert L.mtnn_tnn(None, 0, 6, 8, None, 8, None, 8, None, 6, None, 0) == 0
+    chosen = ctypes.c_int(7)
+    assert L.mtnn_auto(None, 4, 6, 8, A, 7, B, 8, C, 6, W, need, ctypes.byref(chosen)) == 3

@@ -1,0 +1,191 @@
+"""mtnn_nt / mtnn_nn / mtnn_tnn / mtnn_auto against the fp64 CPU oracle.
+
+Tolerance (the benchmark's definition): max relative error <= 1e-5 * sqrt(k), read both
+componentwise against S = |A| |B|^T and normwise against max |C| (see gpu_util.check_gemm).
+Integer-valued inputs must match bit for bit.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1702_03192_amd import binding as mt
+from paper_1702_03192_amd import inputs as I
+from gpu_util import Guarded, check_gemm, dev_matrix
+
+pytestmark = pytest.mark.gpu
+
+NCFG = 7
+
+
+def sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def run(op, cfg, A, B, lda=None, ldb=None, ldc=None, misalign=0):
+    """Run one GEMM through the C ABI; returns the fp32 host result (guard bands verified)."""
+    m, k = A.shape
+    n = B.shape[0] if op == mt.OP_NT else B.shape[1]
+    dA, dB = dev_matrix(A, lda, misalign=misalign), dev_matrix(B, ldb, misalign=2 * misalign)
+    out = Guarded(m, n, ldc, misalign=misalign)
+    mt.mtnn_gemm_ex(op, cfg, dA, dB, out.view)
+    sync()
+    got, intact = out.host()
+    assert intact, "GEMM wrote outside its logical output"
+    return got
+
+
+def reference(op, A, B, rows=None):
+    return (oracle.nt_ref if op == mt.OP_NT else oracle.nn_ref)(A, B, rows=rows, with_bound=True)
+
+
+def operands(op, m, n, k, seed, dist="uniform"):
+    A, B = I.nt_operands(m, n, k, seed, dist)
+    if op == mt.OP_NN:
+        B = np.ascontiguousarray(B.T)          # k x n
+    return A, B
+
+
+def test_config_count_matches():
+    assert len(mt.gemm_configs()) == NCFG
+
+
+@pytest.mark.parametrize("op", [mt.OP_NT, mt.OP_NN], ids=["NT", "NN"])
+@pytest.mark.parametrize("cfg", list(range(NCFG)))
+@pytest.mark.parametrize("m,n,k", [(300, 520, 77), (64, 64, 64), (33, 31, 5), (257, 255, 130)])
+def test_every_config_against_oracle(op, cfg, m, n, k):
+    A, B = operands(op, m, n, k, 100 + cfg)
+    got = run(op, cfg, A, B)
+    C, S = reference(op, A, B)
+    check_gemm(got, C, S, k, f"op{op} cfg{cfg} {m}x{n}x{k}")
+
+
+@pytest.mark.parametrize("op", [mt.OP_NT, mt.OP_NN], ids=["NT", "NN"])
+@pytest.mark.parametrize("cfg", list(range(NCFG)))
+def test_integer_inputs_are_bit_exact(op, cfg):
+    m, n, k = 290, 275, 203
+    A, B = operands(op, m, n, k, 200 + cfg, dist="int")
+    got = run(op, cfg, A, B)
+    C, _ = reference(op, A, B)
+    assert np.array_equal(got, C.astype(np.float32))
+
+
+@pytest.mark.parametrize("op", [mt.OP_NT, mt.OP_NN], ids=["NT", "NN"])
+@pytest.mark.parametrize("cfg", [-1, 0, 1, 5, 6])
+def test_odd_leading_dimensions_nan_padding_and_misaligned_bases(op, cfg):
+    m, n, k = 131, 262, 45
+    A, B = operands(op, m, n, k, 300)
+    C, S = reference(op, A, B)
+    bcols = B.shape[1]
+    for (lda, ldb, ldc, mis) in [(k + 3, bcols + 3, n + 3, 0), (k + 4, bcols + 8, n + 1, 0), (k, bcols, n, 1)]:
+        got = run(op, cfg, A, B, lda, ldb, ldc, misalign=mis)       # padding holds NaN
+        check_gemm(got, C, S, k, f"op{op} cfg{cfg} ld+({lda - k},{ldb - bcols},{ldc - n})")
+
+
+@pytest.mark.parametrize("op", [mt.OP_NT, mt.OP_NN], ids=["NT", "NN"])
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 7, 8, 9, 15, 16, 17, 31, 33])
+def test_k_tails(op, k):
+    m, n = 70, 90
+    A, B = operands(op, m, n, k, 400 + k, dist="normal")
+    got = run(op, -1, A, B)
+    C, S = reference(op, A, B)
+    check_gemm(got, C, S, k, f"op{op} k={k}")
+
+
+def test_degenerate_sizes():
+    import torch
+    out = Guarded(6, 9, 11)
+    a = torch.zeros((6, 1), device="cuda")
+    b = torch.zeros((9, 1), device="cuda")
+    L = mt.lib()
+    # k == 0: the empty sum
+    assert L.mtnn_nt(None, 6, 9, 0, None, 1, None, 1, out.view.data_ptr(), 11) == 0
+    sync()
+    got, intact = out.host()
+    assert intact and np.array_equal(got, np.zeros((6, 9), np.float32)) and not np.signbit(got).any()
+    out2 = Guarded(6, 9)
+    assert L.mtnn_nn(None, 0, 9, 4, a.data_ptr(), 4, b.data_ptr(), 9, out2.view.data_ptr(), 9) == 0
+    assert L.mtnn_nt(None, 6, 0, 4, a.data_ptr(), 4, b.data_ptr(), 4, out2.view.data_ptr(), 1) == 0
+    sync()
+    assert np.isnan(out2.host()[0]).all()          # untouched
+
+
+def test_identity_and_permutation_on_device():
+    A = I.uniform_pm1(500, 0, 100, 96)
+    eye = np.eye(96, dtype=np.float32)
+    assert np.array_equal(run(mt.OP_NT, -1, A, eye), A)
+    assert np.array_equal(run(mt.OP_NN, -1, A, eye), A)
+    perm = I.uniform_ints(501, 0, 96, 0, 10 ** 6).argsort()
+    assert np.array_equal(run(mt.OP_NT, -1, A, eye[perm]), A[:, perm])
+
+
+# ---- the benchmark configurations -----------------------------------------------------------
+
+def check_all_paths(m, n, k, seed, dist, rows=None):
+    """NT, TNN and auto on one shape against the oracle (all rows, or a row sample)."""
+    import torch
+    A, B = I.nt_operands(m, n, k, seed, dist)
+    C, S = oracle.nt_ref(A, B, rows=rows, with_bound=True)
+    dA, dB = dev_matrix(A), dev_matrix(B)
+    ws = torch.empty(mt.mtnn_tnn_workspace_bytes(n, k), dtype=torch.uint8, device="cuda")
+    pick = (lambda x: x) if rows is None else (lambda x: x[rows])
+    outs = {}
+    for name in ("nt", "tnn", "auto"):
+        out = Guarded(m, n)
+        if name == "nt":
+            mt.mtnn_nt(dA, dB, out.view)
+        elif name == "tnn":
+            mt.mtnn_tnn(dA, dB, out.view, ws)
+        else:
+            label = mt.mtnn_auto(dA, dB, out.view, ws)
+            assert label == mt.mtnn_select(m, n, k)
+        sync()
+        got, intact = out.host()
+        assert intact
+        check_gemm(pick(got), C, S, k, f"{name} {m}x{n}x{k}")
+        outs[name] = got
+    # rerun bit-identity (no atomics, fixed summation order)
+    again = Guarded(m, n)
+    mt.mtnn_nt(dA, dB, again.view)
+    sync()
+    assert again.host()[0].tobytes() == outs["nt"].tobytes()
+    # the transposed B in the workspace is bit-exact
+    bt = ws[: n * k * 4].view(torch.float32).view(k, n).cpu().numpy()
+    assert bt.tobytes() == np.ascontiguousarray(B.T).tobytes()
+    # the two alternatives agree with each other within twice the tolerance
+    d = np.abs(pick(outs["nt"]).astype(np.float64) - pick(outs["tnn"]).astype(np.float64))
+    assert (d / np.where(S > 0, S, 1)).max() <= 2e-5 * np.sqrt(k)
+
+
+def test_config1_single_nt_256():
+    check_all_paths(256, 256, 256, 1702, "uniform")
+
+
+@pytest.mark.parametrize("shape,seed", zip(I.CONFIG2["shapes"], I.CONFIG2["seeds"]))
+def test_config2_fc_layer_shapes(shape, seed):
+    check_all_paths(*shape, seed, "uniform")
+
+
+@pytest.mark.parametrize("shape,seed", zip(I.CONFIG4["shapes"], I.CONFIG4["seeds"]))
+def test_config4_skinny_and_irregular(shape, seed):
+    check_all_paths(*shape, seed, "normal")
+
+
+def test_auto_without_workspace_runs_nt():
+    A, B = I.nt_operands(128, 128, 128, 9)
+    dA, dB = dev_matrix(A), dev_matrix(B)
+    out = Guarded(128, 128)
+    assert mt.mtnn_auto(dA, dB, out.view, None) == 1
+    sync()
+    C, S = oracle.nt_ref(A, B, with_bound=True)
+    check_gemm(out.host()[0], C, S, 128)
+
+
+@pytest.mark.parametrize("m,n,k", [(8192, 8192, 8192), (64, 8192, 8192), (8192, 64, 64), (2048, 8192, 512)])
+def test_config3_sweep_corners_sampled_rows(m, n, k):
+    # the largest sweep shapes: the oracle checks the first/last rows of tile boundaries plus a
+    # pseudo-random sample of rows, every column
+    seed = 10000
+    rows = sorted(set([0, 1, m - 2, m - 1] + [r for r in (255, 256, 257, 4095, 4096) if r < m] +
+                      [int(x) for x in I.uniform_ints(seed, 9, 24, 0, m - 1)]))
+    check_all_paths(m, n, k, seed, "uniform", rows=np.array(rows))

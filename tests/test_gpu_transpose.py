@@ -1,0 +1,86 @@
+"""mtnn_transpose against the CPU oracle: bit-exact, including padding and guard bands."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1702_03192_amd import binding as mt
+from paper_1702_03192_amd import inputs as I
+from gpu_util import CANARY_BITS, Guarded, dev_matrix
+
+pytestmark = pytest.mark.gpu
+
+
+def run_transpose(x, ldin=None, ldout=None, misalign=0):
+    import torch
+    rows, cols = x.shape
+    d_in = dev_matrix(x, ldin, misalign=misalign)
+    out = Guarded(cols, rows, ldout, misalign=misalign)
+    mt.mtnn_transpose(d_in, out.view)
+    torch.cuda.synchronize()
+    got, intact = out.host()
+    assert intact, "transpose wrote outside its logical output"
+    return got
+
+
+@pytest.mark.parametrize("rows,cols", [(64, 64), (128, 192), (5, 7), (1, 300), (300, 1), (65, 63), (257, 130),
+                                       (1000, 10), (10, 1000), (4500, 1500), (4096, 1024), (1024, 4096)])
+def test_transpose_bit_exact(rows, cols):
+    x = I.uniform_pm1(6000, 0, rows, cols)
+    got = run_transpose(x)
+    want = np.ascontiguousarray(oracle.transpose_ref(x))
+    assert got.tobytes() == want.tobytes()
+
+
+def test_transpose_index_coded_4096():
+    x = I.index_coded(4096, 4096)
+    got = run_transpose(x)
+    assert got.tobytes() == np.ascontiguousarray(oracle.transpose_ref(x)).tobytes()
+
+
+@pytest.mark.parametrize("rows,cols,ldin,ldout,mis", [(130, 70, 73, 133, 0), (128, 128, 132, 136, 0),
+                                                      (128, 128, 128, 128, 1), (64, 200, 200, 67, 3),
+                                                      (200, 64, 64, 200, 2)])
+def test_transpose_leading_dims_padding_and_alignment(rows, cols, ldin, ldout, mis):
+    x = I.normal01(6001, 0, rows, cols)
+    got = run_transpose(x, ldin, ldout, misalign=mis)
+    assert got.tobytes() == np.ascontiguousarray(oracle.transpose_ref(x)).tobytes()
+
+
+def test_transpose_preserves_nan_payloads_and_signed_zero():
+    rng_bits = (I._bits(6002, 0, 96, 160) >> np.uint64(32)).astype(np.uint32)   # arbitrary 32-bit patterns
+    rng_bits[0, 0] = 0x7FC00001
+    rng_bits[1, 2] = 0x80000000
+    rng_bits[95, 159] = 0xFFC12345
+    x = rng_bits.view(np.float32)
+    got = run_transpose(x)
+    assert np.array_equal(got.view(np.uint32), rng_bits.T)
+
+
+def test_transpose_large_sampled_full_size():
+    # 8192 x 8192 (the largest B of the sweep): whole-matrix comparison against the oracle
+    x = I.uniform_pm1(6003, 0, 8192, 8192)
+    got = run_transpose(x)
+    want = np.ascontiguousarray(oracle.transpose_ref(x))
+    assert got.tobytes() == want.tobytes()
+
+
+def test_transpose_empty_is_a_noop():
+    import torch
+    out = Guarded(0, 5)
+    x = torch.empty((5, 0), dtype=torch.float32, device="cuda")
+    assert mt.lib().mtnn_transpose(None, 5, 0, x.data_ptr(), 1, out.view.data_ptr(), 5) == 0
+    assert mt.lib().mtnn_transpose(None, 0, 5, x.data_ptr(), 5, out.view.data_ptr(), 1) == 0
+    torch.cuda.synchronize()
+    assert out.host()[1]
+
+
+def test_transpose_involution_on_device():
+    import torch
+    x = I.normal01(6004, 0, 777, 333)
+    d = dev_matrix(x)
+    t1 = torch.empty((333, 777), dtype=torch.float32, device="cuda")
+    t2 = torch.empty((777, 333), dtype=torch.float32, device="cuda")
+    mt.mtnn_transpose(d, t1)
+    mt.mtnn_transpose(t1, t2)
+    torch.cuda.synchronize()
+    assert t2.cpu().numpy().tobytes() == x.tobytes()
