@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the NT-operation hot path on one MI355X.
+
+A "step" is one pass of the whole path over the FC-layer NT shapes
+(m, n, k) = (1024, 4096, 4096) and (4096, 4096, 1024), fp32, uniform[-1, 1) inputs from seeds:
+for each shape the direct NT kernel (mtnn_nt), TNN = transpose + NN (mtnn_tnn) and the
+selected path (mtnn_select + mtnn_auto).  Every call computes a full NT product, so the step's
+work is 3 x sum(2mnk) flop and `value` is that work over the step time, in GFLOP/s.  Inputs are
+resident in HBM before the timed region; nothing is allocated inside it.
+
+Prints ONE JSON line (see the keys below).  Per-kernel durations come from HIP events recorded,
+inside the timed region, on the stream the kernels are launched on.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak: 256 CUs x 2.4 GHz x 256 flop/clk/CU
+PEAK_HBM_GBS = 8000.0             # MI355X HBM3E peak
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (the NT path needs no exchange between "
+              "GPUs; see DESIGN.md, 'More than one GPU'); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_1702_03192_amd import binding as mt
+    from paper_1702_03192_amd import inputs, selector_data
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    mt.lib()
+    stream = torch.cuda.current_stream()
+
+    cfg = inputs.CONFIG2
+    work = []
+    for (m, n, k), seed in zip(cfg["shapes"], cfg["seeds"]):
+        A, B = inputs.nt_operands(m, n, k, seed, cfg["dist"])
+        w = {"shape": (m, n, k), "hA": A, "hB": B,
+             "A": torch.from_numpy(A).cuda(), "B": torch.from_numpy(B).cuda(),
+             "C_nt": torch.empty((m, n), dtype=torch.float32, device="cuda"),
+             "C_tnn": torch.empty((m, n), dtype=torch.float32, device="cuda"),
+             "C_auto": torch.empty((m, n), dtype=torch.float32, device="cuda"),
+             "ws": torch.empty(mt.mtnn_tnn_workspace_bytes(n, k), dtype=torch.uint8, device="cuda"),
+             "Bt": torch.empty((k, n), dtype=torch.float32, device="cuda"),
+             "flops": 2.0 * m * n * k}
+        work.append(w)
+    torch.cuda.synchronize()
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def step(record=None):
+        for wi, w in enumerate(work):
+            A, B = w["A"], w["B"]
+            if record is not None:
+                e = [ev() for _ in range(6)]
+                e[0].record(stream)
+                mt.mtnn_nt(A, B, w["C_nt"])                      # a1
+                e[1].record(stream)
+                mt.mtnn_transpose(B, w["Bt"])                    # a2 } a4, the same two launches
+                e[2].record(stream)
+                mt.mtnn_nn(A, w["Bt"], w["C_tnn"])               # a3 } mtnn_tnn makes
+                e[3].record(stream)
+                mt.mtnn_tnn(A, B, w["C_tnn"], w["ws"])           # a4 through its own entry point
+                e[4].record(stream)
+                w["label"] = mt.mtnn_auto(A, B, w["C_auto"], w["ws"])   # a5 + dispatch
+                e[5].record(stream)
+                record.append((wi, e))
+            else:
+                mt.mtnn_nt(A, B, w["C_nt"])
+                mt.mtnn_transpose(B, w["Bt"])
+                mt.mtnn_nn(A, w["Bt"], w["C_tnn"])
+                mt.mtnn_tnn(A, B, w["C_tnn"], w["ws"])
+                w["label"] = mt.mtnn_auto(A, B, w["C_auto"], w["ws"])
+
+    # NT products per shape and step: mtnn_nt, transpose+mtnn_nn, mtnn_tnn, mtnn_auto = 4
+    products_per_shape = 4
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    records = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(records)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    total_flops = products_per_shape * sum(w["flops"] for w in work)
+    value = total_flops / (ms_per_step * 1e-3) / 1e9
+
+    # per-kernel averages from the events of the timed region
+    acc = {}
+    for wi, e in records:
+        for name, a, b in (("nt", 0, 1), ("transpose", 1, 2), ("nn", 2, 3), ("tnn", 3, 4), ("auto", 4, 5)):
+            acc.setdefault((wi, name), []).append(e[a].elapsed_time(e[b]) * 1e-3)
+    per_shape = []
+    kernels = []
+    for wi, w in enumerate(work):
+        m, n, k = w["shape"]
+        t = {name: float(np.mean(acc[(wi, name)])) for name in ("nt", "transpose", "nn", "tnn", "auto")}
+        fl = w["flops"]
+        alg_bytes = 4.0 * (m * k + n * k + m * n)
+        roof_s = max(fl / (PEAK_FP32_MFMA_TFLOPS * 1e12), alg_bytes / (PEAK_HBM_GBS * 1e9))
+        per_shape.append({
+            "m": m, "n": n, "k": k,
+            "nt_gflops": fl / t["nt"] / 1e9, "nn_gflops": fl / t["nn"] / 1e9,
+            "tnn_gflops": fl / t["tnn"] / 1e9, "mtnn_gflops": fl / t["auto"] / 1e9,
+            "transpose_gbs": 8.0 * n * k / t["transpose"] / 1e9,
+            "label": int(w["label"]), "nt_roofline_frac": roof_s / t["nt"], "tnn_roofline_frac": roof_s / t["tnn"],
+            "nt_cfg": mt.gemm_configs()[mt.mtnn_gemm_default_config(mt.OP_NT, m, n, k)],
+            "nn_cfg": mt.gemm_configs()[mt.mtnn_gemm_default_config(mt.OP_NN, m, n, k)],
+        })
+        kernels.append(("gemm_kernel NT %s (m,n,k)=(%d,%d,%d)" % (per_shape[-1]["nt_cfg"], m, n, k), "mfma", fl, t["nt"]))
+        kernels.append(("gemm_kernel NN %s (m,n,k)=(%d,%d,%d)" % (per_shape[-1]["nn_cfg"], m, n, k), "mfma", fl, t["nn"]))
+        kernels.append(("transpose_kernel %dx%d" % (n, k), "hbm", 8.0 * n * k, t["transpose"]))
+
+    # the dominant kernel of the step = the launch with the largest average duration
+    name, bound, units, dur = max(kernels, key=lambda r: r[3])
+    if bound == "mfma":
+        roofline = {"bound": "mfma", "achieved": units / dur / 1e12, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s"}
+    else:
+        roofline = {"bound": "hbm", "achieved": units / dur / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline["traffic"] = selector_data.measured_traffic_bytes(name)   # from profiles/, or None
+    roofline["kernel"] = name
+    roofline["avg_launch_us"] = dur * 1e6
+    other = []
+    for kname, b, u, d in kernels:
+        peak = PEAK_FP32_MFMA_TFLOPS if b == "mfma" else PEAK_HBM_GBS
+        ach = u / d / (1e12 if b == "mfma" else 1e9)
+        other.append({"kernel": kname, "bound": b, "achieved": ach, "peak": peak, "frac": ach / peak,
+                      "avg_launch_us": d * 1e6})
+
+    # known-traffic copy (counter calibration point, and the practical HBM ceiling); outside the timed region
+    src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    mt.mtnn_copy_bytes(src, dst)
+    torch.cuda.synchronize()
+    c0, c1 = ev(), ev()
+    c0.record(stream)
+    for _ in range(5):
+        mt.mtnn_copy_bytes(src, dst)
+    c1.record(stream)
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2.0 * src.numel() / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
+
+    # selector: accuracy on the stored sweep (trained through the library) and per-call cost
+    selector = selector_data.selector_report()
+    n_calls = 200000
+    shapes = [(int(a), int(b), int(c)) for a, b, c in
+              inputs.uniform_ints(7, 0, 3 * 1024, 64, 8192).reshape(-1, 3)]
+    L = mt.lib()
+    ts = time.perf_counter()
+    for i in range(n_calls):
+        s = shapes[i & 1023]
+        L.mtnn_select(s[0], s[1], s[2])
+    te = time.perf_counter()
+    tb = time.perf_counter()
+    for i in range(n_calls):
+        s = shapes[i & 1023]
+        L.mtnn_version()
+    tf = time.perf_counter()
+    selector["select_ns_per_call_incl_ctypes"] = (te - ts) / n_calls * 1e9
+    selector["ctypes_call_overhead_ns"] = (tf - tb) / n_calls * 1e9
+
+    out = {
+        "metric": "NT GFLOP/s (2mnk/t, fp32)", "value": value, "unit": "GFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config 2: FC-layer NT shapes (1024,4096,4096) and (4096,4096,1024); per shape "
+                               "mtnn_nt, mtnn_transpose+mtnn_nn, mtnn_tnn, mtnn_select+mtnn_auto",
+                   "nt_products_per_step": products_per_shape * len(work)},
+        "roofline": roofline, "kernels": other, "per_shape": per_shape,
+        "copy_kernel_gbs": copy_gbs, "selector": selector,
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        tc0 = time.perf_counter()
+        macs = 0.0
+        for w in work:
+            oracle.nt_ref(w["hA"], w["hB"])
+            macs += w["flops"]
+        tc1 = time.perf_counter()
+        out["cpu_baseline"] = {"value": macs / (tc1 - tc0) / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": "oracle nt_ref (fp64 triple loop) once on each config-2 shape in full, "
+                                         "%.1f s wall" % (tc1 - tc0)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -145,6 +145,14 @@ MTNN_API int mtnn_gemm_default_config(int op, int m, int n, int k);
 MTNN_API int mtnn_gemm_ex(void *stream, int op, int cfg, int m, int n, int k,
                  const float *A, int lda, const float *B, int ldb, float *C, int ldc);
 
+/* ---- measurement aid ------------------------------------------------------------------------ */
+
+/* Plain device-to-device streaming copy of `bytes` (a multiple of 16, both pointers 16-byte
+ * aligned, ranges disjoint).  Not part of the paper's method: it is the known-traffic kernel
+ * that hardware byte counters are scaled against, and the practical ceiling a read-once /
+ * write-once kernel such as the transpose can be compared with. */
+MTNN_API int mtnn_copy_bytes(void *stream, size_t bytes, const void *in, void *out);
+
 /* ---- misc ---------------------------------------------------------------------------------- */
 
 MTNN_API const char *mtnn_status_string(int status);

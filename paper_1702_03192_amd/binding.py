@@ -53,6 +53,7 @@ SIGNATURES = {
     "mtnn_gemm_config_name": (ctypes.c_char_p, [_c_int]),
     "mtnn_gemm_default_config": (_c_int, [_c_int, _c_int, _c_int, _c_int]),
     "mtnn_gemm_ex": (_c_int, [_c_vp, _c_int, _c_int] + _GEMM[1:]),
+    "mtnn_copy_bytes": (_c_int, [_c_vp, _c_sz, _c_vp, _c_vp]),
     "mtnn_status_string": (ctypes.c_char_p, [_c_int]),
     "mtnn_last_hip_error": (_c_int, []),
     "mtnn_version": (_c_int, []),
@@ -260,6 +261,15 @@ def gemm_configs():
 
 def mtnn_gemm_default_config(op: int, m: int, n: int, k: int) -> int:
     return int(lib().mtnn_gemm_default_config(op, m, n, k))
+
+
+def mtnn_copy_bytes(src, dst, stream=None):
+    """Streaming device copy of a whole tensor (the known-traffic calibration kernel)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("size mismatch")
+    _check(lib().mtnn_copy_bytes(_stream(stream), nbytes, src.data_ptr(), dst.data_ptr()), "mtnn_copy_bytes")
+    return dst
 
 
 def mtnn_status_string(status: int) -> str:

@@ -119,6 +119,17 @@ int mtnn_transpose(void* stream, int rows, int cols, const float* in, int ldin, 
     return launch_status(err);
 }
 
+int mtnn_copy_bytes(void* stream, size_t bytes, const void* in, void* out)
+{
+    if (bytes == 0) return MTNN_OK;
+    if (!in || !out) return MTNN_ERR_NULL;
+    if ((bytes & 15) || (reinterpret_cast<uintptr_t>(in) & 15) || (reinterpret_cast<uintptr_t>(out) & 15))
+        return MTNN_ERR_ARG;
+    const uintptr_t a = reinterpret_cast<uintptr_t>(in), b = reinterpret_cast<uintptr_t>(out);
+    if (a < b + bytes && b < a + bytes) return MTNN_ERR_ALIAS;
+    return launch_status(mtnn::launch_copy(static_cast<hipStream_t>(stream), bytes / 16, in, out));
+}
+
 size_t mtnn_tnn_workspace_bytes(int n, int k)
 {
     if (n <= 0 || k <= 0) return 0;

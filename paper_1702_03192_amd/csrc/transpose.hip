@@ -118,4 +118,22 @@ int launch_fill_zero(hipStream_t s, int m, int n, float* C, long ldc)
     return (int)hipGetLastError();
 }
 
+// Plain streaming copy of 16-byte words: the reference point for HBM counters and for what a
+// pure read-once/write-once kernel reaches on this machine (not part of the paper's method).
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ in, u32x4* __restrict__ out, size_t nvec)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) out[i] = in[i];
+}
+
+int launch_copy(hipStream_t s, size_t nvec, const void* in, void* out)
+{
+    if (nvec == 0) return 0;
+    size_t blocks = (nvec + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                       static_cast<const u32x4*>(in), static_cast<u32x4*>(out), nvec);
+    return (int)hipGetLastError();
+}
+
 }  // namespace mtnn

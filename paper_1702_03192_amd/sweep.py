@@ -1,0 +1,149 @@
+"""Data collection and model fitting for the selector (Section IV-A / IV-B of the MTNN paper).
+
+  python -m paper_1702_03192_amd.sweep collect --out gpurun_out/sweep_gfx950.csv     (needs the GPU)
+  python -m paper_1702_03192_amd.sweep train   --csv <table> --model <file>           (host only)
+
+collect: for every (m, n, k) of the grid {64, ..., 8192}^3 it times the direct NT kernel and TNN
+(transpose + NN through mtnn_tnn, workspace allocated beforehand) and writes one CSV row per
+shape, appended as it goes, so an interrupted sweep resumes where it stopped.  The paper states
+no timing protocol; here each path gets 3 warm-up calls, then `samples` event-timed batches of
+back-to-back calls sized to last at least `min_batch_us`, and the table keeps median and
+minimum per call.  TNN is also timed with a per-call allocation of the B^T buffer through
+PyTorch's caching allocator, because the paper counts allocation and release in T_transpose
+(Section III); labels use the pre-allocated figure.
+
+train: evaluates the paper's protocol (80/20 split, 5-fold CV), fits the final model on all
+rows inside libmtnn and saves it.
+"""
+from __future__ import annotations
+
+import argparse
+import csv
+import json
+import os
+import statistics
+import sys
+
+FIELDS = ["m", "n", "k", "seed", "t_nt", "t_nt_min", "t_tnn", "t_tnn_min", "t_transpose", "t_nn",
+          "t_tnn_alloc", "nt_cfg", "nn_cfg"]
+
+
+def _time_batches(fn, stream, samples, min_batch_us):
+    import torch
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    fn()
+    b.record(stream)
+    torch.cuda.synchronize()
+    once = max(a.elapsed_time(b) * 1e3, 1.0)                 # us
+    reps = max(1, min(1000, int(min_batch_us / once + 0.999)))
+    per_call = []
+    for _ in range(samples):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(reps):
+            fn()
+        b.record(stream)
+        b.synchronize()
+        per_call.append(a.elapsed_time(b) * 1e-3 / reps)
+    return statistics.median(per_call), min(per_call)
+
+
+def collect(out_path, samples, min_batch_us, limit=None):
+    import torch
+    from . import binding as mt
+    from . import inputs
+    torch.cuda.set_device(0)
+    mt.lib()
+    stream = torch.cuda.current_stream()
+    done = set()
+    if os.path.exists(out_path):
+        with open(out_path, newline="") as f:
+            for rec in csv.DictReader(f):
+                done.add((int(rec["m"]), int(rec["n"]), int(rec["k"])))
+    new_file = not os.path.exists(out_path)
+    os.makedirs(os.path.dirname(os.path.abspath(out_path)), exist_ok=True)
+    shapes = inputs.sweep_shapes()
+    if limit:
+        shapes = shapes[:limit]
+    cfgs = mt.gemm_configs()
+    gen = torch.Generator(device="cuda")
+    with open(out_path, "a", newline="") as f:
+        wr = csv.DictWriter(f, fieldnames=FIELDS)
+        if new_file:
+            wr.writeheader()
+        for idx, (m, n, k, seed) in enumerate(shapes):
+            if (m, n, k) in done:
+                continue
+            gen.manual_seed(seed)                             # uniform[-1, 1) operands, seeded per shape
+            A = torch.rand((m, k), generator=gen, device="cuda") * 2 - 1
+            B = torch.rand((n, k), generator=gen, device="cuda") * 2 - 1
+            C = torch.empty((m, n), dtype=torch.float32, device="cuda")
+            Bt = torch.empty((k, n), dtype=torch.float32, device="cuda")
+            ws = torch.empty(mt.mtnn_tnn_workspace_bytes(n, k), dtype=torch.uint8, device="cuda")
+            nbytes = mt.mtnn_tnn_workspace_bytes(n, k)
+
+            def tnn_alloc():
+                w = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+                mt.mtnn_tnn(A, B, C, w)
+                del w
+
+            t_nt, t_nt_min = _time_batches(lambda: mt.mtnn_nt(A, B, C), stream, samples, min_batch_us)
+            t_tnn, t_tnn_min = _time_batches(lambda: mt.mtnn_tnn(A, B, C, ws), stream, samples, min_batch_us)
+            t_tr, _ = _time_batches(lambda: mt.mtnn_transpose(B, Bt), stream, samples, min_batch_us)
+            t_nn, _ = _time_batches(lambda: mt.mtnn_nn(A, Bt, C), stream, samples, min_batch_us)
+            t_al, _ = _time_batches(tnn_alloc, stream, max(5, samples // 4), min_batch_us)
+            wr.writerow({"m": m, "n": n, "k": k, "seed": seed, "t_nt": "%.9g" % t_nt, "t_nt_min": "%.9g" % t_nt_min,
+                         "t_tnn": "%.9g" % t_tnn, "t_tnn_min": "%.9g" % t_tnn_min, "t_transpose": "%.9g" % t_tr,
+                         "t_nn": "%.9g" % t_nn, "t_tnn_alloc": "%.9g" % t_al,
+                         "nt_cfg": cfgs[mt.mtnn_gemm_default_config(mt.OP_NT, m, n, k)],
+                         "nn_cfg": cfgs[mt.mtnn_gemm_default_config(mt.OP_NN, m, n, k)]})
+            f.flush()
+            if idx % 16 == 0:
+                print(f"[sweep] {idx + 1}/{len(shapes)} ({m},{n},{k}) nt {t_nt * 1e6:.1f} us tnn {t_tnn * 1e6:.1f} us",
+                      flush=True)
+            del A, B, C, Bt, ws
+    print(f"[sweep] wrote {out_path}", flush=True)
+
+
+def train(csv_path, model_path, report_path=None):
+    from . import binding as mt
+    from . import selector_data as sd
+    rows = sd.load_sweep(csv_path)
+    report = sd.evaluate(rows)                                   # leaves the all-rows model installed
+    mt.mtnn_save_model(model_path)
+    report["model"] = model_path
+    report["trees"] = mt.lib().mtnn_model_num_trees()
+    text = json.dumps(report, indent=1, sort_keys=True)
+    print(text)
+    if report_path:
+        with open(report_path, "w") as f:
+            f.write(text + "\n")
+    return report
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    c = sub.add_parser("collect")
+    c.add_argument("--out", required=True)
+    c.add_argument("--samples", type=int, default=20)
+    c.add_argument("--min-batch-us", type=float, default=200.0)
+    c.add_argument("--limit", type=int, default=None)
+    t = sub.add_parser("train")
+    t.add_argument("--csv", required=True)
+    t.add_argument("--model", required=True)
+    t.add_argument("--report", default=None)
+    args = ap.parse_args(argv)
+    if args.cmd == "collect":
+        collect(args.out, args.samples, args.min_batch_us, args.limit)
+    else:
+        train(args.csv, args.model, args.report)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
