@@ -145,6 +145,53 @@ MTNN_API int mtnn_gemm_default_config(int op, int m, int n, int k);
 MTNN_API int mtnn_gemm_ex(void *stream, int op, int cfg, int m, int n, int k,
                  const float *A, int lda, const float *B, int ldb, float *C, int ldc);
 
+/* ---- one training step of a fully connected net (Section V-C, Table IX sizes) ---------------- */
+
+/* The paper evaluates MTNN inside fully connected nets given only by their layer sizes: the forward
+ * product of a layer (mini-batch of activations, mb x l1, times the transpose of the l2 x l1
+ * weights) is an NT operation; the backward products are NN operations.  The rest of the step is
+ * this library's reading (the paper is silent): bias on every layer, ReLU after every hidden layer,
+ * softmax cross-entropy averaged over the mini-batch, plain SGD.  All buffers are device fp32
+ * (labels: device int32), dense (ld = width), owned by the caller. */
+typedef struct mtnn_fc_step_desc {
+    int num_layers;          /* L >= 1 weight layers                                              */
+    const int *dims;         /* HOST array of L+1 widths: input, hidden..., output                */
+    int batch;               /* mini-batch size                                                   */
+    const float *X;          /* batch x dims[0]                                                   */
+    const int *labels;       /* batch class indices in [0, dims[L])                               */
+    float *const *W;         /* HOST array of L device pointers, W[l]: dims[l+1] x dims[l]; updated in place */
+    float *const *b;         /* HOST array of L device pointers, b[l]: dims[l+1]; updated in place */
+    float *const *dW;        /* HOST array of L device pointers: gradients w.r.t. W[l] (outputs)  */
+    float *const *db;        /* HOST array of L device pointers: gradients w.r.t. b[l] (outputs)  */
+    float *logits;           /* optional output, batch x dims[L] (may be NULL)                    */
+    float *loss;             /* output, 1 float: mean cross-entropy                               */
+    void *workspace;         /* at least mtnn_fc_workspace_bytes(...)                             */
+    size_t workspace_bytes;
+    float lr;                /* SGD step                                                          */
+    int forward_mode;        /* 0 = mtnn_auto (Algorithm 2), +1 = always NT, -1 = always TNN      */
+} mtnn_fc_step_desc;
+
+MTNN_API size_t mtnn_fc_workspace_bytes(int num_layers, const int *dims, int batch);
+/* forward (NT per layer via the selected path) -> loss -> backward (dW = transpose + NN, dX = NN)
+ * -> SGD update, all enqueued on `stream`. */
+MTNN_API int mtnn_fc_train_step(void *stream, const mtnn_fc_step_desc *desc);
+
+/* The elementwise / reduction steps of the training step, exported for tests:
+ * Z[i][j] += b[j] (then ReLU if relu != 0), in place, Z batch x width dense. */
+MTNN_API int mtnn_fc_bias_act(void *stream, int batch, int width, float *Z, const float *b, int relu);
+/* dZ = (softmax(logits) - onehot(labels)) / batch; row_loss[i] = -log softmax(logits_i)[label_i];
+ * mean_loss[0] = mean of row_loss. */
+MTNN_API int mtnn_fc_softmax_xent(void *stream, int batch, int classes, const float *logits, const int *labels,
+                         float *dZ, float *row_loss, float *mean_loss);
+/* dH[e] = H[e] > 0 ? dH[e] : 0 over `count` elements (H is the ReLU output). */
+MTNN_API int mtnn_fc_relu_backward(void *stream, long long count, float *dH, const float *H);
+/* db[j] = sum_i dZ[i][j], dZ batch x width dense. */
+MTNN_API int mtnn_fc_bias_grad(void *stream, int batch, int width, const float *dZ, float *db);
+/* P[e] -= lr * G[e] over `count` elements. */
+MTNN_API int mtnn_fc_sgd(void *stream, long long count, float *P, const float *G, float lr);
+/* dense device-to-device copy of a rows x cols matrix */
+MTNN_API int mtnn_copy_rows(void *stream, int rows, int cols, const float *in, float *out);
+
 /* ---- measurement aid ------------------------------------------------------------------------ */
 
 /* Plain device-to-device streaming copy of `bytes` (a multiple of 16, both pointers 16-byte

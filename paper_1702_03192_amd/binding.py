@@ -26,6 +26,18 @@ _c_dbl = ctypes.c_double
 _p_int = ctypes.POINTER(ctypes.c_int)
 _p_dbl = ctypes.POINTER(ctypes.c_double)
 
+_c_ll = ctypes.c_longlong
+_c_flt = ctypes.c_float
+
+
+class FcStepDesc(ctypes.Structure):
+    """Mirror of mtnn_fc_step_desc."""
+    _fields_ = [("num_layers", _c_int), ("dims", _p_int), ("batch", _c_int), ("X", _c_vp), ("labels", _c_vp),
+                ("W", ctypes.POINTER(_c_vp)), ("b", ctypes.POINTER(_c_vp)), ("dW", ctypes.POINTER(_c_vp)),
+                ("db", ctypes.POINTER(_c_vp)), ("logits", _c_vp), ("loss", _c_vp), ("workspace", _c_vp),
+                ("workspace_bytes", _c_sz), ("lr", _c_flt), ("forward_mode", _c_int)]
+
+
 _GEMM = [_c_vp, _c_int, _c_int, _c_int, _c_vp, _c_int, _c_vp, _c_int, _c_vp, _c_int]
 
 # name -> (restype, argtypes): every symbol include/mtnn.h declares
@@ -53,6 +65,14 @@ SIGNATURES = {
     "mtnn_gemm_config_name": (ctypes.c_char_p, [_c_int]),
     "mtnn_gemm_default_config": (_c_int, [_c_int, _c_int, _c_int, _c_int]),
     "mtnn_gemm_ex": (_c_int, [_c_vp, _c_int, _c_int] + _GEMM[1:]),
+    "mtnn_fc_workspace_bytes": (_c_sz, [_c_int, _p_int, _c_int]),
+    "mtnn_fc_train_step": (_c_int, [_c_vp, ctypes.POINTER(FcStepDesc)]),
+    "mtnn_fc_bias_act": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp, _c_int]),
+    "mtnn_fc_softmax_xent": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp, _c_vp, _c_vp, _c_vp]),
+    "mtnn_fc_relu_backward": (_c_int, [_c_vp, _c_ll, _c_vp, _c_vp]),
+    "mtnn_fc_bias_grad": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp]),
+    "mtnn_fc_sgd": (_c_int, [_c_vp, _c_ll, _c_vp, _c_vp, _c_flt]),
+    "mtnn_copy_rows": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp]),
     "mtnn_copy_bytes": (_c_int, [_c_vp, _c_sz, _c_vp, _c_vp]),
     "mtnn_status_string": (ctypes.c_char_p, [_c_int]),
     "mtnn_last_hip_error": (_c_int, []),
@@ -261,6 +281,57 @@ def gemm_configs():
 
 def mtnn_gemm_default_config(op: int, m: int, n: int, k: int) -> int:
     return int(lib().mtnn_gemm_default_config(op, m, n, k))
+
+
+# ---- fully connected training step -------------------------------------------------------
+
+def mtnn_fc_workspace_bytes(dims, batch: int) -> int:
+    arr = (ctypes.c_int * len(dims))(*dims)
+    return int(lib().mtnn_fc_workspace_bytes(len(dims) - 1, arr, batch))
+
+
+def make_fc_desc(dims, batch, X, labels, W, b, dW, db, loss, workspace, lr, forward_mode=0, logits=None):
+    """Fill a mtnn_fc_step_desc from device tensors.  Returns (desc, keepalive)."""
+    L = len(dims) - 1
+    dims_arr = (ctypes.c_int * (L + 1))(*dims)
+
+    def ptrs(ts):
+        return (_c_vp * L)(*[t.data_ptr() for t in ts])
+
+    pw, pb, pdw, pdb = ptrs(W), ptrs(b), ptrs(dW), ptrs(db)
+    desc = FcStepDesc(L, dims_arr, batch, X.data_ptr(), labels.data_ptr(), pw, pb, pdw, pdb,
+                      logits.data_ptr() if logits is not None else None, loss.data_ptr(),
+                      workspace.data_ptr(), workspace.numel() * workspace.element_size(), lr, forward_mode)
+    return desc, (dims_arr, pw, pb, pdw, pdb)
+
+
+def mtnn_fc_train_step(desc, stream=None) -> None:
+    _check(lib().mtnn_fc_train_step(_stream(stream), ctypes.byref(desc)), "mtnn_fc_train_step")
+
+
+def mtnn_fc_bias_act(Z, b, relu: bool, stream=None):
+    _check(lib().mtnn_fc_bias_act(_stream(stream), Z.shape[0], Z.shape[1], Z.data_ptr(), b.data_ptr(), int(relu)),
+           "mtnn_fc_bias_act")
+
+
+def mtnn_fc_softmax_xent(logits, labels, dZ, row_loss, mean_loss, stream=None):
+    _check(lib().mtnn_fc_softmax_xent(_stream(stream), logits.shape[0], logits.shape[1], logits.data_ptr(),
+                                      labels.data_ptr(), dZ.data_ptr(), row_loss.data_ptr(), mean_loss.data_ptr()),
+           "mtnn_fc_softmax_xent")
+
+
+def mtnn_fc_relu_backward(dH, H, stream=None):
+    _check(lib().mtnn_fc_relu_backward(_stream(stream), dH.numel(), dH.data_ptr(), H.data_ptr()),
+           "mtnn_fc_relu_backward")
+
+
+def mtnn_fc_bias_grad(dZ, db, stream=None):
+    _check(lib().mtnn_fc_bias_grad(_stream(stream), dZ.shape[0], dZ.shape[1], dZ.data_ptr(), db.data_ptr()),
+           "mtnn_fc_bias_grad")
+
+
+def mtnn_fc_sgd(P, G, lr: float, stream=None):
+    _check(lib().mtnn_fc_sgd(_stream(stream), P.numel(), P.data_ptr(), G.data_ptr(), lr), "mtnn_fc_sgd")
 
 
 def mtnn_copy_bytes(src, dst, stream=None):

@@ -1,0 +1,283 @@
+// One training step of a fully connected net built on the NT / NN / transpose operations
+// (the setting of Section V-C of the MTNN paper: layer sizes as in Table IX, where the forward
+// product of a layer -- activations (mb x l1) times the transpose of the weights (l2 x l1) -- is
+// the NT operation MTNN accelerates and the backward products are plain NN operations).
+//
+// The paper fixes only the layer sizes.  The rest is this library's reading: a bias on every
+// layer, ReLU after every hidden layer, softmax cross-entropy averaged over the mini-batch, plain
+// SGD.  Every matrix product goes through mtnn_nt / mtnn_tnn / mtnn_auto (forward) and
+// mtnn_nn / mtnn_transpose (backward); the kernels here are the small elementwise and reduction
+// steps around them.  All reductions run in a fixed order: results are bit-reproducible.
+#include "../../include/mtnn.h"
+#include "mtnn_internal.h"
+
+#include <math.h>
+
+namespace mtnn {
+
+// Z[i][j] += b[j]; if relu, clamp at zero.  In place on the GEMM output (batch x width, ld = width).
+__global__ __launch_bounds__(256) void bias_act_kernel(float* __restrict__ Z, const float* __restrict__ b,
+                                                       long long total, int width, int relu)
+{
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long long)gridDim.x * blockDim.x) {
+        float v = Z[e] + b[e % width];
+        if (relu) v = v > 0.f ? v : 0.f;
+        Z[e] = v;
+    }
+}
+
+// One wave per row: stable softmax, loss_i = -log p[label_i], dZ = (p - onehot) / batch.
+__global__ __launch_bounds__(64) void softmax_xent_kernel(const float* __restrict__ logits, const int* __restrict__ labels,
+                                                          float* __restrict__ dZ, float* __restrict__ row_loss,
+                                                          int batch, int classes)
+{
+    const int row = blockIdx.x;
+    const int lane = threadIdx.x;
+    const float* z = logits + (size_t)row * classes;
+    float mx = -INFINITY;
+    for (int j = lane; j < classes; j += 64) mx = fmaxf(mx, z[j]);
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    float sum = 0.f;
+    for (int j = lane; j < classes; j += 64) sum += expf(z[j] - mx);
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    const float lse = logf(sum);
+    const int lab = labels[row];
+    const float inv_b = 1.0f / (float)batch;
+    for (int j = lane; j < classes; j += 64) {
+        const float p = expf(z[j] - mx - lse);
+        dZ[(size_t)row * classes + j] = (p - (j == lab ? 1.f : 0.f)) * inv_b;
+    }
+    // a label outside [0, classes) has no log-probability: its row reports NaN instead of reading out of bounds
+    if (lane == 0) row_loss[row] = (lab >= 0 && lab < classes) ? -(z[lab] - mx - lse) : NAN;
+}
+
+// mean of `n` values with one workgroup and a fixed tree: out[0] = sum(v) / n
+__global__ __launch_bounds__(256) void mean_kernel(const float* __restrict__ v, int n, float* __restrict__ out)
+{
+    __shared__ float part[256];
+    float s = 0.f;
+    for (int i = threadIdx.x; i < n; i += 256) s += v[i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[0] = part[0] / (float)n;
+}
+
+// dZ = dH where H > 0 else 0 (H is the ReLU output; H > 0 exactly where the pre-activation was > 0)
+__global__ __launch_bounds__(256) void relu_backward_kernel(float* __restrict__ dH, const float* __restrict__ H, long long total)
+{
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long long)gridDim.x * blockDim.x)
+        dH[e] = H[e] > 0.f ? dH[e] : 0.f;
+}
+
+// db[j] = sum_i dZ[i][j]: 64 columns per workgroup, 4 row groups of 64 lanes, rows in a fixed order
+__global__ __launch_bounds__(256) void bias_grad_kernel(const float* __restrict__ dZ, float* __restrict__ db, int batch, int width)
+{
+    __shared__ float part[4][64];
+    const int col = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int grp = threadIdx.x >> 6;
+    float s = 0.f;
+    if (col < width)
+        for (int i = grp; i < batch; i += 4) s += dZ[(size_t)i * width + col];
+    part[grp][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (grp == 0 && col < width) db[col] = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+}
+
+// P -= lr * G
+__global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ P, const float* __restrict__ G, long long total, float lr)
+{
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long long)gridDim.x * blockDim.x)
+        P[e] = P[e] - lr * G[e];
+}
+
+static unsigned blocks_for(long long total)
+{
+    long long b = (total + 255) / 256;
+    return (unsigned)(b > 8192 ? 8192 : (b < 1 ? 1 : b));
+}
+
+}  // namespace mtnn
+
+namespace {
+int status_of(hipError_t e) { return e == hipSuccess ? MTNN_OK : MTNN_ERR_LAUNCH; }
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+}  // namespace
+
+extern "C" {
+
+int mtnn_fc_bias_act(void* stream, int batch, int width, float* Z, const float* b, int relu)
+{
+    if (batch < 0 || width < 0) return MTNN_ERR_DIM;
+    if (batch == 0 || width == 0) return MTNN_OK;
+    if (!Z || !b) return MTNN_ERR_NULL;
+    const long long total = (long long)batch * width;
+    hipLaunchKernelGGL(mtnn::bias_act_kernel, dim3(mtnn::blocks_for(total)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       Z, b, total, width, relu);
+    return status_of(hipGetLastError());
+}
+
+int mtnn_fc_softmax_xent(void* stream, int batch, int classes, const float* logits, const int* labels,
+                         float* dZ, float* row_loss, float* mean_loss)
+{
+    if (batch <= 0 || classes <= 0) return MTNN_ERR_DIM;
+    if (!logits || !labels || !dZ || !row_loss || !mean_loss) return MTNN_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(mtnn::softmax_xent_kernel, dim3(batch), dim3(64), 0, s, logits, labels, dZ, row_loss, batch, classes);
+    hipLaunchKernelGGL(mtnn::mean_kernel, dim3(1), dim3(256), 0, s, row_loss, batch, mean_loss);
+    return status_of(hipGetLastError());
+}
+
+int mtnn_fc_relu_backward(void* stream, long long count, float* dH, const float* H)
+{
+    if (count < 0) return MTNN_ERR_DIM;
+    if (count == 0) return MTNN_OK;
+    if (!dH || !H) return MTNN_ERR_NULL;
+    hipLaunchKernelGGL(mtnn::relu_backward_kernel, dim3(mtnn::blocks_for(count)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), dH, H, count);
+    return status_of(hipGetLastError());
+}
+
+int mtnn_fc_bias_grad(void* stream, int batch, int width, const float* dZ, float* db)
+{
+    if (batch <= 0 || width <= 0) return MTNN_ERR_DIM;
+    if (!dZ || !db) return MTNN_ERR_NULL;
+    hipLaunchKernelGGL(mtnn::bias_grad_kernel, dim3((width + 63) / 64), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       dZ, db, batch, width);
+    return status_of(hipGetLastError());
+}
+
+int mtnn_fc_sgd(void* stream, long long count, float* P, const float* G, float lr)
+{
+    if (count < 0) return MTNN_ERR_DIM;
+    if (count == 0) return MTNN_OK;
+    if (!P || !G) return MTNN_ERR_NULL;
+    hipLaunchKernelGGL(mtnn::sgd_kernel, dim3(mtnn::blocks_for(count)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       P, G, count, lr);
+    return status_of(hipGetLastError());
+}
+
+// workspace layout (all blocks 256-byte aligned):
+//   H_1 .. H_L        batch x dims[l]            activations (H_L = logits)
+//   dA, dB            batch x max_width each     ping-pong gradients w.r.t. layer outputs / inputs
+//   dZt               max_width x batch          transposed gradient for the dW product
+//   Bt                max(out x in) floats       B^T buffer for the TNN forward path
+//   row_loss          batch
+size_t mtnn_fc_workspace_bytes(int num_layers, const int* dims, int batch)
+{
+    if (num_layers <= 0 || !dims || batch <= 0) return 0;
+    size_t total = 0, max_w = 0, max_wt = 0;
+    for (int l = 0; l <= num_layers; ++l) {
+        if (dims[l] <= 0) return 0;
+        if ((size_t)dims[l] > max_w) max_w = (size_t)dims[l];
+    }
+    for (int l = 1; l <= num_layers; ++l) {
+        total += align256((size_t)batch * dims[l] * 4);
+        const size_t wt = (size_t)dims[l] * dims[l - 1];
+        if (wt > max_wt) max_wt = wt;
+    }
+    total += 2 * align256((size_t)batch * max_w * 4);
+    total += align256(max_w * (size_t)batch * 4);
+    total += align256(max_wt * 4);
+    total += align256((size_t)batch * 4);
+    return total;
+}
+
+int mtnn_fc_train_step(void* stream, const mtnn_fc_step_desc* d)
+{
+    if (!d) return MTNN_ERR_NULL;
+    const int L = d->num_layers;
+    if (L <= 0 || L > 64 || d->batch <= 0 || !d->dims) return MTNN_ERR_DIM;
+    for (int l = 0; l <= L; ++l)
+        if (d->dims[l] <= 0) return MTNN_ERR_DIM;
+    if (!d->X || !d->labels || !d->W || !d->b || !d->dW || !d->db || !d->loss || !d->workspace) return MTNN_ERR_NULL;
+    for (int l = 0; l < L; ++l)
+        if (!d->W[l] || !d->b[l] || !d->dW[l] || !d->db[l]) return MTNN_ERR_NULL;
+    if (d->forward_mode != 0 && d->forward_mode != 1 && d->forward_mode != -1) return MTNN_ERR_ARG;
+    if (d->workspace_bytes < mtnn_fc_workspace_bytes(L, d->dims, d->batch)) return MTNN_ERR_WORKSPACE;
+
+    const int batch = d->batch;
+    const int* dims = d->dims;
+    size_t max_w = 0, max_wt = 0;
+    for (int l = 0; l <= L; ++l) if ((size_t)dims[l] > max_w) max_w = (size_t)dims[l];
+    for (int l = 1; l <= L; ++l) {
+        const size_t wt = (size_t)dims[l] * dims[l - 1];
+        if (wt > max_wt) max_wt = wt;
+    }
+    char* base = static_cast<char*>(d->workspace);
+    size_t off = 0;
+    auto carve = [&](size_t bytes) { char* p = base + off; off += align256(bytes); return reinterpret_cast<float*>(p); };
+    float* H[65];
+    H[0] = const_cast<float*>(d->X);
+    for (int l = 1; l <= L; ++l) H[l] = carve((size_t)batch * dims[l] * 4);
+    float* dA = carve((size_t)batch * max_w * 4);
+    float* dB = carve((size_t)batch * max_w * 4);
+    float* dZt = carve(max_w * (size_t)batch * 4);
+    float* Bt = carve(max_wt * 4);
+    float* row_loss = carve((size_t)batch * 4);
+    const size_t bt_bytes = align256(max_wt * 4);
+
+    int st;
+    // forward: H_l = act(H_{l-1} x W_l^T + b_l) -- the NT operation of each layer
+    for (int l = 0; l < L; ++l) {
+        const int in = dims[l], out = dims[l + 1];
+        if (d->forward_mode == 1)
+            st = mtnn_nt(stream, batch, out, in, H[l], in, d->W[l], in, H[l + 1], out);
+        else if (d->forward_mode == -1)
+            st = mtnn_tnn(stream, batch, out, in, H[l], in, d->W[l], in, H[l + 1], out, Bt, bt_bytes);
+        else
+            st = mtnn_auto(stream, batch, out, in, H[l], in, d->W[l], in, H[l + 1], out, Bt, bt_bytes, nullptr);
+        if (st != MTNN_OK) return st;
+        st = mtnn_fc_bias_act(stream, batch, out, H[l + 1], d->b[l], l < L - 1 ? 1 : 0);
+        if (st != MTNN_OK) return st;
+    }
+    if (d->logits) {
+        st = mtnn_copy_rows(stream, batch, dims[L], H[L], d->logits);
+        if (st != MTNN_OK) return st;
+    }
+    // loss and gradient w.r.t. the logits
+    float* dZ = dA;
+    float* dNext = dB;
+    st = mtnn_fc_softmax_xent(stream, batch, dims[L], H[L], d->labels, dZ, row_loss, d->loss);
+    if (st != MTNN_OK) return st;
+    // backward, last layer first
+    for (int l = L - 1; l >= 0; --l) {
+        const int in = dims[l], out = dims[l + 1];
+        st = mtnn_fc_bias_grad(stream, batch, out, dZ, d->db[l]);
+        if (st != MTNN_OK) return st;
+        // dW_l = dZ^T x H_l : transpose dZ (batch x out -> out x batch), then an NN product
+        st = mtnn_transpose(stream, batch, out, dZ, out, dZt, batch);
+        if (st != MTNN_OK) return st;
+        st = mtnn_nn(stream, out, in, batch, dZt, batch, H[l], in, d->dW[l], in);
+        if (st != MTNN_OK) return st;
+        if (l > 0) {
+            // dH_l = dZ x W_l (NN, with the weights before their update), then through the ReLU
+            st = mtnn_nn(stream, batch, in, out, dZ, out, d->W[l], in, dNext, in);
+            if (st != MTNN_OK) return st;
+            st = mtnn_fc_relu_backward(stream, (long long)batch * in, dNext, H[l]);
+            if (st != MTNN_OK) return st;
+        }
+        st = mtnn_fc_sgd(stream, (long long)out * in, d->W[l], d->dW[l], d->lr);
+        if (st != MTNN_OK) return st;
+        st = mtnn_fc_sgd(stream, out, d->b[l], d->db[l], d->lr);
+        if (st != MTNN_OK) return st;
+        float* t = dZ; dZ = dNext; dNext = t;
+    }
+    return MTNN_OK;
+}
+
+int mtnn_copy_rows(void* stream, int rows, int cols, const float* in, float* out)
+{
+    if (rows < 0 || cols < 0) return MTNN_ERR_DIM;
+    if (rows == 0 || cols == 0) return MTNN_OK;
+    if (!in || !out) return MTNN_ERR_NULL;
+    return status_of(hipMemcpyAsync(out, in, (size_t)rows * cols * 4, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -105,3 +105,28 @@ def test_tnn_workspace_rules(L):
     assert L.mtnn_tnn(None, 0, 6, 8, None, 8, None, 8, None, 6, None, 0) == 0
     chosen = ctypes.c_int(7)
     assert L.mtnn_auto(None, 4, 6, 8, A, 7, B, 8, C, 6, W, need, ctypes.byref(chosen)) == 3
+
+
+def test_fc_step_validation(L):
+    import ctypes
+    dims = (ctypes.c_int * 3)(8, 16, 4)
+    assert L.mtnn_fc_workspace_bytes(0, dims, 4) == 0
+    assert L.mtnn_fc_workspace_bytes(2, dims, 0) == 0
+    need = L.mtnn_fc_workspace_bytes(2, dims, 4)
+    # H1 4x16, H2 4x4, dA, dB 4x16 each, dZt 16x4, Bt 16x8, row_loss 4 -> all rounded to 256 B
+    assert need == 256 + 256 + 2 * 256 + 256 + 512 + 256
+    assert L.mtnn_fc_train_step(None, None) == 2
+    ptrs = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    d = mt.FcStepDesc(2, dims, 4, 0x100, 0x200, ptrs, ptrs, ptrs, ptrs, None, 0x300, 0x400, need - 1, 0.01, 0)
+    assert L.mtnn_fc_train_step(None, ctypes.byref(d)) == 5            # workspace too small
+    d.workspace_bytes = need
+    d.forward_mode = 3
+    assert L.mtnn_fc_train_step(None, ctypes.byref(d)) == 8
+    d.forward_mode = 0
+    d.X = None
+    assert L.mtnn_fc_train_step(None, ctypes.byref(d)) == 2
+    d.X = 0x100
+    d.batch = 0
+    assert L.mtnn_fc_train_step(None, ctypes.byref(d)) == 1
+    assert L.mtnn_fc_sgd(None, -1, 0x10, 0x20, 0.1) == 1
+    assert L.mtnn_fc_bias_act(None, 4, 4, None, 0x20, 1) == 2

@@ -1,0 +1,155 @@
+"""One training step of a fully connected net (config 5 and a small net) against the fp64 oracle."""
+import numpy as np
+import pytest
+
+from oracle import fc as ofc
+from paper_1702_03192_amd import binding as mt
+from paper_1702_03192_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+def make_net(dims, batch, seed):
+    X = I.normal01(seed, 0, batch, dims[0])
+    labels = I.uniform_ints(seed, 1, batch, 0, dims[-1] - 1).astype(np.int32)
+    W = [I.xavier_uniform(seed + 1 + l, 2, dims[l + 1], dims[l]) for l in range(len(dims) - 1)]
+    b = [np.zeros(dims[l + 1], np.float32) for l in range(len(dims) - 1)]
+    return X, labels, W, b
+
+
+def settle_relu_decisions(X, W, b, tau=2e-4):
+    """Nudge hidden-layer biases (by multiples of tau, in fp32) until every pre-activation, evaluated
+    in float64 on the host, is at least tau away from zero.  The ReLU decision z > 0 is then the same
+    in the kernels' fp32 as in the oracle's fp64 (the fp32 forward error is ~1e-5 at these sizes), so
+    both sides take every decision identically and the comparison measures rounding, not flipped
+    units.  Uses only host arithmetic on the seeded inputs."""
+    H = X.astype(np.float64)
+    for l in range(len(W) - 1):
+        zw = H @ W[l].astype(np.float64).T
+        for _ in range(3):
+            z = zw + b[l].astype(np.float64)
+            bad = np.where(np.abs(z).min(axis=0) < tau)[0]
+            if bad.size == 0:
+                break
+            for j in bad:
+                col = z[:, j]
+                for c in range(1, 400):
+                    done = False
+                    for sign in (1.0, -1.0):
+                        d = sign * c * tau
+                        if np.abs(col + d).min() >= 1.5 * tau:
+                            b[l][j] = np.float32(b[l][j] + d)
+                            done = True
+                            break
+                    if done:
+                        break
+        z = zw + b[l].astype(np.float64)
+        assert np.abs(z).min() >= tau, "could not separate the pre-activations from zero"
+        H = np.maximum(z, 0.0)
+    return b
+
+
+def run_step(dims, batch, X, labels, W, b, lr, mode):
+    import torch
+    L = len(dims) - 1
+    dX = torch.from_numpy(X).cuda()
+    dl = torch.from_numpy(labels).cuda()
+    dW_ = [torch.from_numpy(w.copy()).cuda() for w in W]
+    db_ = [torch.from_numpy(v.copy()).cuda() for v in b]
+    gW = [torch.full_like(w, float("nan")) for w in dW_]
+    gb = [torch.full_like(v, float("nan")) for v in db_]
+    loss = torch.full((1,), float("nan"), device="cuda")
+    logits = torch.empty((batch, dims[-1]), device="cuda")
+    ws = torch.empty(mt.mtnn_fc_workspace_bytes(dims, batch), dtype=torch.uint8, device="cuda")
+    desc, keep = mt.make_fc_desc(dims, batch, dX, dl, dW_, db_, gW, gb, loss, ws, lr, mode, logits)
+    mt.mtnn_fc_train_step(desc)
+    torch.cuda.synchronize()
+    return {"loss": float(loss.item()), "logits": logits.cpu().numpy(),
+            "dW": [g.cpu().numpy() for g in gW], "db": [g.cpu().numpy() for g in gb],
+            "W_new": [w.cpu().numpy() for w in dW_], "b_new": [v.cpu().numpy() for v in db_]}
+
+
+def nrm_err(got, want):
+    want = np.asarray(want, dtype=np.float64)
+    return float(np.linalg.norm(got.astype(np.float64) - want) / max(np.linalg.norm(want), 1e-300))
+
+
+def check_step(dims, batch, seed, mode, lr=0.01, tol=1e-4):
+    X, labels, W, b = make_net(dims, batch, seed)
+    if len(dims) > 2:
+        b[0] = (I.uniform_pm1(seed, 7, 1, dims[1])[0] * 0.1).astype(np.float32)   # a non-zero bias somewhere
+    b = settle_relu_decisions(X, W, b)
+    ref = ofc.fc_step(X, labels, W, b, lr)
+    got = run_step(dims, batch, X, labels, W, b, lr, mode)
+    assert abs(got["loss"] - ref["loss"]) <= 1e-5 * max(1.0, abs(ref["loss"]))
+    assert nrm_err(got["logits"], ref["logits"]) <= tol
+    for l in range(len(dims) - 1):
+        assert nrm_err(got["dW"][l], ref["dW"][l]) <= tol, f"dW[{l}]"
+        assert nrm_err(got["db"][l], ref["db"][l]) <= tol, f"db[{l}]"
+        assert nrm_err(got["W_new"][l], ref["W_new"][l]) <= 1e-6, f"W_new[{l}]"
+        assert nrm_err(got["b_new"][l] + 1.0, ref["b_new"][l] + 1.0) <= 1e-6, f"b_new[{l}]"
+    return got
+
+
+@pytest.mark.parametrize("mode", [0, 1, -1], ids=["auto", "nt", "tnn"])
+def test_small_net_all_forward_modes(mode):
+    check_step([37, 70, 45, 10], 33, 5100, mode)
+
+
+def test_forward_modes_agree_and_rerun_is_bit_identical():
+    dims, batch = [100, 200, 150, 10], 64
+    X, labels, W, b = make_net(dims, batch, 5200)
+    a = run_step(dims, batch, X, labels, W, b, 0.01, 1)
+    a2 = run_step(dims, batch, X, labels, W, b, 0.01, 1)
+    t = run_step(dims, batch, X, labels, W, b, 0.01, -1)
+    assert a["loss"] == a2["loss"]
+    for l in range(3):
+        assert a["W_new"][l].tobytes() == a2["W_new"][l].tobytes()
+        assert nrm_err(a["dW"][l], t["dW"][l]) < 1e-5
+
+
+@pytest.mark.parametrize("mode", [1, -1, 0], ids=["nt", "tnn", "auto"])
+def test_config5_step(mode):
+    cfg = I.CONFIG5
+    check_step(cfg["dims"], cfg["batch"], cfg["seed"], mode)
+
+
+def test_elementwise_steps_against_numpy():
+    import torch
+    rng_z = I.normal01(5300, 0, 50, 70)
+    bias = I.normal01(5300, 1, 1, 70)[0]
+    Z = torch.from_numpy(rng_z.copy()).cuda()
+    mt.mtnn_fc_bias_act(Z, torch.from_numpy(bias).cuda(), True)
+    assert np.array_equal(Z.cpu().numpy(), np.maximum(rng_z + bias, np.float32(0)))
+    Z2 = torch.from_numpy(rng_z.copy()).cuda()
+    mt.mtnn_fc_bias_act(Z2, torch.from_numpy(bias).cuda(), False)
+    assert np.array_equal(Z2.cpu().numpy(), rng_z + bias)
+    # relu backward
+    H = torch.from_numpy(np.maximum(rng_z, 0)).cuda()
+    dH = torch.from_numpy(bias[None, :].repeat(50, 0).copy()).cuda()
+    mt.mtnn_fc_relu_backward(dH, H)
+    assert np.array_equal(dH.cpu().numpy(), np.where(rng_z > 0, bias[None, :], np.float32(0)))
+    # bias gradient (column sums)
+    dZ = torch.from_numpy(rng_z.copy()).cuda()
+    db = torch.empty(70, device="cuda")
+    mt.mtnn_fc_bias_grad(dZ, db)
+    assert np.allclose(db.cpu().numpy(), rng_z.astype(np.float64).sum(0), rtol=1e-5, atol=1e-5)
+    # sgd
+    P = torch.from_numpy(rng_z.copy()).cuda()
+    mt.mtnn_fc_sgd(P, dZ, 0.5)
+    assert np.array_equal(P.cpu().numpy(), rng_z - np.float32(0.5) * rng_z)
+    # softmax cross-entropy
+    labels = I.uniform_ints(5300, 2, 50, 0, 69).astype(np.int32)
+    out = torch.empty((50, 70), device="cuda")
+    rl = torch.empty(50, device="cuda")
+    ml = torch.empty(1, device="cuda")
+    mt.mtnn_fc_softmax_xent(torch.from_numpy(rng_z).cuda(), torch.from_numpy(labels).cuda(), out, rl, ml)
+    torch.cuda.synchronize()
+    z = rng_z.astype(np.float64)
+    lp = z - z.max(1, keepdims=True)
+    lp = lp - np.log(np.exp(lp).sum(1, keepdims=True))
+    want = np.exp(lp)
+    want[np.arange(50), labels] -= 1
+    assert np.allclose(out.cpu().numpy(), want / 50, rtol=1e-5, atol=1e-7)
+    assert np.allclose(rl.cpu().numpy(), -lp[np.arange(50), labels], rtol=1e-5, atol=1e-6)
+    assert abs(ml.item() + lp[np.arange(50), labels].mean()) < 1e-5
