@@ -17,7 +17,7 @@ LIB = os.path.join(HERE, "libmtnn.so")
 
 SOURCES = ["gemm.hip", "transpose.hip", "fc.hip", "api.cpp", "selector.cpp"]
 
-COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-parameter", "-ffp-contract=off",
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-parameter", "-Wno-inline-asm", "-ffp-contract=off",
           "-fvisibility=hidden"]
 # packed fp32 VALU forms are switched off for device code (build flags)
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

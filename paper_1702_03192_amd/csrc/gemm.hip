@@ -294,40 +294,306 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(GemmParams 
     }
 }
 
+// ---- the pipelined kernel: global -> LDS by DMA, NSTAGE slabs in flight --------------------------
+//
+// Same tiling and MFMA blocking as gemm_kernel, different data movement.  Slabs are copied from
+// global memory straight into LDS with global_load_lds_dwordx4 (no staging registers, no LDS store
+// instructions), NSTAGE slab buffers deep: the copy of slab j is issued while slab j - NSTAGE is
+// still being multiplied, so it has NSTAGE - 1 slab times to land.  Each lane's 16 bytes land at
+// (wave-uniform LDS base) + 16 * lane, so a wave instruction fills 1 KB of LDS linearly and the
+// lane chooses WHICH 16 global bytes it fetches: the tile is stored without padding and with the
+// 16-byte chunks of each row XOR-swizzled, which keeps the 128-bit fragment reads conflict-free.
+// Fragments are double-buffered in registers: the reads for the next 8 k (or for the first 8 k of
+// the next slab, right after the slab barrier) are in flight while the current ones feed the
+// matrix cores, so after a barrier the MFMAs restart from registers at once.
+//
+// Preconditions (checked by the launcher, which otherwise uses gemm_kernel): 16-byte aligned A and
+// B, lda and ldb multiples of 4, K a multiple of 4, and for NN also N a multiple of 4 -- every
+// 16-byte chunk is then entirely inside or entirely outside the matrix.  Chunks at or beyond K are
+// fetched from a 16-byte block of zeros; rows beyond m / n (and, for NN, chunks beyond N) are
+// clamped to valid ones and only feed outputs that are never stored.
+
+__device__ __attribute__((aligned(16))) float g_zero_chunk[4] = {0.f, 0.f, 0.f, 0.f};
+
+// one 16-byte global -> LDS copy per lane; lds_base is wave-uniform, lane l lands at lds_base + 16 l
+__device__ __forceinline__ void dma_chunk(const float* src, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(src), "s"(lds_base) : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+// All of this wave's LDS traffic done, then the workgroup barrier; global loads stay in flight.
+// The wait is the compiler's own s_waitcnt (vmcnt and expcnt fields left at "no wait"), so its
+// counter bookkeeping knows the fragment registers are valid afterwards; the empty asm statements
+// keep memory accesses from being moved across.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmParams p)
+{
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M;
+    constexpr int WN = BN / WAVES_N;
+    constexpr int TM = WM / 32;
+    constexpr int TN = WN / 32;
+    constexpr int KK = BK / 8;                        // fragment steps per slab
+    constexpr int CPR = BK / 4;                       // 16-byte chunks per [row][k] row
+    constexpr int RPL = (CPR >= 16) ? 1 : 16 / CPR;   // rows per 256 bytes of LDS
+    constexpr int NCH = BN / 4;                       // chunks per [k][n] row (NN)
+    constexpr int A_WORDS = BM * BK;
+    constexpr int B_WORDS = BN * BK;
+    constexpr int STAGE_WORDS = A_WORDS + B_WORDS;
+    constexpr int A_BLOCKS = A_WORDS / 256;           // 1 KB wave copies per slab
+    constexpr int B_BLOCKS = B_WORDS / 256;
+    constexpr int A_LOADS = (A_BLOCKS + NW - 1) / NW;
+    constexpr int B_LOADS = (B_BLOCKS + NW - 1) / NW;
+    constexpr int LPS = A_LOADS + B_LOADS;            // copies per wave per slab (same for every wave)
+    static_assert(KK >= 2 && KK % 2 == 0, "an even number of fragment steps per slab (register ping-pong)");
+    static_assert(A_WORDS % 256 == 0 && B_WORDS % 256 == 0, "slabs must be whole 1 KB blocks");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "2..4 slab buffers");
+    static_assert(LPS * (NSTAGE - 1) <= 63, "vmcnt is 6 bits");
+
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    const unsigned lds_base = (unsigned)(uintptr_t)lds;
+
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int lr = lane & 31;
+    const int lh = lane >> 5;
+    const int wm0 = (wave / WAVES_N) * WM;
+    const int wn0 = (wave % WAVES_N) * WN;
+
+    int tm, tn;
+    tile_of_block(p, tm, tn);
+    const int m0 = tm * BM;
+    const int n0 = tn * BN;
+    const int M = p.M, N = p.N, K = p.K;
+
+    // ---- copy geometry: which global chunk this lane fetches for each of its wave's blocks.
+    // A wave with fewer blocks than copies re-fetches a block another wave also fetches (same
+    // bytes to the same place), so every wave issues exactly LPS copies per slab and one
+    // vmcnt bookkeeping fits all.
+    const float* a_src[A_LOADS];
+    int a_k[A_LOADS];
+    unsigned a_dst[A_LOADS];
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) {
+        const int b = (i * NW + wave) % A_BLOCKS;
+        const int u = b * 64 + lane;
+        const int row = u / CPR;
+        const int slot = u % CPR;
+        const int c = slot ^ ((row / RPL) % CPR);
+        a_k[i] = c * 4;
+        a_src[i] = p.A + (size_t)min(m0 + row, M - 1) * p.lda + a_k[i];
+        a_dst[i] = (unsigned)(b * 1024);
+    }
+    const float* b_src[B_LOADS];
+    int b_k[B_LOADS];
+    unsigned b_dst[B_LOADS];
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) {
+        const int b = (i * NW + wave) % B_BLOCKS;
+        const int u = b * 64 + lane;
+        b_dst[i] = (unsigned)(A_WORDS * 4 + b * 1024);
+        if (NT) {
+            const int row = u / CPR;
+            const int slot = u % CPR;
+            const int c = slot ^ ((row / RPL) % CPR);
+            b_k[i] = c * 4;
+            b_src[i] = p.B + (size_t)min(n0 + row, N - 1) * p.ldb + b_k[i];
+        } else {
+            const int krow = u / NCH;
+            const int slot = u % NCH;
+            const int nch = (NCH >= 16) ? (slot ^ (((krow >> 2) & 1) << 3)) : slot;
+            const int col = min(n0 + nch * 4, N - 4);          // N % 4 == 0: a whole valid chunk
+            b_k[i] = krow;
+            b_src[i] = p.B + (size_t)krow * p.ldb + col;
+        }
+    }
+    const size_t b_step = NT ? (size_t)BK : (size_t)BK * p.ldb;
+
+    // issue the copies of slab `slab` into buffer `stage`
+    auto issue = [&](int slab, int stage) {
+        const int k0 = slab * BK;
+        const unsigned base = lds_base + (unsigned)stage * (STAGE_WORDS * 4);
+        const bool ragged = (k0 + BK > K);
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i) {
+            const float* src = a_src[i] + (size_t)k0;
+            if (ragged && k0 + a_k[i] >= K) src = g_zero_chunk;
+            dma_chunk(src, base + a_dst[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < B_LOADS; ++i) {
+            const float* src = b_src[i] + (size_t)slab * b_step;
+            if (ragged && k0 + b_k[i] >= K) src = g_zero_chunk;
+            dma_chunk(src, base + b_dst[i]);
+        }
+    };
+
+    // wait until all but the `newer` most recent slab copies of this wave have landed
+    auto wait_newer = [&](int newer) {
+        if constexpr (NSTAGE >= 4) {
+            if (newer >= 3) { wait_vmcnt<3 * LPS>(); return; }
+        }
+        if constexpr (NSTAGE >= 3) {
+            if (newer == 2) { wait_vmcnt<2 * LPS>(); return; }
+        }
+        if (newer == 1) wait_vmcnt<LPS>();
+        else wait_vmcnt<0>();
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // fragment reads of step kk from buffer `stage`
+    auto read_frags = [&](int stage, int kk, f32x4 (&af)[TM], f32x4 (&bf)[TN]) {
+        const float* as = lds + stage * STAGE_WORDS;
+        const float* bs = as + A_WORDS;
+        const int c = kk * 2 + lh;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = wm0 + i * 32 + lr;
+            af[i] = *reinterpret_cast<const f32x4*>(&as[row * BK + ((c ^ ((row / RPL) % CPR)) * 4)]);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            if (NT) {
+                const int row = wn0 + j * 32 + lr;
+                bf[j] = *reinterpret_cast<const f32x4*>(&bs[row * BK + ((c ^ ((row / RPL) % CPR)) * 4)]);
+            } else {
+                const int col = wn0 + j * 32 + lr;
+                const int krow = kk * 8 + lh * 4;             // rows krow..krow+3 share (krow>>2)&1
+                const int sw = (NCH >= 16) ? (((krow >> 2) & 1) << 3) : 0;
+                const float* q = &bs[krow * BN + (((col >> 2) ^ sw) << 2) + (col & 3)];
+                bf[j].x = q[0];
+                bf[j].y = q[BN];
+                bf[j].z = q[2 * BN];
+                bf[j].w = q[3 * BN];
+            }
+        }
+    };
+
+    const int num_slabs = (K + BK - 1) / BK;
+    const int pre = min(num_slabs, NSTAGE);
+    for (int s = 0; s < pre; ++s) issue(s, s);
+    wait_newer(pre - 1);
+    lds_barrier();
+
+    f32x4 af[2][TM], bf[2][TN];
+    read_frags(0, 0, af[0], bf[0]);
+
+    int stage = 0;
+    for (int s = 0; s < num_slabs; ++s) {
+        const int next_stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            const int cur = kk & 1;
+            if (kk + 1 < KK) {
+                read_frags(stage, kk + 1, af[cur ^ 1], bf[cur ^ 1]);
+            } else {
+                // every fragment read of slab s has been issued: after the barrier its buffer is free
+                if (s + 1 < num_slabs) wait_newer(min(num_slabs - 2 - s, NSTAGE - 2));
+                lds_barrier();
+                if (s + NSTAGE < num_slabs) issue(s + NSTAGE, stage);
+                if (s + 1 < num_slabs) read_frags(next_stage, 0, af[cur ^ 1], bf[cur ^ 1]);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][i][q], bf[cur][j][q], acc[i][j], 0, 0, 0);
+        }
+        stage = next_stage;
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn0 + j * 32 + lr;
+            if (col < N) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = m0 + wm0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
+                    if (row < M) p.C[(size_t)row * p.ldc + col] = acc[i][j][r];
+                }
+            }
+        }
+    }
+}
+
 // ---- configurations ---------------------------------------------------------------------------
 
 struct Config {
     const char* name;
     int bm, bn, bk;
-    void (*kern[2][2])(GemmParams);   // [op][vec]
+    void (*kern[2][2])(GemmParams);   // guarded kernel, [op][vec]
+    void (*dma[2])(GemmParams);       // pipelined kernel, [op]; null if the configuration has none
+    int nstage;
     int threads;
-    // LDS bytes: two buffers of an A slab and a B slab (layouts as in the kernel)
+    // LDS bytes of the guarded kernel: two buffers of an A slab and a B slab (layouts as in the kernel)
     size_t lds_bytes(int op) const
     {
         const size_t a = (size_t)bm * (bk + 4);
         const size_t b = (op == OP_NT) ? (size_t)bn * (bk + 4) : (size_t)bk * (bn + 8);
         return 2 * (a + b) * sizeof(float);
     }
+    size_t lds_bytes_dma() const { return (size_t)nstage * (bm + bn) * bk * sizeof(float); }
 };
 
+#define MTNN_GUARDED(BM, BN, BK, WMV, WNV)                                                    \
+    {{gemm_kernel<BM, BN, BK, WMV, WNV, false, false>, gemm_kernel<BM, BN, BK, WMV, WNV, false, true>},   \
+     {gemm_kernel<BM, BN, BK, WMV, WNV, true, false>, gemm_kernel<BM, BN, BK, WMV, WNV, true, true>}}
+
+// guarded kernel only
 #define MTNN_CFG(BM, BN, BK, WMV, WNV)                                                        \
-    {                                                                                         \
-        #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV, BM, BN, BK,                                   \
-            {{gemm_kernel<BM, BN, BK, WMV, WNV, false, false>,                                \
-              gemm_kernel<BM, BN, BK, WMV, WNV, false, true>},                                \
-             {gemm_kernel<BM, BN, BK, WMV, WNV, true, false>,                                 \
-              gemm_kernel<BM, BN, BK, WMV, WNV, true, true>}},                                \
-            WMV * WNV * 64                                                                    \
-    }
+    { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV, BM, BN, BK, MTNN_GUARDED(BM, BN, BK, WMV, WNV),   \
+      {nullptr, nullptr}, 0, WMV * WNV * 64 }
+
+// pipelined kernel with NS slab buffers; the guarded kernel of the same tile serves what it cannot
+#define MTNN_CFG_DMA(BM, BN, BK, WMV, WNV, NS)                                                \
+    { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV "_dma" #NS, BM, BN, BK, MTNN_GUARDED(BM, BN, BK, WMV, WNV), \
+      {gemm_dma_kernel<BM, BN, BK, WMV, WNV, false, NS>, gemm_dma_kernel<BM, BN, BK, WMV, WNV, true, NS>}, \
+      NS, WMV * WNV * 64 }
 
 static const Config kConfigs[] = {
-    MTNN_CFG(256, 256, 16, 2, 4),   // 0: 8 waves, wave tile 128 x 64
-    MTNN_CFG(128, 128, 16, 2, 2),   // 1: 4 waves, wave tile 64 x 64
-    MTNN_CFG(64, 64, 16, 2, 2),     // 2: 4 waves, wave tile 32 x 32
-    MTNN_CFG(256, 128, 16, 4, 2),   // 3: 8 waves, wave tile 64 x 64
-    MTNN_CFG(128, 256, 16, 2, 4),   // 4: 8 waves, wave tile 64 x 64
-    MTNN_CFG(32, 256, 16, 1, 4),    // 5: 4 waves, wave tile 32 x 64 (small m)
-    MTNN_CFG(256, 32, 16, 4, 1),    // 6: 4 waves, wave tile 64 x 32 (small n)
+    MTNN_CFG(256, 256, 16, 2, 4),          // 0: 8 waves, wave tile 128 x 64
+    MTNN_CFG(128, 128, 16, 2, 2),          // 1: 4 waves, wave tile 64 x 64
+    MTNN_CFG(64, 64, 16, 2, 2),            // 2: 4 waves, wave tile 32 x 32
+    MTNN_CFG(256, 128, 16, 4, 2),          // 3: 8 waves, wave tile 64 x 64
+    MTNN_CFG(128, 256, 16, 2, 4),          // 4: 8 waves, wave tile 64 x 64
+    MTNN_CFG(32, 256, 16, 1, 4),           // 5: 4 waves, wave tile 32 x 64 (small m)
+    MTNN_CFG(256, 32, 16, 4, 1),           // 6: 4 waves, wave tile 64 x 32 (small n)
+    MTNN_CFG_DMA(256, 256, 16, 4, 2, 4),   // 7
+    MTNN_CFG_DMA(256, 256, 16, 2, 4, 4),   // 8
+    MTNN_CFG_DMA(256, 256, 16, 4, 2, 2),   // 9: 64 KB of LDS
+    MTNN_CFG_DMA(128, 128, 16, 2, 2, 4),   // 10: 64 KB
+    MTNN_CFG_DMA(128, 128, 32, 2, 2, 4),   // 11
+    MTNN_CFG_DMA(128, 128, 32, 4, 2, 4),   // 12
+    MTNN_CFG_DMA(256, 128, 16, 4, 2, 4),   // 13
+    MTNN_CFG_DMA(64, 64, 32, 2, 2, 4),     // 14: 64 KB
+    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2),   // 15: 128 KB
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 
@@ -366,18 +632,21 @@ int launch_gemm(hipStream_t s, int op, int cfg, int m, int n, int k,
     const bool vec = (lda % 4 == 0) && (ldb % 4 == 0) &&
                      ((reinterpret_cast<uintptr_t>(A) & 15) == 0) &&
                      ((reinterpret_cast<uintptr_t>(B) & 15) == 0);
-    auto kern = c.kern[op][vec ? 1 : 0];
-    const size_t lds = c.lds_bytes(op);
+    // the pipelined kernel needs whole 16-byte chunks everywhere (see its preconditions)
+    const bool dma_ok = vec && c.dma[op] && (k % 4 == 0) && (op == OP_NT || n % 4 == 0);
+    auto kern = dma_ok ? c.dma[op] : c.kern[op][vec ? 1 : 0];
+    const size_t lds = dma_ok ? c.lds_bytes_dma() : c.lds_bytes(op);
     if (lds > 64 * 1024) {
         // opt in to the large LDS carve-out once per kernel and device
-        static bool raised[kNumConfigs][2][2][16] = {};
+        static bool raised[kNumConfigs][2][3][16] = {};
+        const int which = dma_ok ? 2 : (vec ? 1 : 0);
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess) return (int)hipGetLastError();
-        if (dev < 0 || dev >= 16 || !raised[cfg][op][vec ? 1 : 0][dev]) {
+        if (dev < 0 || dev >= 16 || !raised[cfg][op][which][dev]) {
             const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return (int)e;
-            if (dev >= 0 && dev < 16) raised[cfg][op][vec ? 1 : 0][dev] = true;
+            if (dev >= 0 && dev < 16) raised[cfg][op][which][dev] = true;
         }
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(c.threads), lds, s, p);

@@ -14,7 +14,7 @@ from gpu_util import Guarded, check_gemm, dev_matrix
 
 pytestmark = pytest.mark.gpu
 
-NCFG = 7
+NCFG = 16
 
 
 def sync():
