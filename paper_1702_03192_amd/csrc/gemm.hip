@@ -309,17 +309,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(GemmParams 
 //
 // Preconditions (checked by the launcher, which otherwise uses gemm_kernel): 16-byte aligned A and
 // B, lda and ldb multiples of 4, K a multiple of 4, and for NN also N a multiple of 4 -- every
-// 16-byte chunk is then entirely inside or entirely outside the matrix.  Chunks at or beyond K are
-// fetched from a 16-byte block of zeros; rows beyond m / n (and, for NN, chunks beyond N) are
+// 16-byte chunk is then entirely inside or entirely outside the matrix; and leading dimensions small
+// enough that byte offsets within one tile fit 32 bits.  Chunks at or beyond K are zeroed in LDS
+// after they land; rows beyond m / n (and, for NN, chunks beyond N) are
 // clamped to valid ones and only feed outputs that are never stored.
 
-__device__ __attribute__((aligned(16))) float g_zero_chunk[4] = {0.f, 0.f, 0.f, 0.f};
-
-// one 16-byte global -> LDS copy per lane; lds_base is wave-uniform, lane l lands at lds_base + 16 l
-__device__ __forceinline__ void dma_chunk(const float* src, unsigned lds_base)
+// One 16-byte global -> LDS copy per lane: lane l fetches base + lane_off (a wave-uniform 64-bit
+// base and a per-lane unsigned 32-bit byte offset) and its bytes land at lds_base + 16 l.  Per slab
+// only the scalar base moves, so a copy costs two scalar and one vector-memory instruction.
+__device__ __forceinline__ void dma_chunk_s(const float* base, unsigned lane_off, unsigned lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :: "v"(src), "s"(lds_base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(lane_off), "s"(base), "s"(lds_base) : "memory", "m0");
 }
 
 template <int N>
@@ -357,13 +358,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
     constexpr int STAGE_WORDS = A_WORDS + B_WORDS;
     constexpr int A_BLOCKS = A_WORDS / 256;           // 1 KB wave copies per slab
     constexpr int B_BLOCKS = B_WORDS / 256;
-    constexpr int A_LOADS = (A_BLOCKS + NW - 1) / NW;
-    constexpr int B_LOADS = (B_BLOCKS + NW - 1) / NW;
-    constexpr int LPS = A_LOADS + B_LOADS;            // copies per wave per slab (same for every wave)
+    // Copies are issued by half of the waves at a time: with 8 waves, waves 0-3 (one per SIMD) feed
+    // the even slabs and waves 4-7 the odd ones.  While a wave is busy issuing copies its SIMD
+    // partner keeps the matrix core fed, so the issue work is hidden instead of stalling both.
+    constexpr int NG = (NW >= 8) ? 2 : 1;             // issuer groups
+    constexpr int NI = NW / NG;                       // waves per group
+    constexpr int A_LOADS = (A_BLOCKS + NI - 1) / NI;
+    constexpr int B_LOADS = (B_BLOCKS + NI - 1) / NI;
+    constexpr int LPS = A_LOADS + B_LOADS;            // copies per issuing wave per slab
     static_assert(KK >= 2 && KK % 2 == 0, "an even number of fragment steps per slab (register ping-pong)");
     static_assert(A_WORDS % 256 == 0 && B_WORDS % 256 == 0, "slabs must be whole 1 KB blocks");
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "2..4 slab buffers");
-    static_assert(LPS * (NSTAGE - 1) <= 63, "vmcnt is 6 bits");
+    static_assert(LPS * 2 <= 63, "vmcnt is 6 bits");
 
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const unsigned lds_base = (unsigned)(uintptr_t)lds;
@@ -382,30 +388,32 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
     const int n0 = tn * BN;
     const int M = p.M, N = p.N, K = p.K;
 
-    // ---- copy geometry: which global chunk this lane fetches for each of its wave's blocks.
-    // A wave with fewer blocks than copies re-fetches a block another wave also fetches (same
-    // bytes to the same place), so every wave issues exactly LPS copies per slab and one
-    // vmcnt bookkeeping fits all.
-    const float* a_src[A_LOADS];
+    // ---- copy geometry: which global chunk this lane fetches for each of its wave's blocks, as
+    // a byte offset from the tile's first row (A) / first row or first k-row (B).  A wave with fewer
+    // blocks than copies re-fetches a block another wave also fetches (same bytes to the same
+    // place), so every issuing wave issues exactly LPS copies per slab.
+    const int grp = wave / NI;
+    const int wi = wave % NI;
+    const float* a_tile = p.A + (size_t)m0 * p.lda;
+    const float* b_tile = NT ? p.B + (size_t)n0 * p.ldb : p.B;
+    unsigned a_off[A_LOADS], a_dst[A_LOADS];
     int a_k[A_LOADS];
-    unsigned a_dst[A_LOADS];
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i) {
-        const int b = (i * NW + wave) % A_BLOCKS;
+        const int b = (i * NI + wi) % A_BLOCKS;
         const int u = b * 64 + lane;
         const int row = u / CPR;
         const int slot = u % CPR;
         const int c = slot ^ ((row / RPL) % CPR);
         a_k[i] = c * 4;
-        a_src[i] = p.A + (size_t)min(m0 + row, M - 1) * p.lda + a_k[i];
+        a_off[i] = (unsigned)(((size_t)(min(m0 + row, M - 1) - m0) * p.lda + a_k[i]) * 4);
         a_dst[i] = (unsigned)(b * 1024);
     }
-    const float* b_src[B_LOADS];
+    unsigned b_off[B_LOADS], b_dst[B_LOADS];
     int b_k[B_LOADS];
-    unsigned b_dst[B_LOADS];
 #pragma unroll
     for (int i = 0; i < B_LOADS; ++i) {
-        const int b = (i * NW + wave) % B_BLOCKS;
+        const int b = (i * NI + wi) % B_BLOCKS;
         const int u = b * 64 + lane;
         b_dst[i] = (unsigned)(A_WORDS * 4 + b * 1024);
         if (NT) {
@@ -413,36 +421,63 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
             const int slot = u % CPR;
             const int c = slot ^ ((row / RPL) % CPR);
             b_k[i] = c * 4;
-            b_src[i] = p.B + (size_t)min(n0 + row, N - 1) * p.ldb + b_k[i];
+            b_off[i] = (unsigned)(((size_t)(min(n0 + row, N - 1) - n0) * p.ldb + b_k[i]) * 4);
         } else {
             const int krow = u / NCH;
             const int slot = u % NCH;
             const int nch = (NCH >= 16) ? (slot ^ (((krow >> 2) & 1) << 3)) : slot;
             const int col = min(n0 + nch * 4, N - 4);          // N % 4 == 0: a whole valid chunk
             b_k[i] = krow;
-            b_src[i] = p.B + (size_t)krow * p.ldb + col;
+            b_off[i] = (unsigned)(((size_t)krow * p.ldb + col) * 4);
         }
     }
     const size_t b_step = NT ? (size_t)BK : (size_t)BK * p.ldb;
 
-    // issue the copies of slab `slab` into buffer `stage`
+    // Issue this wave's copies of slab `slab` into buffer `stage`.  In a ragged last slab a chunk at
+    // or beyond K is fetched from the last valid chunk instead (a valid address); zero_tail() then
+    // overwrites it with zeros once the copy has landed.
     auto issue = [&](int slab, int stage) {
         const int k0 = slab * BK;
         const unsigned base = lds_base + (unsigned)stage * (STAGE_WORDS * 4);
-        const bool ragged = (k0 + BK > K);
+        const float* a_base = a_tile + (size_t)k0;
+        const float* b_base = b_tile + (size_t)slab * b_step;
+        if (k0 + BK <= K) {
 #pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) {
-            const float* src = a_src[i] + (size_t)k0;
-            if (ragged && k0 + a_k[i] >= K) src = g_zero_chunk;
-            dma_chunk(src, base + a_dst[i]);
-        }
+            for (int i = 0; i < A_LOADS; ++i) dma_chunk_s(a_base, a_off[i], base + a_dst[i]);
 #pragma unroll
-        for (int i = 0; i < B_LOADS; ++i) {
-            const float* src = b_src[i] + (size_t)slab * b_step;
-            if (ragged && k0 + b_k[i] >= K) src = g_zero_chunk;
-            dma_chunk(src, base + b_dst[i]);
+            for (int i = 0; i < B_LOADS; ++i) dma_chunk_s(b_base, b_off[i], base + b_dst[i]);
+        } else {
+            const int kv = K - k0;                           // valid k in this slab, a multiple of 4
+#pragma unroll
+            for (int i = 0; i < A_LOADS; ++i) {
+                const unsigned off = (a_k[i] < kv) ? a_off[i] : a_off[i] - (unsigned)((a_k[i] - (kv - 4)) * 4);
+                dma_chunk_s(a_base, off, base + a_dst[i]);
+            }
+#pragma unroll
+            for (int i = 0; i < B_LOADS; ++i) {
+                unsigned off = b_off[i];
+                if (b_k[i] >= kv)
+                    off -= NT ? (unsigned)((b_k[i] - (kv - 4)) * 4)
+                              : (unsigned)((size_t)(b_k[i] - (kv - 1)) * p.ldb * 4);
+                dma_chunk_s(b_base, off, base + b_dst[i]);
+            }
         }
     };
+    // after this wave's copies of a ragged slab have landed: zeros over the chunks at or beyond K
+    auto zero_tail = [&](int slab, int stage) {
+        const int kv = K - slab * BK;
+        if (kv >= BK) return;
+        float* buf = lds + stage * STAGE_WORDS;
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i)
+            if (a_k[i] >= kv) *reinterpret_cast<f32x4*>(buf + a_dst[i] / 4 + lane * 4) = z;
+#pragma unroll
+        for (int i = 0; i < B_LOADS; ++i)
+            if (b_k[i] >= kv) *reinterpret_cast<f32x4*>(buf + b_dst[i] / 4 + lane * 4) = z;
+    };
+    // does this wave feed slab j?
+    auto feeds = [&](int j) { return NG == 1 || (j & 1) == grp; };
 
     // wait until all but the `newer` most recent slab copies of this wave have landed
     auto wait_newer = [&](int newer) {
@@ -492,10 +527,23 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
         }
     };
 
+    // Ring of NSTAGE buffers, slab j in buffer j % NSTAGE.  Slabs 0 .. NSTAGE-1 are requested before
+    // the loop; slab j + NSTAGE is requested right after the barrier that ends the reads of slab j.
+    // A wave waits only for copies it issued itself: when it needs slab s + 1 (which it fed iff
+    // feeds(s + 1)), the copies it has issued since then are those of the slabs it feeds among
+    // s + 2 .. last requested.
     const int num_slabs = (K + BK - 1) / BK;
     const int pre = min(num_slabs, NSTAGE);
-    for (int s = 0; s < pre; ++s) issue(s, s);
-    wait_newer(pre - 1);
+    for (int s = 0; s < pre; ++s)
+        if (feeds(s)) issue(s, s);
+    {
+        int newer = 0;
+        for (int j = 1; j < pre; ++j) newer += feeds(j) ? 1 : 0;
+        if (feeds(0)) {
+            wait_newer(newer);
+            zero_tail(0, 0);
+        }
+    }
     lds_barrier();
 
     f32x4 af[2][TM], bf[2][TN];
@@ -511,9 +559,15 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
                 read_frags(stage, kk + 1, af[cur ^ 1], bf[cur ^ 1]);
             } else {
                 // every fragment read of slab s has been issued: after the barrier its buffer is free
-                if (s + 1 < num_slabs) wait_newer(min(num_slabs - 2 - s, NSTAGE - 2));
+                if (s + 1 < num_slabs && feeds(s + 1)) {
+                    const int last = min(s + NSTAGE - 1, num_slabs - 1);      // last slab requested so far
+                    int newer = 0;
+                    for (int j = s + 2; j <= last; ++j) newer += feeds(j) ? 1 : 0;
+                    wait_newer(newer);
+                    zero_tail(s + 1, next_stage);
+                }
                 lds_barrier();
-                if (s + NSTAGE < num_slabs) issue(s + NSTAGE, stage);
+                if (s + NSTAGE < num_slabs && feeds(s + NSTAGE)) issue(s + NSTAGE, stage);
                 if (s + 1 < num_slabs) read_frags(next_stage, 0, af[cur ^ 1], bf[cur ^ 1]);
             }
 #pragma unroll
@@ -585,15 +639,19 @@ static const Config kConfigs[] = {
     MTNN_CFG(128, 256, 16, 2, 4),          // 4: 8 waves, wave tile 64 x 64
     MTNN_CFG(32, 256, 16, 1, 4),           // 5: 4 waves, wave tile 32 x 64 (small m)
     MTNN_CFG(256, 32, 16, 4, 1),           // 6: 4 waves, wave tile 64 x 32 (small n)
-    MTNN_CFG_DMA(256, 256, 16, 4, 2, 4),   // 7
-    MTNN_CFG_DMA(256, 256, 16, 2, 4, 4),   // 8
-    MTNN_CFG_DMA(256, 256, 16, 4, 2, 2),   // 9: 64 KB of LDS
-    MTNN_CFG_DMA(128, 128, 16, 2, 2, 4),   // 10: 64 KB
-    MTNN_CFG_DMA(128, 128, 32, 2, 2, 4),   // 11
-    MTNN_CFG_DMA(128, 128, 32, 4, 2, 4),   // 12
-    MTNN_CFG_DMA(256, 128, 16, 4, 2, 4),   // 13
-    MTNN_CFG_DMA(64, 64, 32, 2, 2, 4),     // 14: 64 KB
-    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2),   // 15: 128 KB
+    MTNN_CFG_DMA(256, 256, 16, 4, 2, 2),   // 7: 64 KB of LDS
+    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2),   // 8: 128 KB
+    MTNN_CFG_DMA(256, 256, 32, 2, 4, 2),   // 9
+    MTNN_CFG_DMA(128, 128, 32, 4, 2, 4),   // 10
+    MTNN_CFG_DMA(128, 128, 32, 4, 2, 2),   // 11
+    MTNN_CFG_DMA(128, 128, 64, 4, 2, 2),   // 12: 128 KB
+    MTNN_CFG_DMA(128, 128, 64, 2, 2, 2),   // 13
+    MTNN_CFG_DMA(256, 128, 16, 2, 2, 3),   // 14: 4 waves of 128 x 64, 72 KB: two workgroups per CU
+    MTNN_CFG_DMA(256, 128, 32, 4, 2, 2),   // 15: 96 KB
+    MTNN_CFG_DMA(128, 256, 32, 2, 4, 2),   // 16
+    MTNN_CFG_DMA(64, 64, 32, 2, 2, 4),     // 17: 64 KB
+    MTNN_CFG_DMA(64, 64, 64, 2, 2, 2),     // 18
+    MTNN_CFG_DMA(128, 64, 32, 2, 2, 4),    // 19
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 
@@ -633,7 +691,12 @@ int launch_gemm(hipStream_t s, int op, int cfg, int m, int n, int k,
                      ((reinterpret_cast<uintptr_t>(A) & 15) == 0) &&
                      ((reinterpret_cast<uintptr_t>(B) & 15) == 0);
     // the pipelined kernel needs whole 16-byte chunks everywhere (see its preconditions)
-    const bool dma_ok = vec && c.dma[op] && (k % 4 == 0) && (op == OP_NT || n % 4 == 0);
+    // ... and per-lane byte offsets inside a tile that fit 32 bits
+    const unsigned long long lim = 1ull << 32;
+    const bool off_ok = (unsigned long long)c.bm * (unsigned long long)lda * 4ull < lim &&
+                        (op == OP_NT ? (unsigned long long)c.bn * (unsigned long long)ldb * 4ull < lim
+                                     : (unsigned long long)(c.bk + 1) * (unsigned long long)ldb * 4ull < lim);
+    const bool dma_ok = vec && c.dma[op] && (k % 4 == 0) && (op == OP_NT || n % 4 == 0) && off_ok;
     auto kern = dma_ok ? c.dma[op] : c.kern[op][vec ? 1 : 0];
     const size_t lds = dma_ok ? c.lds_bytes_dma() : c.lds_bytes(op);
     if (lds > 64 * 1024) {

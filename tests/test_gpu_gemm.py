@@ -14,7 +14,7 @@ from gpu_util import Guarded, check_gemm, dev_matrix
 
 pytestmark = pytest.mark.gpu
 
-NCFG = 16
+NCFG = 20
 
 
 def sync():
@@ -52,7 +52,8 @@ def test_config_count_matches():
 
 @pytest.mark.parametrize("op", [mt.OP_NT, mt.OP_NN], ids=["NT", "NN"])
 @pytest.mark.parametrize("cfg", list(range(NCFG)))
-@pytest.mark.parametrize("m,n,k", [(300, 520, 77), (64, 64, 64), (33, 31, 5), (257, 255, 130)])
+@pytest.mark.parametrize("m,n,k", [(300, 520, 77), (64, 64, 64), (33, 31, 5), (257, 255, 130), (130, 260, 100),
+                                   (70, 36, 12), (264, 392, 200)])
 def test_every_config_against_oracle(op, cfg, m, n, k):
     A, B = operands(op, m, n, k, 100 + cfg)
     got = run(op, cfg, A, B)
