@@ -11,9 +11,10 @@
  *
  * Conventions for every call
  *   - matrices are row-major fp32; leading dimensions are in ELEMENTS;
- *   - A, B, C, in, out and workspace are DEVICE pointers owned by the caller; the library
- *     neither allocates nor frees device memory on these calls and keeps no reference to the
- *     buffers after the enqueued work has run;
+ *   - A, B, C, in, out and workspace are DEVICE pointers owned by the caller; the library keeps no
+ *     reference to them after the enqueued work has run.  The only device memory the library ever
+ *     allocates is the split-k scratch described at mtnn_gemm_ex (once per device and stream,
+ *     on the first launch that needs it);
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); work is enqueued
  *     on it and the call returns without synchronising;
  *   - alpha = 1 and there is no beta*C term (Section II): C is overwritten;
@@ -136,13 +137,19 @@ MTNN_API int mtnn_model_margin(const double *x, int nfeat, double *margin);
 
 /* ---- tile configurations (tuning, tests) -------------------------------------------------- */
 
-/* The GEMM kernels come in several tile configurations; mtnn_nt / mtnn_nn choose one per shape
- * with a fixed rule.  These calls run a given configuration (cfg in [0, count)), or the default
- * choice when cfg == -1.  op: 0 = NN, 1 = NT. */
+/* The GEMM kernels come in several tile configurations, optionally with the k range split over
+ * several workgroups per C tile (partial products summed in a fixed order by a second kernel);
+ * mtnn_nt / mtnn_nn choose both per shape with a fixed cost model.  These calls run a given
+ * configuration (cfg in [0, count), or -1 for the model's choice) and split count (1..32, or 0 for
+ * the model's choice when cfg is -1 and no split when cfg is given).  op: 0 = NN, 1 = NT.
+ * Split-k keeps its partial products in a 64 MiB scratch buffer that the library allocates once per
+ * (device, stream) the first time it is needed and never frees; a launch whose partials do not fit
+ * runs unsplit. */
 MTNN_API int mtnn_gemm_config_count(void);
 MTNN_API const char *mtnn_gemm_config_name(int cfg);
 MTNN_API int mtnn_gemm_default_config(int op, int m, int n, int k);
-MTNN_API int mtnn_gemm_ex(void *stream, int op, int cfg, int m, int n, int k,
+MTNN_API int mtnn_gemm_default_splits(int op, int m, int n, int k);
+MTNN_API int mtnn_gemm_ex(void *stream, int op, int cfg, int splits, int m, int n, int k,
                  const float *A, int lda, const float *B, int ldb, float *C, int ldc);
 
 /* ---- one training step of a fully connected net (Section V-C, Table IX sizes) ---------------- */

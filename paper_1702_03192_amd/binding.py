@@ -64,7 +64,8 @@ SIGNATURES = {
     "mtnn_gemm_config_count": (_c_int, []),
     "mtnn_gemm_config_name": (ctypes.c_char_p, [_c_int]),
     "mtnn_gemm_default_config": (_c_int, [_c_int, _c_int, _c_int, _c_int]),
-    "mtnn_gemm_ex": (_c_int, [_c_vp, _c_int, _c_int] + _GEMM[1:]),
+    "mtnn_gemm_default_splits": (_c_int, [_c_int, _c_int, _c_int, _c_int]),
+    "mtnn_gemm_ex": (_c_int, [_c_vp, _c_int, _c_int, _c_int] + _GEMM[1:]),
     "mtnn_fc_workspace_bytes": (_c_sz, [_c_int, _p_int, _c_int]),
     "mtnn_fc_train_step": (_c_int, [_c_vp, ctypes.POINTER(FcStepDesc)]),
     "mtnn_fc_bias_act": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp, _c_int]),
@@ -166,12 +167,12 @@ def mtnn_nn(A, B, C, stream=None):
     return C
 
 
-def mtnn_gemm_ex(op, cfg, A, B, C, stream=None):
-    """A given tile configuration of the NN (op 0) or NT (op 1) kernel; cfg -1 = default rule."""
+def mtnn_gemm_ex(op, cfg, A, B, C, stream=None, splits=0):
+    """A given tile configuration / split count of the NN (op 0) or NT (op 1) kernel; cfg -1 = default rule."""
     (pa, lda), (pb, ldb), (pc, ldc) = _dev(A, "A"), _dev(B, "B"), _dev(C, "C")
     m, k = A.shape
     n = B.shape[0] if op == OP_NT else B.shape[1]
-    _check(lib().mtnn_gemm_ex(_stream(stream), op, cfg, m, n, k, pa, lda, pb, ldb, pc, ldc), "mtnn_gemm_ex")
+    _check(lib().mtnn_gemm_ex(_stream(stream), op, cfg, splits, m, n, k, pa, lda, pb, ldb, pc, ldc), "mtnn_gemm_ex")
     return C
 
 
@@ -341,6 +342,10 @@ def mtnn_copy_bytes(src, dst, stream=None):
         raise ValueError("size mismatch")
     _check(lib().mtnn_copy_bytes(_stream(stream), nbytes, src.data_ptr(), dst.data_ptr()), "mtnn_copy_bytes")
     return dst
+
+
+def mtnn_gemm_default_splits(op: int, m: int, n: int, k: int) -> int:
+    return int(lib().mtnn_gemm_default_splits(op, m, n, k))
 
 
 def mtnn_status_string(status: int) -> str:

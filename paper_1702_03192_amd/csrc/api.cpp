@@ -55,7 +55,7 @@ int check_gemm(int op, int m, int n, int k, const float* A, int lda, const float
     return MTNN_OK;
 }
 
-int run_gemm(void* stream, int op, int cfg, int m, int n, int k, const float* A, int lda,
+int run_gemm(void* stream, int op, int cfg, int splits, int m, int n, int k, const float* A, int lda,
              const float* B, int ldb, float* C, int ldc)
 {
     const int st = check_gemm(op, m, n, k, A, lda, B, ldb, C, ldc);
@@ -64,7 +64,7 @@ int run_gemm(void* stream, int op, int cfg, int m, int n, int k, const float* A,
     hipStream_t s = static_cast<hipStream_t>(stream);
     int err;
     if (k == 0) err = mtnn::launch_fill_zero(s, m, n, C, ldc);
-    else err = mtnn::launch_gemm(s, op, cfg, m, n, k, A, lda, B, ldb, C, ldc);
+    else err = mtnn::launch_gemm(s, op, cfg, splits, m, n, k, A, lda, B, ldb, C, ldc);
     return launch_status(err);
 }
 
@@ -85,21 +85,28 @@ extern "C" {
 int mtnn_nt(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
             float* C, int ldc)
 {
-    return run_gemm(stream, mtnn::OP_NT, -1, m, n, k, A, lda, B, ldb, C, ldc);
+    return run_gemm(stream, mtnn::OP_NT, -1, 0, m, n, k, A, lda, B, ldb, C, ldc);
 }
 
 int mtnn_nn(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
             float* C, int ldc)
 {
-    return run_gemm(stream, mtnn::OP_NN, -1, m, n, k, A, lda, B, ldb, C, ldc);
+    return run_gemm(stream, mtnn::OP_NN, -1, 0, m, n, k, A, lda, B, ldb, C, ldc);
 }
 
-int mtnn_gemm_ex(void* stream, int op, int cfg, int m, int n, int k, const float* A, int lda,
+int mtnn_gemm_ex(void* stream, int op, int cfg, int splits, int m, int n, int k, const float* A, int lda,
                  const float* B, int ldb, float* C, int ldc)
 {
-    if ((op != mtnn::OP_NN && op != mtnn::OP_NT) || cfg < -1 || cfg >= mtnn::gemm_config_count())
+    if ((op != mtnn::OP_NN && op != mtnn::OP_NT) || cfg < -1 || cfg >= mtnn::gemm_config_count() ||
+        splits < 0 || splits > 32)
         return MTNN_ERR_ARG;
-    return run_gemm(stream, op, cfg, m, n, k, A, lda, B, ldb, C, ldc);
+    return run_gemm(stream, op, cfg, splits, m, n, k, A, lda, B, ldb, C, ldc);
+}
+
+int mtnn_gemm_default_splits(int op, int m, int n, int k)
+{
+    if ((op != mtnn::OP_NN && op != mtnn::OP_NT) || m <= 0 || n <= 0 || k <= 0) return -1;
+    return mtnn::gemm_default_splits(op, m, n, k);
 }
 
 int mtnn_gemm_config_count(void) { return mtnn::gemm_config_count(); }
@@ -143,7 +150,7 @@ int mtnn_tnn(void* stream, int m, int n, int k, const float* A, int lda, const f
     int st = check_gemm(mtnn::OP_NT, m, n, k, A, lda, B, ldb, C, ldc);
     if (st != MTNN_OK) return st;
     if (m == 0 || n == 0) return MTNN_OK;
-    if (k == 0) return run_gemm(stream, mtnn::OP_NT, -1, m, n, k, A, lda, B, ldb, C, ldc);
+    if (k == 0) return run_gemm(stream, mtnn::OP_NT, -1, 0, m, n, k, A, lda, B, ldb, C, ldc);
     if (!workspace || workspace_bytes < mtnn_tnn_workspace_bytes(n, k)) return MTNN_ERR_WORKSPACE;
     float* Bt = static_cast<float*>(workspace);
     const Range rw = span(Bt, k, n, n);
@@ -152,7 +159,7 @@ int mtnn_tnn(void* stream, int m, int n, int k, const float* A, int lda, const f
     // Algorithm 1: B (n x k) -> B^T (k x n), then the NN product on the same stream
     st = mtnn_transpose(stream, n, k, B, ldb, Bt, n);
     if (st != MTNN_OK) return st;
-    return run_gemm(stream, mtnn::OP_NN, -1, m, n, k, A, lda, Bt, n, C, ldc);
+    return run_gemm(stream, mtnn::OP_NN, -1, 0, m, n, k, A, lda, Bt, n, C, ldc);
 }
 
 int mtnn_auto(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,

@@ -28,6 +28,8 @@
 // results are bit-reproducible.
 #include "mtnn_internal.h"
 
+#include <mutex>
+
 namespace mtnn {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -42,7 +44,43 @@ struct GemmParams {
     int tiles_m, tiles_n;
     int group_m;      // C-tile rows per band (L2 locality)
     int num_xcd;      // 8 on MI355X
+    // split-k: workgroup w handles C tile w % tiles and k range [split * k_per_split, ...) with
+    // split = w / tiles; partial products go to `part` (splits dense M x N matrices), summed by
+    // reduce_splits_kernel in split order.  splits == 1: results go straight to C.
+    int splits;
+    int k_per_split;  // a multiple of every configuration's k slab
+    float* part;
 };
+
+// what one workgroup works on: its k range of A and B, and where its tile of results goes
+struct WorkView {
+    const float* A;
+    const float* B;
+    float* C;
+    long ldc;
+    int K;
+    int pid;          // C tile index before the XCD / band remapping
+};
+
+__device__ __forceinline__ WorkView work_view(const GemmParams& p, bool nt)
+{
+    WorkView v;
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int split = (p.splits > 1) ? (int)blockIdx.x / tiles : 0;
+    v.pid = (int)blockIdx.x - split * tiles;
+    const int ks = split * p.k_per_split;
+    v.K = min(p.K - ks, p.k_per_split);
+    v.A = p.A + ks;
+    v.B = nt ? p.B + ks : p.B + (size_t)ks * p.ldb;
+    if (p.splits > 1) {
+        v.C = p.part + (size_t)split * p.M * p.N;
+        v.ldc = p.N;
+    } else {
+        v.C = p.C;
+        v.ldc = p.ldc;
+    }
+    return v;
+}
 
 // ---- guarded global loads -------------------------------------------------------------------
 
@@ -89,10 +127,9 @@ __device__ __forceinline__ f32x4 load_n4(const float* __restrict__ B, long ldb, 
 
 // ---- workgroup id -> C tile -------------------------------------------------------------------
 
-__device__ __forceinline__ void tile_of_block(const GemmParams& p, int& tm, int& tn)
+__device__ __forceinline__ void tile_of_block(const GemmParams& p, int pid, int& tm, int& tn)
 {
     const int total = p.tiles_m * p.tiles_n;
-    int pid = blockIdx.x;
     // undo the round-robin deal to XCDs: XCD x receives ids x, x+X, x+2X, ...; give it the
     // contiguous range of logical ids [start(x), start(x+1))
     const int X = p.num_xcd;
@@ -154,11 +191,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(GemmParams 
     const int wm0 = (wave / WAVES_N) * WM;
     const int wn0 = (wave % WAVES_N) * WN;
 
+    const WorkView w = work_view(p, NT);
     int tm, tn;
-    tile_of_block(p, tm, tn);
+    tile_of_block(p, w.pid, tm, tn);
     const int m0 = tm * BM;
     const int n0 = tn * BN;
-    const int M = p.M, N = p.N, K = p.K;
+    const int M = p.M, N = p.N, K = w.K;
 
     // per-thread staging geometry
     const float* a_row[A_LOADS];
@@ -168,7 +206,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(GemmParams 
         const int f = a_on ? t + i * NTH : 0;
         const int row = f / KQ;
         a_kq[i] = (f % KQ) * 4;
-        a_row[i] = p.A + (size_t)min(m0 + row, M - 1) * p.lda;
+        a_row[i] = w.A + (size_t)min(m0 + row, M - 1) * p.lda;
         a_lds[i] = row * SA + a_kq[i];
     }
     const float* b_row[B_LOADS];
@@ -179,13 +217,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(GemmParams 
         if (NT) {
             const int row = f / KQ;
             b_off[i] = (f % KQ) * 4;
-            b_row[i] = p.B + (size_t)min(n0 + row, N - 1) * p.ldb;
+            b_row[i] = w.B + (size_t)min(n0 + row, N - 1) * p.ldb;
             b_lds[i] = row * SA + b_off[i];
             b_krow[i] = 0;
         } else {
             b_krow[i] = f / (BN / 4);
             b_off[i] = n0 + (f % (BN / 4)) * 4;
-            b_row[i] = p.B;
+            b_row[i] = w.B;
             b_lds[i] = b_krow[i] * SBN + (f % (BN / 4)) * 4;
         }
     }
@@ -287,7 +325,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(GemmParams 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = m0 + wm0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
-                    if (row < M) p.C[(size_t)row * p.ldc + col] = acc[i][j][r];
+                    if (row < M) w.C[(size_t)row * w.ldc + col] = acc[i][j][r];
                 }
             }
         }
@@ -382,11 +420,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
     const int wm0 = (wave / WAVES_N) * WM;
     const int wn0 = (wave % WAVES_N) * WN;
 
+    const WorkView w = work_view(p, NT);
     int tm, tn;
-    tile_of_block(p, tm, tn);
+    tile_of_block(p, w.pid, tm, tn);
     const int m0 = tm * BM;
     const int n0 = tn * BN;
-    const int M = p.M, N = p.N, K = p.K;
+    const int M = p.M, N = p.N, K = w.K;
 
     // ---- copy geometry: which global chunk this lane fetches for each of its wave's blocks, as
     // a byte offset from the tile's first row (A) / first row or first k-row (B).  A wave with fewer
@@ -394,8 +433,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
     // place), so every issuing wave issues exactly LPS copies per slab.
     const int grp = wave / NI;
     const int wi = wave % NI;
-    const float* a_tile = p.A + (size_t)m0 * p.lda;
-    const float* b_tile = NT ? p.B + (size_t)n0 * p.ldb : p.B;
+    const float* a_tile = w.A + (size_t)m0 * p.lda;
+    const float* b_tile = NT ? w.B + (size_t)n0 * p.ldb : w.B;
     unsigned a_off[A_LOADS], a_dst[A_LOADS];
     int a_k[A_LOADS];
 #pragma unroll
@@ -590,10 +629,26 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = m0 + wm0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
-                    if (row < M) p.C[(size_t)row * p.ldc + col] = acc[i][j][r];
+                    if (row < M) w.C[(size_t)row * w.ldc + col] = acc[i][j][r];
                 }
             }
         }
+    }
+}
+
+// ---- split-k reduction ---------------------------------------------------------------------------
+
+// C[i][j] = part[0][i][j] + part[1][i][j] + ... in split order (fixed, so results are reproducible)
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ part, int splits,
+                                                            int M, int N, float* __restrict__ C, long ldc)
+{
+    const long long total = (long long)M * N;
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long long)gridDim.x * blockDim.x) {
+        float acc = part[e];
+        for (int s = 1; s < splits; ++s) acc += part[(size_t)s * total + e];
+        const long long i = e / N;
+        C[(size_t)i * ldc + (e - i * N)] = acc;
     }
 }
 
@@ -606,6 +661,7 @@ struct Config {
     void (*dma[2])(GemmParams);       // pipelined kernel, [op]; null if the configuration has none
     int nstage;
     int threads;
+    float eff;                        // measured fraction of the fp32 MFMA peak with every CU busy
     // LDS bytes of the guarded kernel: two buffers of an A slab and a B slab (layouts as in the kernel)
     size_t lds_bytes(int op) const
     {
@@ -614,68 +670,137 @@ struct Config {
         return 2 * (a + b) * sizeof(float);
     }
     size_t lds_bytes_dma() const { return (size_t)nstage * (bm + bn) * bk * sizeof(float); }
+    // workgroups of the pipelined kernel that fit one CU (160 KB of LDS, 2048 threads, 512 VGPRs per lane slot)
+    int wg_per_cu() const
+    {
+        const int by_lds = (int)((160 * 1024) / lds_bytes_dma());
+        const int by_thr = threads >= 512 ? 1 : 2;     // registers: one 8-wave or two 4-wave workgroups
+        const int r = by_lds < by_thr ? by_lds : by_thr;
+        return r < 1 ? 1 : r;
+    }
 };
 
 #define MTNN_GUARDED(BM, BN, BK, WMV, WNV)                                                    \
     {{gemm_kernel<BM, BN, BK, WMV, WNV, false, false>, gemm_kernel<BM, BN, BK, WMV, WNV, false, true>},   \
      {gemm_kernel<BM, BN, BK, WMV, WNV, true, false>, gemm_kernel<BM, BN, BK, WMV, WNV, true, true>}}
 
-// guarded kernel only
-#define MTNN_CFG(BM, BN, BK, WMV, WNV)                                                        \
-    { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV, BM, BN, BK, MTNN_GUARDED(BM, BN, BK, WMV, WNV),   \
-      {nullptr, nullptr}, 0, WMV * WNV * 64 }
-
-// pipelined kernel with NS slab buffers; the guarded kernel of the same tile serves what it cannot
-#define MTNN_CFG_DMA(BM, BN, BK, WMV, WNV, NS)                                                \
-    { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV "_dma" #NS, BM, BN, BK, MTNN_GUARDED(BM, BN, BK, WMV, WNV), \
+// pipelined kernel with NS slab buffers, and the guarded kernel (slab GBK) that serves what it cannot
+#define MTNN_CFG_DMA(BM, BN, BK, WMV, WNV, NS, GBK, EFF)                                      \
+    { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV "_dma" #NS, BM, BN, BK, MTNN_GUARDED(BM, BN, GBK, WMV, WNV), \
       {gemm_dma_kernel<BM, BN, BK, WMV, WNV, false, NS>, gemm_dma_kernel<BM, BN, BK, WMV, WNV, true, NS>}, \
-      NS, WMV * WNV * 64 }
+      NS, WMV * WNV * 64, EFF }
 
 static const Config kConfigs[] = {
-    MTNN_CFG(256, 256, 16, 2, 4),          // 0: 8 waves, wave tile 128 x 64
-    MTNN_CFG(128, 128, 16, 2, 2),          // 1: 4 waves, wave tile 64 x 64
-    MTNN_CFG(64, 64, 16, 2, 2),            // 2: 4 waves, wave tile 32 x 32
-    MTNN_CFG(256, 128, 16, 4, 2),          // 3: 8 waves, wave tile 64 x 64
-    MTNN_CFG(128, 256, 16, 2, 4),          // 4: 8 waves, wave tile 64 x 64
-    MTNN_CFG(32, 256, 16, 1, 4),           // 5: 4 waves, wave tile 32 x 64 (small m)
-    MTNN_CFG(256, 32, 16, 4, 1),           // 6: 4 waves, wave tile 64 x 32 (small n)
-    MTNN_CFG_DMA(256, 256, 16, 4, 2, 2),   // 7: 64 KB of LDS
-    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2),   // 8: 128 KB
-    MTNN_CFG_DMA(256, 256, 32, 2, 4, 2),   // 9
-    MTNN_CFG_DMA(128, 128, 32, 4, 2, 4),   // 10
-    MTNN_CFG_DMA(128, 128, 32, 4, 2, 2),   // 11
-    MTNN_CFG_DMA(128, 128, 64, 4, 2, 2),   // 12: 128 KB
-    MTNN_CFG_DMA(128, 128, 64, 2, 2, 2),   // 13
-    MTNN_CFG_DMA(256, 128, 16, 2, 2, 3),   // 14: 4 waves of 128 x 64, 72 KB: two workgroups per CU
-    MTNN_CFG_DMA(256, 128, 32, 4, 2, 2),   // 15: 96 KB
-    MTNN_CFG_DMA(128, 256, 32, 2, 4, 2),   // 16
-    MTNN_CFG_DMA(64, 64, 32, 2, 2, 4),     // 17: 64 KB
-    MTNN_CFG_DMA(64, 64, 64, 2, 2, 2),     // 18
-    MTNN_CFG_DMA(128, 64, 32, 2, 2, 4),    // 19
+    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2, 16, 0.943f),   // 0: 8 waves of 64 x 128, 128 KB of LDS
+    MTNN_CFG_DMA(256, 128, 16, 2, 2, 3, 16, 0.940f),   // 1: 4 waves of 128 x 64, 72 KB: two per CU
+    MTNN_CFG_DMA(128, 128, 64, 4, 2, 2, 16, 0.900f),   // 2: 8 waves of 32 x 64, 128 KB
+    MTNN_CFG_DMA(64, 64, 64, 2, 2, 2, 16, 0.887f),     // 3: 4 waves of 32 x 32, 64 KB: two per CU
+    MTNN_CFG_DMA(32, 256, 32, 1, 4, 4, 16, 0.670f),    // 4: 4 waves of 32 x 64 (small m)
+    MTNN_CFG_DMA(256, 32, 32, 4, 1, 4, 16, 0.650f),    // 5: 4 waves of 64 x 32 (small n)
+    MTNN_CFG_DMA(128, 256, 32, 2, 4, 2, 16, 0.925f),   // 6: 8 waves of 64 x 64, 96 KB
+    MTNN_CFG_DMA(256, 128, 32, 4, 2, 2, 16, 0.920f),   // 7: 8 waves of 64 x 64, 96 KB
+    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16, 0.897f),    // 8: 4 waves of 64 x 32
+    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16, 0.928f),    // 9: 4 waves of 32 x 64
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
+constexpr int kMaxSplits = 32;
+constexpr int kSplitQuantum = 64;     // k ranges of split-k are multiples of this (every slab size divides it)
 
 int gemm_config_count() { return kNumConfigs; }
 const char* gemm_config_name(int cfg) { return (cfg >= 0 && cfg < kNumConfigs) ? kConfigs[cfg].name : nullptr; }
 
-int gemm_default_config(int /*op*/, int m, int n, int /*k*/)
+// ---- scratch for split-k partial products -------------------------------------------------------
+//
+// One fixed-size buffer per (device, stream), allocated the first time a split-k launch needs it and
+// kept until the process ends; launches on one stream are ordered, so they can share it.  A launch
+// whose partials do not fit, or a ninth stream, simply runs without split-k.
+namespace {
+constexpr size_t kScratchBytes = 64u << 20;
+struct ScratchSlot { int dev; hipStream_t stream; float* ptr; };
+ScratchSlot g_scratch[8];
+int g_scratch_used = 0;
+std::mutex g_scratch_mutex;
+
+float* scratch_for(hipStream_t s)
 {
-    auto tiles = [&](int c) {
-        return (long long)((m + kConfigs[c].bm - 1) / kConfigs[c].bm) * ((n + kConfigs[c].bn - 1) / kConfigs[c].bn);
-    };
-    if (m <= 32) return 5;
-    if (n <= 32) return 6;
-    if (tiles(0) >= 256) return 0;
-    if (tiles(1) >= 128) return 1;
-    if (m <= 64 || n <= 64 || tiles(1) < 32) return 2;
-    return 1;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    for (int i = 0; i < g_scratch_used; ++i)
+        if (g_scratch[i].dev == dev && g_scratch[i].stream == s) return g_scratch[i].ptr;
+    if (g_scratch_used == 8) return nullptr;
+    float* ptr = nullptr;
+    if (hipMalloc(&ptr, kScratchBytes) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    g_scratch[g_scratch_used++] = ScratchSlot{dev, s, ptr};
+    return ptr;
+}
+}  // namespace
+
+// ---- choice of configuration and split count ----------------------------------------------------
+//
+// A small cost model, evaluated for every configuration and split count; the cheapest wins, ties go
+// to the earlier (larger) configuration.  For a candidate: workgroups = tiles x splits are dealt
+// evenly to the 256 CUs; a CU works through its share at the configuration's measured rate, less if
+// it holds fewer workgroups than it could overlap; every workgroup pays a fixed prologue/epilogue;
+// split-k adds the traffic of writing and re-reading the partial products.  The choice depends only
+// on (op, m, n, k), never on timing, so results stay reproducible.
+struct Choice { int cfg; int splits; };
+
+static double predicted_seconds(const Config& c, int m, int n, int k, int splits)
+{
+    const double peak_cu = 157.3e12 / 256.0;
+    const long long tiles = (long long)((m + c.bm - 1) / c.bm) * ((n + c.bn - 1) / c.bn);
+    const long long wgs = tiles * splits;
+    const long long per_cu = (wgs + 255) / 256;
+    int kloc = (k + splits - 1) / splits;
+    kloc = ((kloc + kSplitQuantum - 1) / kSplitQuantum) * kSplitQuantum;
+    if (splits == 1) kloc = k;
+    const int occ = c.wg_per_cu();
+    // a CU that holds a single 4-wave workgroup keeps only one wave per SIMD busy
+    const double solo = (c.threads < 512 && per_cu < occ) ? 0.80 : 1.0;
+    const double wg_flops = 2.0 * c.bm * c.bn * (double)kloc;
+    double t = (double)per_cu * wg_flops / (peak_cu * c.eff * solo);
+    t += 2.5e-6 * (double)((per_cu + occ - 1) / occ);            // prologue + epilogue per round
+    // HBM floor: operands once, result once
+    const double bytes = 4.0 * ((double)m * k + (double)n * k + (double)m * n);
+    if (t < bytes / 5.0e12) t = bytes / 5.0e12;
+    if (splits > 1) t += 4.0e-6 + 0.2e-6 * splits + 4.0 * (double)m * n * (splits + 2) / 4.0e12;
+    return t + 3.0e-6;
 }
 
-int launch_gemm(hipStream_t s, int op, int cfg, int m, int n, int k,
+static Choice choose(int /*op*/, int m, int n, int k, bool allow_split)
+{
+    Choice best = {0, 1};
+    double best_t = 1e30;
+    for (int c = 0; c < kNumConfigs; ++c) {
+        for (int splits = 1; splits <= kMaxSplits; splits *= 2) {
+            if (splits > 1) {
+                if (!allow_split) break;
+                if ((size_t)m * n * splits * sizeof(float) > kScratchBytes) break;
+                if (k / splits < 2 * kSplitQuantum) break;
+            }
+            const double t = predicted_seconds(kConfigs[c], m, n, k, splits);
+            if (t < best_t * 0.999) { best_t = t; best = Choice{c, splits}; }
+        }
+    }
+    return best;
+}
+
+int gemm_default_config(int op, int m, int n, int k) { return choose(op, m, n, k, true).cfg; }
+int gemm_default_splits(int op, int m, int n, int k) { return choose(op, m, n, k, true).splits; }
+
+int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
                 const float* A, long lda, const float* B, long ldb, float* C, long ldc)
 {
-    if (cfg < 0) cfg = gemm_default_config(op, m, n, k);
-    if (cfg >= kNumConfigs || (op != OP_NN && op != OP_NT)) return (int)hipErrorInvalidValue;
+    if (op != OP_NN && op != OP_NT) return (int)hipErrorInvalidValue;
+    if (cfg < 0) {
+        const Choice ch = choose(op, m, n, k, splits <= 0);
+        cfg = ch.cfg;
+        if (splits <= 0) splits = ch.splits;
+    } else if (splits <= 0) {
+        splits = 1;
+    }
+    if (cfg >= kNumConfigs || splits > kMaxSplits) return (int)hipErrorInvalidValue;
     const Config& c = kConfigs[cfg];
     GemmParams p;
     p.A = A; p.B = B; p.C = C;
@@ -685,12 +810,29 @@ int launch_gemm(hipStream_t s, int op, int cfg, int m, int n, int k,
     p.tiles_n = (n + c.bn - 1) / c.bn;
     p.group_m = p.tiles_m < 8 ? p.tiles_m : 8;
     p.num_xcd = 8;
-    const long long total = (long long)p.tiles_m * p.tiles_n;
+    // split-k: equal k ranges, multiples of the quantum; drop splits that would be empty
+    p.splits = 1;
+    p.k_per_split = k;
+    p.part = nullptr;
+    if (splits > 1) {
+        int kps = (k + splits - 1) / splits;
+        kps = ((kps + kSplitQuantum - 1) / kSplitQuantum) * kSplitQuantum;
+        const int eff_splits = (k + kps - 1) / kps;
+        if (eff_splits > 1 && (size_t)m * n * eff_splits * sizeof(float) <= kScratchBytes) {
+            float* part = scratch_for(s);
+            if (part) {
+                p.splits = eff_splits;
+                p.k_per_split = kps;
+                p.part = part;
+            }
+        }
+    }
+    const long long total = (long long)p.tiles_m * p.tiles_n * p.splits;
     if (total > 0x7fffffffLL) return (int)hipErrorInvalidValue;
     const bool vec = (lda % 4 == 0) && (ldb % 4 == 0) &&
                      ((reinterpret_cast<uintptr_t>(A) & 15) == 0) &&
                      ((reinterpret_cast<uintptr_t>(B) & 15) == 0);
-    // the pipelined kernel needs whole 16-byte chunks everywhere (see its preconditions)
+    // the pipelined kernel needs whole 16-byte chunks everywhere (see its preconditions) ...
     // ... and per-lane byte offsets inside a tile that fit 32 bits
     const unsigned long long lim = 1ull << 32;
     const bool off_ok = (unsigned long long)c.bm * (unsigned long long)lda * 4ull < lim &&
@@ -698,7 +840,9 @@ int launch_gemm(hipStream_t s, int op, int cfg, int m, int n, int k,
                                      : (unsigned long long)(c.bk + 1) * (unsigned long long)ldb * 4ull < lim);
     const bool dma_ok = vec && c.dma[op] && (k % 4 == 0) && (op == OP_NT || n % 4 == 0) && off_ok;
     auto kern = dma_ok ? c.dma[op] : c.kern[op][vec ? 1 : 0];
-    const size_t lds = dma_ok ? c.lds_bytes_dma() : c.lds_bytes(op);
+    Config guarded = c;
+    guarded.bk = 16;
+    const size_t lds = dma_ok ? c.lds_bytes_dma() : guarded.lds_bytes(op);
     if (lds > 64 * 1024) {
         // opt in to the large LDS carve-out once per kernel and device
         static bool raised[kNumConfigs][2][3][16] = {};
@@ -713,7 +857,17 @@ int launch_gemm(hipStream_t s, int op, int cfg, int m, int n, int k,
         }
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(c.threads), lds, s, p);
-    return (int)hipGetLastError();
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return (int)err;
+    if (p.splits > 1) {
+        const long long elems = (long long)m * n;
+        long long blocks = (elems + 255) / 256;
+        if (blocks > 2048) blocks = 2048;
+        hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                           p.part, p.splits, m, n, C, ldc);
+        err = hipGetLastError();
+    }
+    return (int)err;
 }
 
 }  // namespace mtnn

@@ -70,15 +70,18 @@ def test_ranges_use_leading_dimensions(L):
 def test_gemm_ex_arguments(L):
     n = L.mtnn_gemm_config_count()
     assert n >= 3
-    assert L.mtnn_gemm_ex(None, 2, 0, 4, 4, 4, A, 4, B, 4, C, 4) == 8
-    assert L.mtnn_gemm_ex(None, 1, n, 4, 4, 4, A, 4, B, 4, C, 4) == 8
-    assert L.mtnn_gemm_ex(None, 1, -2, 4, 4, 4, A, 4, B, 4, C, 4) == 8
-    assert L.mtnn_gemm_ex(None, 1, 0, 4, 4, 4, A, 3, B, 4, C, 4) == 3
+    assert L.mtnn_gemm_ex(None, 2, 0, 1, 4, 4, 4, A, 4, B, 4, C, 4) == 8
+    assert L.mtnn_gemm_ex(None, 1, n, 1, 4, 4, 4, A, 4, B, 4, C, 4) == 8
+    assert L.mtnn_gemm_ex(None, 1, -2, 1, 4, 4, 4, A, 4, B, 4, C, 4) == 8
+    assert L.mtnn_gemm_ex(None, 1, 0, 33, 4, 4, 4, A, 4, B, 4, C, 4) == 8
+    assert L.mtnn_gemm_ex(None, 1, 0, -1, 4, 4, 4, A, 4, B, 4, C, 4) == 8
+    assert L.mtnn_gemm_ex(None, 1, 0, 1, 4, 4, 4, A, 3, B, 4, C, 4) == 3
     names = mt.gemm_configs()
     assert len(set(names)) == n
     for op in (0, 1):
         for shape in [(256, 256, 256), (1024, 4096, 4096), (32, 8192, 8192), (8192, 32, 8192), (1000, 1000, 1000)]:
             assert 0 <= mt.mtnn_gemm_default_config(op, *shape) < n
+            assert 1 <= mt.mtnn_gemm_default_splits(op, *shape) <= 32
     assert mt.mtnn_gemm_default_config(0, 0, 4, 4) == -1
 
 

@@ -14,7 +14,7 @@ from gpu_util import Guarded, check_gemm, dev_matrix
 
 pytestmark = pytest.mark.gpu
 
-NCFG = 20
+NCFG = 10
 
 
 def sync():
@@ -22,13 +22,13 @@ def sync():
     torch.cuda.synchronize()
 
 
-def run(op, cfg, A, B, lda=None, ldb=None, ldc=None, misalign=0):
+def run(op, cfg, A, B, lda=None, ldb=None, ldc=None, misalign=0, splits=0):
     """Run one GEMM through the C ABI; returns the fp32 host result (guard bands verified)."""
     m, k = A.shape
     n = B.shape[0] if op == mt.OP_NT else B.shape[1]
     dA, dB = dev_matrix(A, lda, misalign=misalign), dev_matrix(B, ldb, misalign=2 * misalign)
     out = Guarded(m, n, ldc, misalign=misalign)
-    mt.mtnn_gemm_ex(op, cfg, dA, dB, out.view)
+    mt.mtnn_gemm_ex(op, cfg, dA, dB, out.view, splits=splits)
     sync()
     got, intact = out.host()
     assert intact, "GEMM wrote outside its logical output"
@@ -72,7 +72,7 @@ def test_integer_inputs_are_bit_exact(op, cfg):
 
 
 @pytest.mark.parametrize("op", [mt.OP_NT, mt.OP_NN], ids=["NT", "NN"])
-@pytest.mark.parametrize("cfg", [-1, 0, 1, 5, 6])
+@pytest.mark.parametrize("cfg", [-1, 0, 1, 4, 5])
 def test_odd_leading_dimensions_nan_padding_and_misaligned_bases(op, cfg):
     m, n, k = 131, 262, 45
     A, B = operands(op, m, n, k, 300)
@@ -91,6 +91,27 @@ def test_k_tails(op, k):
     got = run(op, -1, A, B)
     C, S = reference(op, A, B)
     check_gemm(got, C, S, k, f"op{op} k={k}")
+
+
+@pytest.mark.parametrize("op", [mt.OP_NT, mt.OP_NN], ids=["NT", "NN"])
+@pytest.mark.parametrize("cfg,splits", [(0, 2), (2, 3), (3, 4), (3, 32), (4, 5), (5, 8), (-1, 0), (1, 16)])
+@pytest.mark.parametrize("m,n,k", [(70, 92, 1000), (300, 264, 2052), (33, 520, 4099)])
+def test_split_k_against_oracle(op, cfg, splits, m, n, k):
+    A, B = operands(op, m, n, k, 600 + splits, dist="normal")
+    got = run(op, cfg, A, B, splits=splits)
+    C, S = reference(op, A, B)
+    check_gemm(got, C, S, k, f"op{op} cfg{cfg} splits{splits} {m}x{n}x{k}")
+    again = run(op, cfg, A, B, splits=splits)
+    assert again.tobytes() == got.tobytes()            # fixed reduction order
+
+
+def test_split_k_integer_inputs_bit_exact_and_padding():
+    m, n, k = 100, 136, 1536
+    for op in (mt.OP_NT, mt.OP_NN):
+        A, B = operands(op, m, n, k, 650, dist="int")
+        C, _ = reference(op, A, B)
+        got = run(op, 3, A, B, ldc=n + 5, splits=6)
+        assert np.array_equal(got, C.astype(np.float32))
 
 
 def test_degenerate_sizes():
