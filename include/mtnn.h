@@ -87,7 +87,9 @@ MTNN_API int mtnn_tnn(void *stream, int m, int n, int k,
 
 /* MTNN, Algorithm 2: label = mtnn_select(m, n, k); +1 runs NT, -1 runs TNN.
  * Memory rule of Section II: when the workspace is NULL or too small, NT runs whatever the
- * predictor says.  `chosen` (may be NULL) receives +1 or -1 for the path actually run. */
+ * predictor says.  `chosen` (may be NULL) receives +1 or -1 for the path actually run.
+ * Environment: MTNN_FORCE=nt or MTNN_FORCE=tnn (read once per process) replaces the predictor's
+ * answer, for experiments; the memory rule still applies. */
 MTNN_API int mtnn_auto(void *stream, int m, int n, int k,
               const float *A, int lda, const float *B, int ldb, float *C, int ldc,
               void *workspace, size_t workspace_bytes, int *chosen);
@@ -98,7 +100,9 @@ MTNN_API int mtnn_auto(void *stream, int m, int n, int k,
  * m, n, k is <= 0.  Host only, pure, O(trees x depth).  The feature vector is
  * (m, n, k, n*k, m*n, m*k, m*n*k); the margin is the sum of the leaf values reached in each
  * tree (a node sends x left when x[feature] < threshold) and the label is +1 when the margin
- * is >= 0.  With no model loaded the answer is +1 (NT needs no extra memory). */
+ * is >= 0.  With no model loaded the answer is +1 (NT needs no extra memory).  If the environment
+ * variable MTNN_MODEL names a readable model file and no model has been installed yet, the first
+ * call loads it. */
 MTNN_API int mtnn_select(int m, int n, int k);
 
 /* Number of features mtnn_select builds (7) and, into x[0..6], the features themselves. */

@@ -6,6 +6,8 @@
 #include "selector.h"
 
 #include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
 
 namespace {
 
@@ -165,8 +167,16 @@ int mtnn_tnn(void* stream, int m, int n, int k, const float* A, int lda, const f
 int mtnn_auto(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
               float* C, int ldc, void* workspace, size_t workspace_bytes, int* chosen)
 {
-    // Algorithm 2.  The memory rule of Section II overrides the predictor.
-    int label = (m > 0 && n > 0 && k > 0) ? mtnn_select(m, n, k) : 1;
+    // Algorithm 2.  The memory rule of Section II overrides the predictor; the environment variable
+    // MTNN_FORCE=nt|tnn (read once) overrides the predictor for experiments.
+    static const int forced = [] {
+        const char* e = getenv("MTNN_FORCE");
+        if (!e) return 0;
+        if (!strcmp(e, "nt") || !strcmp(e, "NT")) return 1;
+        if (!strcmp(e, "tnn") || !strcmp(e, "TNN")) return -1;
+        return 0;
+    }();
+    int label = (m > 0 && n > 0 && k > 0) ? (forced ? forced : mtnn_select(m, n, k)) : 1;
     if (label == -1 && (!workspace || workspace_bytes < mtnn_tnn_workspace_bytes(n, k))) label = 1;
     if (chosen) *chosen = label;
     if (label == -1)

@@ -13,6 +13,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
 #include <mutex>
@@ -223,8 +224,23 @@ namespace {
 std::mutex g_model_mutex;
 std::shared_ptr<const Model> g_model;   // null = no model: always NT
 
+// first use: a model named by the environment variable MTNN_MODEL is loaded if nothing else has
+// been installed; a missing or malformed file leaves "always NT" in place
+std::once_flag g_env_once;
+void load_from_env()
+{
+    const char* path = std::getenv("MTNN_MODEL");
+    if (!path || !*path) return;
+    Model m;
+    if (!load_model(path, m)) return;
+    auto p = std::make_shared<const Model>(std::move(m));
+    std::lock_guard<std::mutex> lock(g_model_mutex);
+    if (!g_model) g_model = std::move(p);
+}
+
 std::shared_ptr<const Model> current()
 {
+    std::call_once(g_env_once, load_from_env);
     std::lock_guard<std::mutex> lock(g_model_mutex);
     return g_model;
 }

@@ -211,3 +211,25 @@ def test_config3_sweep_corners_sampled_rows(m, n, k):
     rows = sorted(set([0, 1, m - 2, m - 1] + [r for r in (255, 256, 257, 4095, 4096) if r < m] +
                       [int(x) for x in I.uniform_ints(seed, 9, 24, 0, m - 1)]))
     check_all_paths(m, n, k, seed, "uniform", rows=np.array(rows))
+
+
+def test_split_k_on_two_streams_uses_separate_scratch():
+    """Split-k partial products live in a scratch buffer per stream: launches interleaved on two
+    streams must not disturb each other."""
+    import torch
+    m, n, k = 96, 200, 4096
+    A1, B1 = operands(mt.OP_NT, m, n, k, 700, dist="normal")
+    A2, B2 = operands(mt.OP_NT, m, n, k, 701, dist="normal")
+    C1, S1 = reference(mt.OP_NT, A1, B1)
+    C2, S2 = reference(mt.OP_NT, A2, B2)
+    d = [dev_matrix(x) for x in (A1, B1, A2, B2)]
+    o1 = torch.empty((m, n), device="cuda")
+    o2 = torch.empty((m, n), device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(20):
+        mt.mtnn_gemm_ex(mt.OP_NT, 3, d[0], d[1], o1, stream=s1, splits=8)
+        mt.mtnn_gemm_ex(mt.OP_NT, 3, d[2], d[3], o2, stream=s2, splits=8)
+    torch.cuda.synchronize()
+    check_gemm(o1.cpu().numpy(), C1, S1, k, "stream 1")
+    check_gemm(o2.cpu().numpy(), C2, S2, k, "stream 2")

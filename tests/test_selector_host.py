@@ -141,3 +141,85 @@ def test_trainer_argument_checks():
     assert L.mtnn_gbdt_train(4, 2, None, y.ctypes.data, 8, 8, 1.0, 0.0, 1.0, 1.0) == 2
     X[0, 0] = np.nan
     assert L.mtnn_gbdt_train(4, 2, X.ctypes.data, y.ctypes.data, 8, 8, 1.0, 0.0, 1.0, 1.0) == 8
+
+
+def parse_model_file(path):
+    """Independent reader of the model text format (C99 hex floats), for the oracle's evaluator."""
+    lines = [l.split() for l in open(path).read().splitlines() if l.strip()]
+    assert lines[0] == ["mtnn-gbdt", "1"]
+    nfeat = int(lines[1][1])
+    ntrees = int(lines[2][1])
+    pos = 3
+    trees = []
+    for t in range(ntrees):
+        assert lines[pos][0] == "tree" and int(lines[pos][1]) == t
+        n = int(lines[pos][3])
+        pos += 1
+        rows = []
+        for _ in range(n):
+            f, thr, l, r, v = lines[pos]
+            rows.append((int(f), float.fromhex(thr), int(l), int(r), float.fromhex(v)))
+            pos += 1
+        trees.append(rows)
+    return nfeat, trees
+
+
+def flat_margin(trees, x):
+    total = 0.0
+    for rows in trees:
+        at = 0
+        while rows[at][0] >= 0:
+            at = rows[at][2] if x[rows[at][0]] < rows[at][1] else rows[at][3]
+        total += rows[at][4]
+    return total
+
+
+def test_shipped_model_agrees_with_an_independent_evaluator_on_grid_and_random_shapes():
+    if not os.path.exists(mt.DEFAULT_MODEL):
+        pytest.skip("no shipped model")
+    mt.mtnn_load_model(mt.DEFAULT_MODEL)
+    nfeat, trees = parse_model_file(mt.DEFAULT_MODEL)
+    assert nfeat == 7 and len(trees) <= 8
+    assert mt.model_trees() == trees
+    shapes = [(m, n, k) for (m, n, k, _s) in I.sweep_shapes()]
+    shapes += [tuple(int(v) for v in row) for row in I.uniform_ints(78, 0, 30000, 1, 70000).reshape(-1, 3)]
+    for s in shapes:
+        want = 1 if flat_margin(trees, S.features(*s)) >= 0.0 else -1
+        assert mt.mtnn_select(*s) == want
+
+
+def test_trained_on_the_shipped_sweep_table_trainer_parity():
+    """The library's trainer and the oracle's, on the real MI355X timing table."""
+    from paper_1702_03192_amd import selector_data as sd
+    if not os.path.exists(sd.SWEEP_CSV):
+        pytest.skip("no shipped sweep table")
+    rows = sd.load_sweep()
+    shapes = [(r["m"], r["n"], r["k"]) for r in rows]
+    labels = [S.label_from_times(r["t_nt"], r["t_tnn"]) for r in rows]
+    assert labels == [sd.label_of(r["t_nt"], r["t_tnn"]) for r in rows]
+    if len(set(labels)) < 2:
+        pytest.skip("single-class table")
+    mt.mtnn_train_selector(shapes, labels)
+    ref = S.train_gbdt(np.array([S.features(*s) for s in shapes]), labels)
+    same_trees(mt.model_trees(), S.flatten(ref))
+    # and the shipped model file is this model
+    if os.path.exists(mt.DEFAULT_MODEL):
+        assert parse_model_file(mt.DEFAULT_MODEL)[1] == mt.model_trees()
+
+
+def test_env_model_is_loaded_on_first_use(tmp_path):
+    import subprocess
+    import sys
+    rows, lab = synthetic_table()
+    mt.mtnn_train_selector(rows, lab)
+    path = str(tmp_path / "env.model")
+    mt.mtnn_save_model(path)
+    want = [mt.mtnn_select(*r) for r in rows[:64]]
+    code = ("import ctypes, torch; L = ctypes.CDLL(%r); "
+            "print([L.mtnn_select(*r) for r in %r])" % (mt.LIB_PATH, rows[:64]))
+    out = subprocess.run([sys.executable, "-c", code], env=dict(os.environ, MTNN_MODEL=path),
+                         capture_output=True, text=True, check=True).stdout
+    assert eval(out.strip().splitlines()[-1]) == want
+    out = subprocess.run([sys.executable, "-c", code], env=dict(os.environ, MTNN_MODEL=str(tmp_path / "none")),
+                         capture_output=True, text=True, check=True).stdout
+    assert eval(out.strip().splitlines()[-1]) == [1] * 64
