@@ -842,7 +842,15 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
     auto kern = dma_ok ? c.dma[op] : c.kern[op][vec ? 1 : 0];
     Config guarded = c;
     guarded.bk = 16;
-    const size_t lds = dma_ok ? c.lds_bytes_dma() : guarded.lds_bytes(op);
+    size_t lds = dma_ok ? c.lds_bytes_dma() : guarded.lds_bytes(op);
+    if (dma_ok) {
+        // Ask for at least 1/wg_per_cu of the CU's LDS: no CU can then take more workgroups than the
+        // cost model assumed, so a grid of exactly 256 x wg_per_cu workgroups spreads evenly instead
+        // of piling three on some CUs and one on others.
+        const size_t share = ((160 * 1024) / (size_t)c.wg_per_cu()) & ~(size_t)1023;
+        const size_t floor_bytes = share > 1024 ? share - 1024 : share;
+        if (lds < floor_bytes) lds = floor_bytes;
+    }
     if (lds > 64 * 1024) {
         // opt in to the large LDS carve-out once per kernel and device
         static bool raised[kNumConfigs][2][3][16] = {};
