@@ -757,7 +757,7 @@ static double predicted_seconds(const Config& c, int m, int n, int k, int splits
     if (splits == 1) kloc = k;
     const int occ = c.wg_per_cu();
     // a CU that holds a single 4-wave workgroup keeps only one wave per SIMD busy
-    const double solo = (c.threads < 512 && per_cu < occ) ? 0.80 : 1.0;
+    const double solo = (c.threads < 512 && per_cu < occ) ? 0.90 : 1.0;
     const double wg_flops = 2.0 * c.bm * c.bn * (double)kloc;
     double t = (double)per_cu * wg_flops / (peak_cu * c.eff * solo);
     t += 2.5e-6 * (double)((per_cu + occ - 1) / occ);            // prologue + epilogue per round
