@@ -186,6 +186,10 @@ MTNN_API size_t mtnn_fc_workspace_bytes(int num_layers, const int *dims, int bat
 /* forward (NT per layer via the selected path) -> loss -> backward (dW = transpose + NN, dX = NN)
  * -> SGD update, all enqueued on `stream`. */
 MTNN_API int mtnn_fc_train_step(void *stream, const mtnn_fc_step_desc *desc);
+/* The forward half alone: activations, logits (if requested) and the loss (its gradient w.r.t. the
+ * logits is left in the workspace); W, b, dW, db are not written and dW / db may be NULL.  Used to
+ * split a step's time into forward and backward as in the paper's Table X. */
+MTNN_API int mtnn_fc_forward(void *stream, const mtnn_fc_step_desc *desc);
 
 /* The elementwise / reduction steps of the training step, exported for tests:
  * Z[i][j] += b[j] (then ReLU if relu != 0), in place, Z batch x width dense. */

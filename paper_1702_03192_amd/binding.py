@@ -68,6 +68,7 @@ SIGNATURES = {
     "mtnn_gemm_ex": (_c_int, [_c_vp, _c_int, _c_int, _c_int] + _GEMM[1:]),
     "mtnn_fc_workspace_bytes": (_c_sz, [_c_int, _p_int, _c_int]),
     "mtnn_fc_train_step": (_c_int, [_c_vp, ctypes.POINTER(FcStepDesc)]),
+    "mtnn_fc_forward": (_c_int, [_c_vp, ctypes.POINTER(FcStepDesc)]),
     "mtnn_fc_bias_act": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp, _c_int]),
     "mtnn_fc_softmax_xent": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp, _c_vp, _c_vp, _c_vp]),
     "mtnn_fc_relu_backward": (_c_int, [_c_vp, _c_ll, _c_vp, _c_vp]),
@@ -308,6 +309,10 @@ def make_fc_desc(dims, batch, X, labels, W, b, dW, db, loss, workspace, lr, forw
 
 def mtnn_fc_train_step(desc, stream=None) -> None:
     _check(lib().mtnn_fc_train_step(_stream(stream), ctypes.byref(desc)), "mtnn_fc_train_step")
+
+
+def mtnn_fc_forward(desc, stream=None) -> None:
+    _check(lib().mtnn_fc_forward(_stream(stream), ctypes.byref(desc)), "mtnn_fc_forward")
 
 
 def mtnn_fc_bias_act(Z, b, relu: bool, stream=None):

@@ -189,16 +189,19 @@ size_t mtnn_fc_workspace_bytes(int num_layers, const int* dims, int batch)
     return total;
 }
 
-int mtnn_fc_train_step(void* stream, const mtnn_fc_step_desc* d)
+static int fc_run(void* stream, const mtnn_fc_step_desc* d, bool forward_only)
 {
     if (!d) return MTNN_ERR_NULL;
     const int L = d->num_layers;
     if (L <= 0 || L > 64 || d->batch <= 0 || !d->dims) return MTNN_ERR_DIM;
     for (int l = 0; l <= L; ++l)
         if (d->dims[l] <= 0) return MTNN_ERR_DIM;
-    if (!d->X || !d->labels || !d->W || !d->b || !d->dW || !d->db || !d->loss || !d->workspace) return MTNN_ERR_NULL;
-    for (int l = 0; l < L; ++l)
-        if (!d->W[l] || !d->b[l] || !d->dW[l] || !d->db[l]) return MTNN_ERR_NULL;
+    if (!d->X || !d->labels || !d->W || !d->b || !d->loss || !d->workspace) return MTNN_ERR_NULL;
+    if (!forward_only && (!d->dW || !d->db)) return MTNN_ERR_NULL;
+    for (int l = 0; l < L; ++l) {
+        if (!d->W[l] || !d->b[l]) return MTNN_ERR_NULL;
+        if (!forward_only && (!d->dW[l] || !d->db[l])) return MTNN_ERR_NULL;
+    }
     if (d->forward_mode != 0 && d->forward_mode != 1 && d->forward_mode != -1) return MTNN_ERR_ARG;
     if (d->workspace_bytes < mtnn_fc_workspace_bytes(L, d->dims, d->batch)) return MTNN_ERR_WORKSPACE;
 
@@ -246,6 +249,7 @@ int mtnn_fc_train_step(void* stream, const mtnn_fc_step_desc* d)
     float* dNext = dB;
     st = mtnn_fc_softmax_xent(stream, batch, dims[L], H[L], d->labels, dZ, row_loss, d->loss);
     if (st != MTNN_OK) return st;
+    if (forward_only) return MTNN_OK;
     // backward, last layer first
     for (int l = L - 1; l >= 0; --l) {
         const int in = dims[l], out = dims[l + 1];
@@ -271,6 +275,10 @@ int mtnn_fc_train_step(void* stream, const mtnn_fc_step_desc* d)
     }
     return MTNN_OK;
 }
+
+int mtnn_fc_train_step(void* stream, const mtnn_fc_step_desc* d) { return fc_run(stream, d, false); }
+
+int mtnn_fc_forward(void* stream, const mtnn_fc_step_desc* d) { return fc_run(stream, d, true); }
 
 int mtnn_copy_rows(void* stream, int rows, int cols, const float* in, float* out)
 {

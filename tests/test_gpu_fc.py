@@ -153,3 +153,35 @@ def test_elementwise_steps_against_numpy():
     assert np.allclose(out.cpu().numpy(), want / 50, rtol=1e-5, atol=1e-7)
     assert np.allclose(rl.cpu().numpy(), -lp[np.arange(50), labels], rtol=1e-5, atol=1e-6)
     assert abs(ml.item() + lp[np.arange(50), labels].mean()) < 1e-5
+
+
+@pytest.mark.parametrize("dims,batch", [([784, 2048, 1024, 10], 128), ([784, 2048, 2048, 2048, 1024, 10], 64)],
+                         ids=["mnist-2-hidden", "mnist-4-hidden"])
+def test_table_ix_mnist_sized_nets(dims, batch):
+    check_step(dims, batch, 5400 + len(dims), 0)
+
+
+def test_table_ix_synthetic_wide_net():
+    # 26752 inputs and outputs, two hidden layers of 4096 (Table IX), a small mini-batch
+    check_step([26752, 4096, 4096, 26752], 32, 5500, 0)
+
+
+def test_forward_only_entry_matches_the_step_and_leaves_the_weights():
+    import torch
+    dims, batch = [100, 200, 150, 10], 64
+    X, labels, W, b = make_net(dims, batch, 5600)
+    full = run_step(dims, batch, X, labels, W, b, 0.01, 1)
+    dX = torch.from_numpy(X).cuda()
+    dl = torch.from_numpy(labels).cuda()
+    dW_ = [torch.from_numpy(w.copy()).cuda() for w in W]
+    db_ = [torch.from_numpy(v.copy()).cuda() for v in b]
+    loss = torch.full((1,), float("nan"), device="cuda")
+    logits = torch.empty((batch, dims[-1]), device="cuda")
+    ws = torch.empty(mt.mtnn_fc_workspace_bytes(dims, batch), dtype=torch.uint8, device="cuda")
+    desc, keep = mt.make_fc_desc(dims, batch, dX, dl, dW_, db_, dW_, db_, loss, ws, 0.01, 1, logits)
+    mt.mtnn_fc_forward(desc)
+    torch.cuda.synchronize()
+    assert float(loss.item()) == full["loss"]
+    assert logits.cpu().numpy().tobytes() == full["logits"].tobytes()
+    for l in range(3):
+        assert dW_[l].cpu().numpy().tobytes() == W[l].tobytes()
