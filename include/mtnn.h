@@ -105,6 +105,10 @@ MTNN_API int mtnn_auto(void *stream, int m, int n, int k,
  * call loads it. */
 MTNN_API int mtnn_select(int m, int n, int k);
 
+/* mtnn_select over `count` (m, n, k) triples (HOST arrays; labels[i] as mtnn_select would return,
+ * evaluated without the memo). */
+MTNN_API int mtnn_select_batch(int count, const int *mnk, int *labels);
+
 /* Number of features mtnn_select builds (7) and, into x[0..6], the features themselves. */
 MTNN_API int mtnn_num_features(void);
 MTNN_API int mtnn_features(int m, int n, int k, double *x);

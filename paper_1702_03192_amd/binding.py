@@ -49,6 +49,7 @@ SIGNATURES = {
     "mtnn_tnn": (_c_int, _GEMM + [_c_vp, _c_sz]),
     "mtnn_auto": (_c_int, _GEMM + [_c_vp, _c_sz, _p_int]),
     "mtnn_select": (_c_int, [_c_int, _c_int, _c_int]),
+    "mtnn_select_batch": (_c_int, [_c_int, _c_vp, _c_vp]),
     "mtnn_num_features": (_c_int, []),
     "mtnn_features": (_c_int, [_c_int, _c_int, _c_int, _p_dbl]),
     "mtnn_load_model": (_c_int, [ctypes.c_char_p]),
@@ -217,6 +218,15 @@ def mtnn_auto(A, B, C, workspace=None, stream=None) -> int:
 
 def mtnn_select(m: int, n: int, k: int) -> int:
     return int(lib().mtnn_select(m, n, k))
+
+
+def mtnn_select_batch(shapes):
+    """Labels for many (m, n, k) at once (one library call)."""
+    import numpy as np
+    mnk = np.ascontiguousarray(shapes, dtype=np.int32).reshape(-1, 3)
+    out = np.empty(mnk.shape[0], dtype=np.int32)
+    _check(lib().mtnn_select_batch(mnk.shape[0], mnk.ctypes.data, out.ctypes.data), "mtnn_select_batch")
+    return out
 
 
 def mtnn_features(m: int, n: int, k: int):

@@ -282,6 +282,24 @@ int mtnn_select(int m, int n, int k)
     return label;
 }
 
+int mtnn_select_batch(int count, const int* mnk, int* labels)
+{
+    if (count < 0) return MTNN_ERR_DIM;
+    if (count == 0) return MTNN_OK;
+    if (!mnk || !labels) return MTNN_ERR_NULL;
+    auto model = mtnn::current();
+    const bool usable = model && model->num_features == mtnn::kSelectorFeatures;
+    for (int i = 0; i < count; ++i) {
+        const int m = mnk[3 * i], n = mnk[3 * i + 1], k = mnk[3 * i + 2];
+        if (m <= 0 || n <= 0 || k <= 0) { labels[i] = 0; continue; }
+        if (!usable) { labels[i] = 1; continue; }
+        double x[mtnn::kSelectorFeatures];
+        mtnn::selector_features(m, n, k, x);
+        labels[i] = mtnn::model_margin(*model, x) >= 0.0 ? 1 : -1;
+    }
+    return MTNN_OK;
+}
+
 int mtnn_load_model(const char* path)
 {
     if (!path) return MTNN_ERR_NULL;

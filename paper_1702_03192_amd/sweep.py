@@ -28,10 +28,19 @@ FIELDS = ["m", "n", "k", "seed", "t_nt", "t_nt_min", "t_tnn", "t_tnn_min", "t_tr
           "t_tnn_alloc", "nt_cfg", "nn_cfg"]
 
 
-def _time_batches(fn, stream, samples, min_batch_us):
+def _time_batches(fn, stream, samples, min_batch_us, budget_s=None):
+    """Median and minimum seconds per call.  budget_s (optional) caps the time spent on one path:
+    long-running calls get fewer warm-ups and samples (never fewer than 2 samples)."""
     import torch
-    for _ in range(3):
-        fn()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    fn()                                                     # first warm-up, timed to size the rest
+    b.record(stream)
+    torch.cuda.synchronize()
+    first = a.elapsed_time(b) * 1e-3                         # s
+    if budget_s is None or first * 4 < budget_s:
+        for _ in range(2):
+            fn()
     torch.cuda.synchronize()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record(stream)
@@ -40,6 +49,8 @@ def _time_batches(fn, stream, samples, min_batch_us):
     torch.cuda.synchronize()
     once = max(a.elapsed_time(b) * 1e3, 1.0)                 # us
     reps = max(1, min(1000, int(min_batch_us / once + 0.999)))
+    if budget_s is not None:
+        samples = max(2, min(samples, int(budget_s / (once * 1e-6 * reps))))
     per_call = []
     for _ in range(samples):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -52,7 +63,21 @@ def _time_batches(fn, stream, samples, min_batch_us):
     return statistics.median(per_call), min(per_call)
 
 
-def collect(out_path, samples, min_batch_us, limit=None):
+PAPER_SIZES = tuple(2 ** i for i in range(7, 17))            # Section IV-A: S = {2^7, ..., 2^16}
+
+
+def paper_shapes():
+    """The paper's 1000 shapes, smallest first, with a per-shape seed."""
+    out = []
+    for im, m in enumerate(PAPER_SIZES):
+        for in_, n in enumerate(PAPER_SIZES):
+            for ik, k in enumerate(PAPER_SIZES):
+                out.append((m, n, k, 20000 + 100 * im + 10 * in_ + ik))
+    out.sort(key=lambda s: (s[0] * s[1] * s[2], s))
+    return out
+
+
+def collect(out_path, samples, min_batch_us, limit=None, grid="bench", budget_s=None, mem_limit_gib=None):
     import torch
     from . import binding as mt
     from . import inputs
@@ -66,9 +91,11 @@ def collect(out_path, samples, min_batch_us, limit=None):
                 done.add((int(rec["m"]), int(rec["n"]), int(rec["k"])))
     new_file = not os.path.exists(out_path)
     os.makedirs(os.path.dirname(os.path.abspath(out_path)), exist_ok=True)
-    shapes = inputs.sweep_shapes()
+    shapes = paper_shapes() if grid == "paper" else inputs.sweep_shapes()
     if limit:
         shapes = shapes[:limit]
+    free_b, total_b = torch.cuda.mem_get_info()
+    mem_limit = (mem_limit_gib * (1 << 30)) if mem_limit_gib else 0.9 * total_b
     cfgs = mt.gemm_configs()
     gen = torch.Generator(device="cuda")
     with open(out_path, "a", newline="") as f:
@@ -78,9 +105,18 @@ def collect(out_path, samples, min_batch_us, limit=None):
         for idx, (m, n, k, seed) in enumerate(shapes):
             if (m, n, k) in done:
                 continue
+            # Section IV-A drops the samples that do not fit in memory: A, B, C, the B^T workspace
+            # and the second B^T buffer of the separate transpose / NN timings
+            need = 4.0 * (m * k + 3.0 * n * k + m * n)
+            if need > mem_limit:
+                print(f"[sweep] skip ({m},{n},{k}): needs {need / 2 ** 30:.1f} GiB", flush=True)
+                continue
+            big = need > 8 * (1 << 30)
+            if big:
+                torch.cuda.empty_cache()
             gen.manual_seed(seed)                             # uniform[-1, 1) operands, seeded per shape
-            A = torch.rand((m, k), generator=gen, device="cuda") * 2 - 1
-            B = torch.rand((n, k), generator=gen, device="cuda") * 2 - 1
+            A = torch.rand((m, k), generator=gen, device="cuda").mul_(2).sub_(1)
+            B = torch.rand((n, k), generator=gen, device="cuda").mul_(2).sub_(1)
             C = torch.empty((m, n), dtype=torch.float32, device="cuda")
             Bt = torch.empty((k, n), dtype=torch.float32, device="cuda")
             ws = torch.empty(mt.mtnn_tnn_workspace_bytes(n, k), dtype=torch.uint8, device="cuda")
@@ -91,18 +127,22 @@ def collect(out_path, samples, min_batch_us, limit=None):
                 mt.mtnn_tnn(A, B, C, w)
                 del w
 
-            t_nt, t_nt_min = _time_batches(lambda: mt.mtnn_nt(A, B, C), stream, samples, min_batch_us)
-            t_tnn, t_tnn_min = _time_batches(lambda: mt.mtnn_tnn(A, B, C, ws), stream, samples, min_batch_us)
-            t_tr, _ = _time_batches(lambda: mt.mtnn_transpose(B, Bt), stream, samples, min_batch_us)
-            t_nn, _ = _time_batches(lambda: mt.mtnn_nn(A, Bt, C), stream, samples, min_batch_us)
-            t_al, _ = _time_batches(tnn_alloc, stream, max(5, samples // 4), min_batch_us)
+            t_nt, t_nt_min = _time_batches(lambda: mt.mtnn_nt(A, B, C), stream, samples, min_batch_us, budget_s)
+            t_tnn, t_tnn_min = _time_batches(lambda: mt.mtnn_tnn(A, B, C, ws), stream, samples, min_batch_us, budget_s)
+            t_tr, _ = _time_batches(lambda: mt.mtnn_transpose(B, Bt), stream, samples, min_batch_us, budget_s)
+            if budget_s is not None and t_nt > budget_s / 8:
+                t_nn = t_tnn - t_tr                           # long shapes: the difference stands in
+                t_al = float("nan")
+            else:
+                t_nn, _ = _time_batches(lambda: mt.mtnn_nn(A, Bt, C), stream, samples, min_batch_us, budget_s)
+                t_al, _ = _time_batches(tnn_alloc, stream, max(5, samples // 4), min_batch_us, budget_s)
             wr.writerow({"m": m, "n": n, "k": k, "seed": seed, "t_nt": "%.9g" % t_nt, "t_nt_min": "%.9g" % t_nt_min,
                          "t_tnn": "%.9g" % t_tnn, "t_tnn_min": "%.9g" % t_tnn_min, "t_transpose": "%.9g" % t_tr,
                          "t_nn": "%.9g" % t_nn, "t_tnn_alloc": "%.9g" % t_al,
                          "nt_cfg": cfgs[mt.mtnn_gemm_default_config(mt.OP_NT, m, n, k)],
                          "nn_cfg": cfgs[mt.mtnn_gemm_default_config(mt.OP_NN, m, n, k)]})
             f.flush()
-            if idx % 16 == 0:
+            if idx % 16 == 0 or t_nt > 0.05:
                 print(f"[sweep] {idx + 1}/{len(shapes)} ({m},{n},{k}) nt {t_nt * 1e6:.1f} us tnn {t_tnn * 1e6:.1f} us",
                       flush=True)
             del A, B, C, Bt, ws
@@ -133,13 +173,17 @@ def main(argv=None):
     c.add_argument("--samples", type=int, default=20)
     c.add_argument("--min-batch-us", type=float, default=200.0)
     c.add_argument("--limit", type=int, default=None)
+    c.add_argument("--grid", choices=["bench", "paper"], default="bench",
+                   help="bench: {64..8192}^3 (512 shapes); paper: {2^7..2^16}^3 (1000 shapes, Section IV-A)")
+    c.add_argument("--budget-s", type=float, default=None, help="cap on the time spent timing one path of one shape")
+    c.add_argument("--mem-limit-gib", type=float, default=None, help="drop shapes needing more device memory")
     t = sub.add_parser("train")
     t.add_argument("--csv", required=True)
     t.add_argument("--model", required=True)
     t.add_argument("--report", default=None)
     args = ap.parse_args(argv)
     if args.cmd == "collect":
-        collect(args.out, args.samples, args.min_batch_us, args.limit)
+        collect(args.out, args.samples, args.min_batch_us, args.limit, args.grid, args.budget_s, args.mem_limit_gib)
     else:
         train(args.csv, args.model, args.report)
     return 0

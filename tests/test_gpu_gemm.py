@@ -233,3 +233,43 @@ def test_split_k_on_two_streams_uses_separate_scratch():
     torch.cuda.synchronize()
     check_gemm(o1.cpu().numpy(), C1, S1, k, "stream 1")
     check_gemm(o2.cpu().numpy(), C2, S2, k, "stream 2")
+
+
+@pytest.mark.parametrize("which", ["A_rows", "B_rows", "C_elems"])
+def test_offsets_beyond_2_to_31_elements(which):
+    """Row offsets (row x ld) past 2^31 elements in A, in B and in C: 64-bit index arithmetic.
+    Operands are drawn on the device by torch's seeded generator (not by this library) and only the
+    sampled rows travel to the host for the oracle."""
+    import torch
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(31337)
+    if which == "A_rows":
+        m, n, k = 36000, 128, 65536          # A: 2.36e9 elements
+    elif which == "B_rows":
+        m, n, k = 128, 36000, 65536          # B: 2.36e9 elements
+    else:
+        m, n, k = 48000, 48000, 64           # C: 2.30e9 elements
+    A = torch.rand((m, k), generator=gen, device="cuda").mul_(2).sub_(1)
+    B = torch.rand((n, k), generator=gen, device="cuda").mul_(2).sub_(1)
+    C = torch.full((m, n), float("nan"), device="cuda")
+    ws = torch.empty(mt.mtnn_tnn_workspace_bytes(n, k), dtype=torch.uint8, device="cuda")
+    rows = sorted({0, 1, m - 1, m - 2, m // 2, 32768 if m > 32768 else 5, 32769 if m > 32769 else 6, 35999 if m > 35999 else 7})
+    cols = sorted({0, 1, n - 1, n - 2, n // 2, 32768 if n > 32768 else 5, 35999 if n > 35999 else 7})
+    hA = A[rows].cpu().numpy()
+    hB = B[cols].cpu().numpy()
+    Cref, Sref = oracle.nt_ref(hA, hB, with_bound=True)
+    for name in ("nt", "tnn"):
+        C.fill_(float("nan"))
+        if name == "nt":
+            mt.mtnn_nt(A, B, C)
+        else:
+            mt.mtnn_tnn(A, B, C, ws)
+        sync()
+        got = C[rows][:, cols].cpu().numpy()
+        check_gemm(got, Cref, Sref, k, f"{which} {name}")
+    # spot-check that the far corner of the transposed B in the workspace is right
+    bt = ws[: n * k * 4].view(torch.float32).view(k, n)
+    assert torch.equal(bt[k - 1, n - 3:], B[n - 3:, k - 1])
+    assert torch.equal(bt[:4, n - 1], B[n - 1, :4])
+    del A, B, C, ws
+    torch.cuda.empty_cache()

@@ -223,3 +223,38 @@ def test_env_model_is_loaded_on_first_use(tmp_path):
     out = subprocess.run([sys.executable, "-c", code], env=dict(os.environ, MTNN_MODEL=str(tmp_path / "none")),
                          capture_output=True, text=True, check=True).stdout
     assert eval(out.strip().splitlines()[-1]) == [1] * 64
+
+
+def test_select_batch_equals_select():
+    rows, lab = synthetic_table()
+    mt.mtnn_train_selector(rows, lab)
+    shapes = [tuple(int(v) for v in row) for row in I.uniform_ints(79, 0, 3000, -2, 9000).reshape(-1, 3)]
+    got = mt.mtnn_select_batch(shapes)
+    assert list(got) == [mt.mtnn_select(*s) for s in shapes]
+    assert 0 in got                                         # non-positive sizes answer 0
+    mt.mtnn_unload_model()
+    assert set(mt.mtnn_select_batch([(5, 5, 5), (0, 1, 1)])) == {1, 0}
+    assert mt.lib().mtnn_select_batch(-1, None, None) == 1
+    assert mt.lib().mtnn_select_batch(2, None, None) == 2
+
+
+def test_classifier_study_runs_on_a_synthetic_table(tmp_path):
+    import csv
+    import json
+    from paper_1702_03192_amd import classifier_study, sweep
+    rows, lab = synthetic_table()
+    p = tmp_path / "t.csv"
+    with open(p, "w", newline="") as f:
+        wr = csv.DictWriter(f, fieldnames=sweep.FIELDS)
+        wr.writeheader()
+        for (m, n, k), l in zip(rows, lab):
+            wr.writerow({"m": m, "n": n, "k": k, "seed": 0, "t_nt": 1.0 if l == 1 else 2.0, "t_nt_min": 1.0,
+                         "t_tnn": 1.5, "t_tnn_min": 1.5, "t_transpose": 0.1, "t_nn": 1.4, "t_tnn_alloc": 1.6,
+                         "nt_cfg": "a", "nn_cfg": "b"})
+    out = tmp_path / "r.json"
+    classifier_study.main(["--csv", str(p), "--out", str(out)])
+    rep = json.load(open(out))
+    assert rep["samples"] == 512 and len(rep["training_size_curve"]) == 19
+    g = rep["classifiers"]["GBDT (8 trees, depth 8)"]
+    assert g["cv5_accuracy"] >= rep["classifiers"]["majority rule"]["cv5_accuracy"] - 0.02
+    assert rep["training_size_curve"][-1]["accuracy_on_all"] >= rep["training_size_curve"][0]["accuracy_on_all"] - 0.01
