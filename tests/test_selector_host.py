@@ -229,6 +229,7 @@ def test_select_batch_equals_select():
     rows, lab = synthetic_table()
     mt.mtnn_train_selector(rows, lab)
     shapes = [tuple(int(v) for v in row) for row in I.uniform_ints(79, 0, 3000, -2, 9000).reshape(-1, 3)]
+    shapes += [(0, 5, 5), (7, -1, 3)]
     got = mt.mtnn_select_batch(shapes)
     assert list(got) == [mt.mtnn_select(*s) for s in shapes]
     assert 0 in got                                         # non-positive sizes answer 0
