@@ -151,6 +151,42 @@ __device__ __forceinline__ void tile_of_block(const GemmParams& p, int pid, int&
     tn = in_band / rows_here;
 }
 
+// ---- epilogue: accumulators -> C -------------------------------------------------------------
+//
+// Register r of lane l of a 32x32 block is row 8*(r/4) + 4*(l/32) + r%4, column l%32: one store
+// instruction writes two full 128-byte row segments.  Results are not read again by the kernel, so
+// the stores are non-temporal; tiles entirely inside C skip the per-element guards.
+template <int TM, int TN>
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], float* __restrict__ C, long ldc,
+                                           int M, int N, int row0, int col0, int lr, int lh)
+{
+    if (row0 + TM * 32 <= M && col0 + TN * 32 <= N) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float* dst = C + (size_t)(row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4)) * ldc + col0 + lr;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) __builtin_nontemporal_store(acc[i][j][r], dst + j * 32);
+            }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = col0 + j * 32 + lr;
+            if (col < N) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
+                    if (row < M) C[(size_t)row * ldc + col] = acc[i][j][r];
+                }
+            }
+        }
+    }
+}
+
 // ---- the kernel ------------------------------------------------------------------------------
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, bool VEC>
@@ -316,20 +352,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(GemmParams 
     }
 
     // store: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its block
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn0 + j * 32 + lr;
-            if (col < N) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = m0 + wm0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
-                    if (row < M) w.C[(size_t)row * w.ldc + col] = acc[i][j][r];
-                }
-            }
-        }
-    }
+    store_tile<TM, TN>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh);
 }
 
 // ---- the pipelined kernel: global -> LDS by DMA, NSTAGE slabs in flight --------------------------
@@ -620,20 +643,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
         stage = next_stage;
     }
 
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn0 + j * 32 + lr;
-            if (col < N) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int row = m0 + wm0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
-                    if (row < M) w.C[(size_t)row * w.ldc + col] = acc[i][j][r];
-                }
-            }
-        }
-    }
+    store_tile<TM, TN>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh);
 }
 
 // ---- split-k reduction ---------------------------------------------------------------------------
