@@ -187,6 +187,46 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], float* _
     }
 }
 
+// The same through LDS, for tiles entirely inside a C whose rows are 16-byte aligned: 16 rows of the
+// wave's sub-tile at a time are written to a wave-private LDS patch (row stride WN + 8 words: the two
+// lane halves, 4 rows apart, land 32 banks apart) and read back as 128-bit row pieces, so every
+// store instruction writes whole 512-byte (WN = 128) row segments, 16 bytes per lane.
+template <int TM, int TN>
+__device__ __forceinline__ void store_tile_staged(const f32x16 (&acc)[TM][TN], float* __restrict__ C, long ldc,
+                                                  int row0, int col0, int lane, float* patch)
+{
+    constexpr int WN = TN * 32;
+    constexpr int S = WN + 8;
+    constexpr int V = WN / 4;                 // 16-byte pieces per row
+    constexpr int PIECES = 16 * V;            // pieces per 16-row patch
+    const int lr = lane & 31;
+    const int lh = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int rr = 0; rr < 8; ++rr) {
+                const int r = h * 8 + rr;                                   // rows 16h .. 16h+15 of the block
+                const int prow = (rr / 4) * 8 + lh * 4 + (rr % 4);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) patch[prow * S + j * 32 + lr] = acc[i][j][r];
+            }
+#pragma unroll
+            for (int t = 0; t < (PIECES + 63) / 64; ++t) {
+                const int idx = t * 64 + lane;
+                if (PIECES % 64 == 0 || idx < PIECES) {
+                    const int prow = idx / V;
+                    const int c4 = idx % V;
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(&patch[prow * S + c4 * 4]);
+                    __builtin_nontemporal_store(
+                        v, reinterpret_cast<f32x4*>(C + (size_t)(row0 + i * 32 + h * 16 + prow) * ldc + col0 + c4 * 4));
+                }
+            }
+        }
+    }
+}
+
 // ---- the kernel ------------------------------------------------------------------------------
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, bool VEC>
@@ -643,7 +683,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
         stage = next_stage;
     }
 
-    store_tile<TM, TN>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh);
+    // epilogue: interior tiles of a 16-byte-aligned C go through wave-private LDS patches (the slab
+    // buffers are free once every wave has passed this barrier)
+    lds_barrier();
+    const bool c_vec = ((reinterpret_cast<uintptr_t>(w.C) & 15) == 0) && ((w.ldc & 3) == 0);
+    if (c_vec && m0 + BM <= M && n0 + BN <= N)
+        store_tile_staged<TM, TN>(acc, w.C, w.ldc, m0 + wm0, n0 + wn0, lane, lds + wave * (16 * (WN + 8)));
+    else
+        store_tile<TM, TN>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh);
 }
 
 // ---- split-k reduction ---------------------------------------------------------------------------
@@ -671,6 +718,7 @@ struct Config {
     void (*dma[2])(GemmParams);       // pipelined kernel, [op]; null if the configuration has none
     int nstage;
     int threads;
+    int waves_n;
     float eff;                        // measured fraction of the fp32 MFMA peak with every CU busy
     // LDS bytes of the guarded kernel: two buffers of an A slab and a B slab (layouts as in the kernel)
     size_t lds_bytes(int op) const
@@ -679,7 +727,15 @@ struct Config {
         const size_t b = (op == OP_NT) ? (size_t)bn * (bk + 4) : (size_t)bk * (bn + 8);
         return 2 * (a + b) * sizeof(float);
     }
-    size_t lds_bytes_dma() const { return (size_t)nstage * (bm + bn) * bk * sizeof(float); }
+    size_t lds_bytes_dma() const
+    {
+        const size_t ring = (size_t)nstage * (bm + bn) * bk * sizeof(float);
+        // epilogue patches: 16 rows x (wave tile width + 8) words per wave
+        const size_t waves = (size_t)threads / 64;
+        const size_t wn = (size_t)bn / (size_t)waves_n;
+        const size_t patches = waves * 16 * (wn + 8) * sizeof(float);
+        return ring > patches ? ring : patches;
+    }
     // workgroups of the pipelined kernel that fit one CU (160 KB of LDS, 2048 threads, 512 VGPRs per lane slot)
     int wg_per_cu() const
     {
@@ -698,7 +754,7 @@ struct Config {
 #define MTNN_CFG_DMA(BM, BN, BK, WMV, WNV, NS, GBK, EFF)                                      \
     { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV "_dma" #NS, BM, BN, BK, MTNN_GUARDED(BM, BN, GBK, WMV, WNV), \
       {gemm_dma_kernel<BM, BN, BK, WMV, WNV, false, NS>, gemm_dma_kernel<BM, BN, BK, WMV, WNV, true, NS>}, \
-      NS, WMV * WNV * 64, EFF }
+      NS, WMV * WNV * 64, WNV, EFF }
 
 static const Config kConfigs[] = {
     MTNN_CFG_DMA(256, 256, 32, 4, 2, 2, 16, 0.943f),   // 0: 8 waves of 64 x 128, 128 KB of LDS
