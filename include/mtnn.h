@@ -74,6 +74,17 @@ MTNN_API int mtnn_nn(void *stream, int m, int n, int k,
 MTNN_API int mtnn_transpose(void *stream, int rows, int cols,
                    const float *in, int ldin, float *out, int ldout);
 
+/* In-place transpose of a square n x n matrix (ld >= n): X[c][r] <-> X[r][c], bit-exact.  The paper
+ * names in-place transposition as future work for the case where the memory for B^T is missing
+ * (Section III, Section VI); the square case decomposes into independent tile swaps. */
+MTNN_API int mtnn_transpose_inplace(void *stream, int n, float *X, int ld);
+
+/* TNN without a workspace, for a square B (n == k, else MTNN_ERR_ARG): B is transposed in place,
+ * the NN product runs on it, and B is transposed back; B is unchanged once the enqueued work has
+ * run, but it is WRITTEN in between, so nothing else may read it concurrently. */
+MTNN_API int mtnn_tnn_inplace(void *stream, int m, int n, int k,
+                     const float *A, int lda, float *B, int ldb, float *C, int ldc);
+
 /* Bytes of workspace TNN needs for B^T (n*k floats, rounded up to 256 B); 0 if n or k <= 0. */
 MTNN_API size_t mtnn_tnn_workspace_bytes(int n, int k);
 

@@ -45,6 +45,8 @@ SIGNATURES = {
     "mtnn_nt": (_c_int, _GEMM),
     "mtnn_nn": (_c_int, _GEMM),
     "mtnn_transpose": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_int, _c_vp, _c_int]),
+    "mtnn_transpose_inplace": (_c_int, [_c_vp, _c_int, _c_vp, _c_int]),
+    "mtnn_tnn_inplace": (_c_int, _GEMM),
     "mtnn_tnn_workspace_bytes": (_c_sz, [_c_int, _c_int]),
     "mtnn_tnn": (_c_int, _GEMM + [_c_vp, _c_sz]),
     "mtnn_auto": (_c_int, _GEMM + [_c_vp, _c_sz, _p_int]),
@@ -186,6 +188,24 @@ def mtnn_transpose(X, out, stream=None):
         raise ValueError("shape mismatch")
     _check(lib().mtnn_transpose(_stream(stream), rows, cols, pi, ldi, po, ldo), "mtnn_transpose")
     return out
+
+
+def mtnn_transpose_inplace(X, stream=None):
+    """X <- X^T for a square matrix, in place, bit-exact."""
+    p, ld = _dev(X, "X")
+    if X.shape[0] != X.shape[1]:
+        raise ValueError("square matrices only")
+    _check(lib().mtnn_transpose_inplace(_stream(stream), X.shape[0], p, ld), "mtnn_transpose_inplace")
+    return X
+
+
+def mtnn_tnn_inplace(A, B, C, stream=None):
+    """C = A x B^T through an in-place transpose of the square B (restored afterwards)."""
+    (pa, lda), (pb, ldb), (pc, ldc) = _dev(A, "A"), _dev(B, "B"), _dev(C, "C")
+    m, k = A.shape
+    n = B.shape[0]
+    _check(lib().mtnn_tnn_inplace(_stream(stream), m, n, k, pa, lda, pb, ldb, pc, ldc), "mtnn_tnn_inplace")
+    return C
 
 
 def mtnn_tnn_workspace_bytes(n: int, k: int) -> int:

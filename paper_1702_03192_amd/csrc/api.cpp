@@ -128,6 +128,29 @@ int mtnn_transpose(void* stream, int rows, int cols, const float* in, int ldin, 
     return launch_status(err);
 }
 
+int mtnn_transpose_inplace(void* stream, int n, float* X, int ld)
+{
+    if (n < 0) return MTNN_ERR_DIM;
+    if (n == 0) return MTNN_OK;
+    if (!X) return MTNN_ERR_NULL;
+    if (ld < n) return MTNN_ERR_LD;
+    return launch_status(mtnn::launch_transpose_inplace(static_cast<hipStream_t>(stream), n, X, ld));
+}
+
+int mtnn_tnn_inplace(void* stream, int m, int n, int k, const float* A, int lda, float* B, int ldb, float* C, int ldc)
+{
+    // TNN with no workspace, for a square B: transpose B in place, NN product, transpose back
+    if (n != k) return MTNN_ERR_ARG;
+    const int st0 = check_gemm(mtnn::OP_NT, m, n, k, A, lda, B, ldb, C, ldc);
+    if (st0 != MTNN_OK) return st0;
+    if (m == 0 || n == 0) return MTNN_OK;
+    int st = mtnn_transpose_inplace(stream, n, B, ldb);
+    if (st != MTNN_OK) return st;
+    st = run_gemm(stream, mtnn::OP_NN, -1, 0, m, n, k, A, lda, B, ldb, C, ldc);
+    const int st2 = mtnn_transpose_inplace(stream, n, B, ldb);   // restore B even if the product failed to launch
+    return st != MTNN_OK ? st : st2;
+}
+
 int mtnn_copy_bytes(void* stream, size_t bytes, const void* in, void* out)
 {
     if (bytes == 0) return MTNN_OK;

@@ -19,6 +19,7 @@ int gemm_default_config(int op, int m, int n, int k);
 int gemm_default_splits(int op, int m, int n, int k);
 
 int launch_fill_zero(hipStream_t s, int m, int n, float* C, long ldc);
+int launch_transpose_inplace(hipStream_t s, int n, float* X, long ld);
 int launch_copy(hipStream_t s, size_t nvec, const void* in, void* out);
 int launch_transpose(hipStream_t s, int rows, int cols, const float* in, long ldin, float* out, long ldout);
 

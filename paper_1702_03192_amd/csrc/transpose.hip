@@ -133,6 +133,48 @@ int launch_transpose(hipStream_t s, int rows, int cols, const float* in, long ld
     return launch_transpose_t<128>(s, rows, cols, pin, ldin, pout, ldout, vec);
 }
 
+// ---- in-place transpose of a square matrix -------------------------------------------------------
+//
+// The paper's TNN needs extra memory for B^T and names in-place transposition as future work for
+// the case where that memory is missing (Section III, Section VI).  For a square matrix the
+// in-place problem decomposes into independent swaps: the workgroup for tile pair (ti <= tj) loads
+// tile (ti, tj) and tile (tj, ti) into LDS and writes each one transposed into the other's place
+// (a diagonal tile is transposed onto itself).  Every element is read and written exactly once by
+// exactly one workgroup, so there are no hazards between workgroups.  64 x 64 tiles, 256 threads.
+constexpr int IT = 64;
+constexpr int ITP = IT + 1;
+
+__global__ __launch_bounds__(256) void transpose_inplace_kernel(uint32_t* __restrict__ X, int n, long ld)
+{
+    const int ti = blockIdx.y, tj = blockIdx.x;
+    if (ti > tj) return;
+    __shared__ uint32_t ta[IT * ITP];     // tile (ti, tj)
+    __shared__ uint32_t tb[IT * ITP];     // tile (tj, ti)
+    const int t = threadIdx.x;
+    const int lane_c = t & 63;
+    const int rbase = t >> 6;
+    const int r0 = ti * IT, c0 = tj * IT;
+    for (int r = rbase; r < IT; r += 4) {
+        if (r0 + r < n && c0 + lane_c < n) ta[r * ITP + lane_c] = X[(size_t)(r0 + r) * ld + c0 + lane_c];
+        if (ti != tj && c0 + r < n && r0 + lane_c < n) tb[r * ITP + lane_c] = X[(size_t)(c0 + r) * ld + r0 + lane_c];
+    }
+    __syncthreads();
+    for (int r = rbase; r < IT; r += 4) {
+        // row r of the tile at (tj, ti) receives column r of tile (ti, tj), and vice versa
+        if (c0 + r < n && r0 + lane_c < n) X[(size_t)(c0 + r) * ld + r0 + lane_c] = ta[lane_c * ITP + r];
+        if (ti != tj && r0 + r < n && c0 + lane_c < n) X[(size_t)(r0 + r) * ld + c0 + lane_c] = tb[lane_c * ITP + r];
+    }
+}
+
+int launch_transpose_inplace(hipStream_t s, int n, float* X, long ld)
+{
+    if (n <= 0) return 0;
+    const int nt = (n + IT - 1) / IT;
+    if (nt > 65535) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(transpose_inplace_kernel, dim3(nt, nt), dim3(256), 0, s, reinterpret_cast<uint32_t*>(X), n, ld);
+    return (int)hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void fill_zero_kernel(float* __restrict__ C, int m, int n, long ldc)
 {
     const long long total = (long long)m * n;

@@ -133,3 +133,12 @@ def test_fc_step_validation(L):
     assert L.mtnn_fc_train_step(None, ctypes.byref(d)) == 1
     assert L.mtnn_fc_sgd(None, -1, 0x10, 0x20, 0.1) == 1
     assert L.mtnn_fc_bias_act(None, 4, 4, None, 0x20, 1) == 2
+
+
+def test_inplace_transpose_validation(L):
+    assert L.mtnn_transpose_inplace(None, -1, A, 4) == 1
+    assert L.mtnn_transpose_inplace(None, 4, None, 4) == 2
+    assert L.mtnn_transpose_inplace(None, 4, A, 3) == 3
+    assert L.mtnn_transpose_inplace(None, 0, None, 0) == 0
+    assert L.mtnn_tnn_inplace(None, 4, 6, 8, A, 8, B, 8, C, 6) == 8      # B not square
+    assert L.mtnn_tnn_inplace(None, 4, 8, 8, A, 7, B, 8, C, 8) == 3

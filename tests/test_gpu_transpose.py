@@ -84,3 +84,39 @@ def test_transpose_involution_on_device():
     mt.mtnn_transpose(t1, t2)
     torch.cuda.synchronize()
     assert t2.cpu().numpy().tobytes() == x.tobytes()
+
+
+@pytest.mark.parametrize("n,ld", [(64, 64), (1, 1), (5, 9), (130, 130), (257, 300), (1000, 1000), (4096, 4096)])
+def test_inplace_square_transpose_bit_exact(n, ld):
+    import torch
+    x = I.normal01(6100, 0, n, n)
+    d = dev_matrix(x, ld, fill=np.float32(-3.0))
+    base = d.storage_offset()
+    mt.mtnn_transpose_inplace(d)
+    torch.cuda.synchronize()
+    assert d.cpu().numpy().tobytes() == np.ascontiguousarray(oracle.transpose_ref(x)).tobytes()
+    if ld > n:                                           # padding untouched
+        full = d.as_strided((n, ld), (ld, 1), base).cpu().numpy()
+        assert np.all(full[:, n:] == -3.0)
+    mt.mtnn_transpose_inplace(d)
+    torch.cuda.synchronize()
+    assert d.cpu().numpy().tobytes() == x.tobytes()
+
+
+def test_tnn_inplace_matches_oracle_and_restores_b():
+    import torch
+    from gpu_util import check_gemm
+    m, n = 300, 520
+    A, B = I.nt_operands(m, n, n, 6200, "normal")
+    dA, dB = dev_matrix(A), dev_matrix(B)
+    out = Guarded(m, n)
+    mt.mtnn_tnn_inplace(dA, dB, out.view)
+    torch.cuda.synchronize()
+    got, intact = out.host()
+    assert intact
+    C, S = oracle.nt_ref(A, B, with_bound=True)
+    check_gemm(got, C, S, n, "tnn_inplace")
+    assert dB.cpu().numpy().tobytes() == B.tobytes()
+    with pytest.raises(mt.MtnnError) as e:
+        mt.mtnn_tnn_inplace(dA[:, :100].contiguous(), dev_matrix(B[:, :100].copy()), out.view)
+    assert e.value.status == 8
