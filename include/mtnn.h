@@ -215,8 +215,10 @@ MTNN_API int mtnn_fc_softmax_xent(void *stream, int batch, int classes, const fl
                          float *dZ, float *row_loss, float *mean_loss);
 /* dH[e] = H[e] > 0 ? dH[e] : 0 over `count` elements (H is the ReLU output). */
 MTNN_API int mtnn_fc_relu_backward(void *stream, long long count, float *dH, const float *H);
-/* db[j] = sum_i dZ[i][j], dZ batch x width dense. */
-MTNN_API int mtnn_fc_bias_grad(void *stream, int batch, int width, const float *dZ, float *db);
+/* db[j] = sum_i dZ[i][j], dZ batch x width dense.  scratch: optional 32 x width floats; with it the
+ * rows are summed in up to 32 chunks by many workgroups and the chunks added in order (NULL: one
+ * workgroup per 64 columns walks all rows).  Either way the order is fixed. */
+MTNN_API int mtnn_fc_bias_grad(void *stream, int batch, int width, const float *dZ, float *db, float *scratch);
 /* P[e] -= lr * G[e] over `count` elements. */
 MTNN_API int mtnn_fc_sgd(void *stream, long long count, float *P, const float *G, float lr);
 /* dense device-to-device copy of a rows x cols matrix */

@@ -89,6 +89,36 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const float* __restrict_
     if (grp == 0 && col < width) db[col] = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
 }
 
+// Two-stage version for large batches: stage 1 sums row chunk blockIdx.y of 64 columns into
+// part[chunk][col]; stage 2 adds the chunks in order.  Same fixed order on every run.
+__global__ __launch_bounds__(256) void bias_grad_partial_kernel(const float* __restrict__ dZ, float* __restrict__ part,
+                                                                int batch, int width, int rows_per_chunk)
+{
+    __shared__ float acc[4][64];
+    const int col = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int grp = threadIdx.x >> 6;
+    const int r0 = blockIdx.y * rows_per_chunk;
+    const int r1 = min(batch, r0 + rows_per_chunk);
+    float s = 0.f;
+    if (col < width)
+        for (int i = r0 + grp; i < r1; i += 4) s += dZ[(size_t)i * width + col];
+    acc[grp][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (grp == 0 && col < width)
+        part[(size_t)blockIdx.y * width + col] =
+            (acc[0][threadIdx.x] + acc[1][threadIdx.x]) + (acc[2][threadIdx.x] + acc[3][threadIdx.x]);
+}
+
+__global__ __launch_bounds__(256) void bias_grad_final_kernel(const float* __restrict__ part, int chunks, int width,
+                                                              float* __restrict__ db)
+{
+    const int col = blockIdx.x * 256 + threadIdx.x;
+    if (col >= width) return;
+    float s = part[col];
+    for (int c = 1; c < chunks; ++c) s += part[(size_t)c * width + col];
+    db[col] = s;
+}
+
 // P -= lr * G
 __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ P, const float* __restrict__ G, long long total, float lr)
 {
@@ -144,12 +174,25 @@ int mtnn_fc_relu_backward(void* stream, long long count, float* dH, const float*
     return status_of(hipGetLastError());
 }
 
-int mtnn_fc_bias_grad(void* stream, int batch, int width, const float* dZ, float* db)
+int mtnn_fc_bias_grad(void* stream, int batch, int width, const float* dZ, float* db, float* scratch)
 {
     if (batch <= 0 || width <= 0) return MTNN_ERR_DIM;
     if (!dZ || !db) return MTNN_ERR_NULL;
-    hipLaunchKernelGGL(mtnn::bias_grad_kernel, dim3((width + 63) / 64), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       dZ, db, batch, width);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int col_blocks = (width + 63) / 64;
+    // enough row chunks to put ~512 workgroups on the machine, at most 32, at least 32 rows each
+    int chunks = 512 / col_blocks;
+    if (chunks > 32) chunks = 32;
+    if (chunks > batch / 32) chunks = batch / 32;
+    if (!scratch || chunks < 2) {
+        hipLaunchKernelGGL(mtnn::bias_grad_kernel, dim3(col_blocks), dim3(256), 0, s, dZ, db, batch, width);
+        return status_of(hipGetLastError());
+    }
+    const int rows_per_chunk = (batch + chunks - 1) / chunks;
+    chunks = (batch + rows_per_chunk - 1) / rows_per_chunk;
+    hipLaunchKernelGGL(mtnn::bias_grad_partial_kernel, dim3(col_blocks, chunks), dim3(256), 0, s, dZ, scratch, batch,
+                       width, rows_per_chunk);
+    hipLaunchKernelGGL(mtnn::bias_grad_final_kernel, dim3((width + 255) / 256), dim3(256), 0, s, scratch, chunks, width, db);
     return status_of(hipGetLastError());
 }
 
@@ -169,6 +212,7 @@ int mtnn_fc_sgd(void* stream, long long count, float* P, const float* G, float l
 //   dZt               max_width x batch          transposed gradient for the dW product
 //   Bt                max(out x in) floats       B^T buffer for the TNN forward path
 //   row_loss          batch
+//   bias_part         32 x max_width             row-chunk partial sums of the bias gradient
 size_t mtnn_fc_workspace_bytes(int num_layers, const int* dims, int batch)
 {
     if (num_layers <= 0 || !dims || batch <= 0) return 0;
@@ -186,6 +230,7 @@ size_t mtnn_fc_workspace_bytes(int num_layers, const int* dims, int batch)
     total += align256(max_w * (size_t)batch * 4);
     total += align256(max_wt * 4);
     total += align256((size_t)batch * 4);
+    total += align256(32 * max_w * 4);
     return total;
 }
 
@@ -224,6 +269,7 @@ static int fc_run(void* stream, const mtnn_fc_step_desc* d, bool forward_only)
     float* dZt = carve(max_w * (size_t)batch * 4);
     float* Bt = carve(max_wt * 4);
     float* row_loss = carve((size_t)batch * 4);
+    float* bias_part = carve(32 * max_w * 4);
     const size_t bt_bytes = align256(max_wt * 4);
 
     int st;
@@ -253,7 +299,7 @@ static int fc_run(void* stream, const mtnn_fc_step_desc* d, bool forward_only)
     // backward, last layer first
     for (int l = L - 1; l >= 0; --l) {
         const int in = dims[l], out = dims[l + 1];
-        st = mtnn_fc_bias_grad(stream, batch, out, dZ, d->db[l]);
+        st = mtnn_fc_bias_grad(stream, batch, out, dZ, d->db[l], bias_part);
         if (st != MTNN_OK) return st;
         // dW_l = dZ^T x H_l : transpose dZ (batch x out -> out x batch), then an NN product
         st = mtnn_transpose(stream, batch, out, dZ, out, dZt, batch);

@@ -116,8 +116,8 @@ def test_fc_step_validation(L):
     assert L.mtnn_fc_workspace_bytes(0, dims, 4) == 0
     assert L.mtnn_fc_workspace_bytes(2, dims, 0) == 0
     need = L.mtnn_fc_workspace_bytes(2, dims, 4)
-    # H1 4x16, H2 4x4, dA, dB 4x16 each, dZt 16x4, Bt 16x8, row_loss 4 -> all rounded to 256 B
-    assert need == 256 + 256 + 2 * 256 + 256 + 512 + 256
+    # H1 4x16, H2 4x4, dA, dB 4x16 each, dZt 16x4, Bt 16x8, row_loss 4 (each rounded to 256 B), bias partials 32x16
+    assert need == 256 + 256 + 2 * 256 + 256 + 512 + 256 + 2048
     assert L.mtnn_fc_train_step(None, None) == 2
     ptrs = (ctypes.c_void_p * 2)(0x1000, 0x2000)
     d = mt.FcStepDesc(2, dims, 4, 0x100, 0x200, ptrs, ptrs, ptrs, ptrs, None, 0x300, 0x400, need - 1, 0.01, 0)

@@ -134,6 +134,15 @@ def test_elementwise_steps_against_numpy():
     db = torch.empty(70, device="cuda")
     mt.mtnn_fc_bias_grad(dZ, db)
     assert np.allclose(db.cpu().numpy(), rng_z.astype(np.float64).sum(0), rtol=1e-5, atol=1e-5)
+    big = I.normal01(5301, 0, 1000, 200)
+    dbig = torch.from_numpy(big).cuda()
+    db2 = torch.empty(200, device="cuda")
+    db3 = torch.empty(200, device="cuda")
+    mt.mtnn_fc_bias_grad(dbig, db2, scratch=torch.empty(32 * 200, device="cuda"))
+    mt.mtnn_fc_bias_grad(dbig, db3)
+    want = big.astype(np.float64).sum(0)
+    assert np.allclose(db2.cpu().numpy(), want, rtol=1e-5, atol=1e-4)
+    assert np.allclose(db3.cpu().numpy(), want, rtol=1e-5, atol=1e-4)
     # sgd
     P = torch.from_numpy(rng_z.copy()).cuda()
     mt.mtnn_fc_sgd(P, dZ, 0.5)
