@@ -71,8 +71,8 @@ def main(argv=None):
                        "labels": [mt.mtnn_select(batch, dims[l + 1], dims[l]) for l in range(L)]}
                 for mode, name in MODES:
                     desc, keep = mt.make_fc_desc(dims, batch, X, labels, W, b, gW, gb, loss, ws, 0.0, mode)
-                    t_f, _ = _time_batches(lambda: mt.mtnn_fc_forward(desc), stream, args.samples, 200.0)
-                    t_s, _ = _time_batches(lambda: mt.mtnn_fc_train_step(desc), stream, args.samples, 200.0)
+                    t_f, _ = _time_batches(lambda: mt.mtnn_fc_forward(desc), stream, args.samples, 2000.0)
+                    t_s, _ = _time_batches(lambda: mt.mtnn_fc_train_step(desc), stream, args.samples, 2000.0)
                     rec[name] = {"forward_ms": t_f * 1e3, "backward_ms": (t_s - t_f) * 1e3, "total_ms": t_s * 1e3,
                                  "forward_tflops": fwd_flop / t_f / 1e12,
                                  "total_tflops": (fwd_flop + bwd_flop) / t_s / 1e12}

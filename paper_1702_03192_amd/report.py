@@ -60,9 +60,9 @@ def main(argv=None):
         A, B = operands(m, n, k, seed, dist)
         C = torch.empty((m, n), device="cuda")
         ws = torch.empty(mt.mtnn_tnn_workspace_bytes(n, k), dtype=torch.uint8, device="cuda")
-        t_nt, _ = _time_batches(lambda: mt.mtnn_nt(A, B, C), stream, samples, 200.0)
-        t_tnn, _ = _time_batches(lambda: mt.mtnn_tnn(A, B, C, ws), stream, samples, 200.0)
-        t_auto, _ = _time_batches(lambda: mt.mtnn_auto(A, B, C, ws), stream, samples, 200.0)
+        t_nt, _ = _time_batches(lambda: mt.mtnn_nt(A, B, C), stream, samples, 2000.0)
+        t_tnn, _ = _time_batches(lambda: mt.mtnn_tnn(A, B, C, ws), stream, samples, 2000.0)
+        t_auto, _ = _time_batches(lambda: mt.mtnn_auto(A, B, C, ws), stream, samples, 2000.0)
         label = mt.mtnn_select(m, n, k)
         fl = 2.0 * m * n * k
         roof = roofline_seconds(m, n, k)
@@ -101,14 +101,14 @@ def main(argv=None):
     for rows, cols in TRANSPOSES:
         X = torch.rand((rows, cols), device="cuda")
         Y = torch.empty((cols, rows), device="cuda")
-        t, tmin = _time_batches(lambda: mt.mtnn_transpose(X, Y), stream, args.samples, 200.0)
+        t, tmin = _time_batches(lambda: mt.mtnn_transpose(X, Y), stream, args.samples, 2000.0)
         report["transposes"].append({"rows": rows, "cols": cols, "t_us": t * 1e6, "gbs": 8.0 * rows * cols / t / 1e9,
                                      "frac_of_peak": 8.0 * rows * cols / t / 1e9 / PEAK_GBS})
         print(f"[report] transpose {rows}x{cols}: {8.0 * rows * cols / t / 1e9:.0f} GB/s", flush=True)
         del X, Y
     src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     dst = torch.empty_like(src)
-    t, _ = _time_batches(lambda: mt.mtnn_copy_bytes(src, dst), stream, args.samples, 200.0)
+    t, _ = _time_batches(lambda: mt.mtnn_copy_bytes(src, dst), stream, args.samples, 2000.0)
     report["copy_1gib_gbs"] = 2.0 * src.numel() / t / 1e9
     del src, dst
 
@@ -129,7 +129,7 @@ def main(argv=None):
     report["fc_step"] = {"dims": dims, "batch": batch, "gemm_flop": flops}
     for mode, name in ((1, "nt"), (-1, "tnn"), (0, "auto")):
         desc, keep = mt.make_fc_desc(dims, batch, X, labels, W, b, gW, gb, loss, ws, 0.0, mode)
-        t, _ = _time_batches(lambda: mt.mtnn_fc_train_step(desc), stream, args.samples, 200.0)
+        t, _ = _time_batches(lambda: mt.mtnn_fc_train_step(desc), stream, args.samples, 2000.0)
         report["fc_step"][name + "_ms"] = t * 1e3
         report["fc_step"][name + "_gemm_tflops"] = flops / t / 1e12
         print(f"[report] fc step {name}: {t * 1e3:.3f} ms ({flops / t / 1e12:.1f} TFLOP/s of GEMM work)", flush=True)

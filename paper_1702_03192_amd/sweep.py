@@ -7,7 +7,7 @@ collect: for every (m, n, k) of the grid {64, ..., 8192}^3 it times the direct N
 (transpose + NN through mtnn_tnn, workspace allocated beforehand) and writes one CSV row per
 shape, appended as it goes, so an interrupted sweep resumes where it stopped.  The paper states
 no timing protocol; here each path gets 3 warm-up calls, then `samples` event-timed batches of
-back-to-back calls sized to last at least `min_batch_us`, and the table keeps median and
+back-to-back calls sized to last at least `min_batch_us` (2 ms by default), and the table keeps median and
 minimum per call.  TNN is also timed with a per-call allocation of the B^T buffer through
 PyTorch's caching allocator, because the paper counts allocation and release in T_transpose
 (Section III); labels use the pre-allocated figure.
@@ -171,7 +171,7 @@ def main(argv=None):
     c = sub.add_parser("collect")
     c.add_argument("--out", required=True)
     c.add_argument("--samples", type=int, default=20)
-    c.add_argument("--min-batch-us", type=float, default=200.0)
+    c.add_argument("--min-batch-us", type=float, default=2000.0)
     c.add_argument("--limit", type=int, default=None)
     c.add_argument("--grid", choices=["bench", "paper"], default="bench",
                    help="bench: {64..8192}^3 (512 shapes); paper: {2^7..2^16}^3 (1000 shapes, Section IV-A)")
