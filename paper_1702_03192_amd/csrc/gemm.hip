@@ -16,8 +16,8 @@
 //     of 8 is permuted (lanes 0-31 take k = 0..3, lanes 32-63 take k = 4..7); A and B use the
 //     same permutation and a sum does not care;
 //   * NT: B rows are k-contiguous exactly like A rows, so B uses the same staging as A.
-//     NN: B rows are n-contiguous; the slab is kept as [k][n] and a lane reads its column
-//     word by word (consecutive lanes -> consecutive words, conflict-free);
+//     NN: B rows are n-contiguous; the slab is kept as [k][n] (the guarded kernel reads its
+//     column word by word; the pipelined kernel reads TN consecutive n per lane, see there);
 //   * rows of A / B beyond m / n are clamped to the last valid row: they only feed outputs
 //     that are never stored.  Elements beyond k are zero-filled in both operands, so padding
 //     (which may hold NaN) never reaches a sum;
@@ -185,6 +185,43 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], float* _
             }
         }
     }
+}
+
+// Epilogue of the pipelined NN kernel.  There a lane's TN accumulator blocks hold TN CONSECUTIVE
+// columns (block j, lane l <-> column TN * (l % 32) + j, see the B fragment reads), so for interior
+// tiles of an aligned C one store per accumulator register writes TN words: lanes 0-31 cover
+// 32 * TN consecutive words of one row.
+template <int TM, int TN>
+__device__ __forceinline__ void store_tile_interleaved(const f32x16 (&acc)[TM][TN], float* __restrict__ C, long ldc,
+                                                       int M, int N, int row0, int col0, int lr, int lh, bool aligned)
+{
+    typedef float vecN __attribute__((ext_vector_type(TN)));
+    if (TN > 1 && aligned && row0 + TM * 32 <= M && col0 + TN * 32 <= N) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                vecN v;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) v[j] = acc[i][j][r];
+                float* dst = C + (size_t)(row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4)) * ldc + col0 + TN * lr;
+                __builtin_nontemporal_store(v, reinterpret_cast<vecN*>(dst));
+            }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
+            if (row < M) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int col = col0 + TN * lr + j;
+                    if (col < N) C[(size_t)row * ldc + col] = acc[i][j][r];
+                }
+            }
+        }
 }
 
 // The same through LDS, for tiles entirely inside a C whose rows are 16-byte aligned: 16 rows of the
@@ -616,15 +653,22 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
             if (NT) {
                 const int row = wn0 + j * 32 + lr;
                 bf[j] = *reinterpret_cast<const f32x4*>(&bs[row * BK + ((c ^ ((row / RPL) % CPR)) * 4)]);
-            } else {
-                const int col = wn0 + j * 32 + lr;
-                const int krow = kk * 8 + lh * 4;             // rows krow..krow+3 share (krow>>2)&1
-                const int sw = (NCH >= 16) ? (((krow >> 2) & 1) << 3) : 0;
-                const float* q = &bs[krow * BN + (((col >> 2) ^ sw) << 2) + (col & 3)];
-                bf[j].x = q[0];
-                bf[j].y = q[BN];
-                bf[j].z = q[2 * BN];
-                bf[j].w = q[3 * BN];
+            }
+        }
+        if (!NT) {
+            // NN: row krow + s of the [k][n] slab feeds k step s.  A lane reads TN consecutive n
+            // (one 128-, 64- or 32-bit LDS load) and uses them for its TN blocks, so block j of lane l
+            // works on column wn0 + TN * l + j; the epilogue stores with the same mapping.
+            typedef float vecN __attribute__((ext_vector_type(TN)));
+            const int krow = kk * 8 + lh * 4;                 // rows krow..krow+3 share (krow>>2)&1
+            const int sw = (NCH >= 16) ? (((krow >> 2) & 1) << 3) : 0;
+            const int col = wn0 + TN * lr;
+            const float* q = &bs[krow * BN + (((col >> 2) ^ sw) << 2) + (col & 3)];
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                const vecN v = *reinterpret_cast<const vecN*>(q + st * BN);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bf[j][st] = v[j];
             }
         }
     };
@@ -685,12 +729,16 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
 
     // epilogue: interior tiles of a 16-byte-aligned C go through wave-private LDS patches (the slab
     // buffers are free once every wave has passed this barrier)
-    lds_barrier();
     const bool c_vec = ((reinterpret_cast<uintptr_t>(w.C) & 15) == 0) && ((w.ldc & 3) == 0);
-    if (c_vec && m0 + BM <= M && n0 + BN <= N)
-        store_tile_staged<TM, TN>(acc, w.C, w.ldc, m0 + wm0, n0 + wn0, lane, lds + wave * (16 * (WN + 8)));
-    else
-        store_tile<TM, TN>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh);
+    if (!NT) {
+        store_tile_interleaved<TM, TN>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh, c_vec);
+    } else {
+        lds_barrier();
+        if (c_vec && m0 + BM <= M && n0 + BN <= N)
+            store_tile_staged<TM, TN>(acc, w.C, w.ldc, m0 + wm0, n0 + wn0, lane, lds + wave * (16 * (WN + 8)));
+        else
+            store_tile<TM, TN>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh);
+    }
 }
 
 // ---- split-k reduction ---------------------------------------------------------------------------
