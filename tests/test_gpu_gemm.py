@@ -273,3 +273,45 @@ def test_offsets_beyond_2_to_31_elements(which):
     assert torch.equal(bt[:4, n - 1], B[n - 1, :4])
     del A, B, C, ws
     torch.cuda.empty_cache()
+
+
+def _strided_on_device(x, ld):
+    """rows x cols device view with leading dimension ld; the padding is left uninitialised."""
+    import torch
+    rows, cols = x.shape
+    buf = torch.empty(rows * ld, dtype=torch.float32, device="cuda")
+    view = buf.view(rows, ld)[:, :cols]
+    view.copy_(torch.from_numpy(x).cuda())
+    return view
+
+
+@pytest.mark.parametrize("case", ["nt_A_guarded", "nt_A_pipelined", "nt_B_guarded", "nn_B_guarded", "nn_B_pipelined"])
+def test_huge_leading_dimensions(case):
+    """Leading dimensions so large that byte offsets inside one tile reach 2^32: the pipelined kernel
+    addresses a tile with 32-bit lane offsets, so such calls must take the guarded kernel; a leading
+    dimension just under the limit stays on the pipelined kernel with offsets close to 2^32."""
+    import torch
+    if case.startswith("nt"):
+        op, m, n, k = mt.OP_NT, 70, 72, 96
+        A, B = operands(op, m, n, k, 8800)
+        big = (1 << 22) + 4
+        if case == "nt_A_guarded":        # 256 rows x lda x 4 B >= 2^32
+            cfg, dA, dB = 0, _strided_on_device(A, big), _strided_on_device(B, k)
+        elif case == "nt_A_pipelined":    # 64 rows x lda x 4 B just above 2^30
+            cfg, dA, dB = 3, _strided_on_device(A, big), _strided_on_device(B, k)
+        else:
+            cfg, dA, dB = 0, _strided_on_device(A, k), _strided_on_device(B, big)
+    else:
+        op, m, n, k = mt.OP_NN, 70, 72, 40
+        A, B = operands(op, m, n, k, 8801)
+        ldb = (1 << 26) if case == "nn_B_guarded" else (1 << 24)      # (BK + 1) x ldb x 4 B vs 2^32
+        cfg, dA, dB = 0, _strided_on_device(A, k), _strided_on_device(B, ldb)
+    out = Guarded(m, n, n + 4)
+    mt.mtnn_gemm_ex(op, cfg, dA, dB, out.view)
+    sync()
+    got, intact = out.host()
+    assert intact
+    Cref, Sref = reference(op, A, B)
+    check_gemm(got, Cref, Sref, k, case)
+    del dA, dB
+    torch.cuda.empty_cache()
