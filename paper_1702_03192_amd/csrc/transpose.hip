@@ -2,47 +2,56 @@
 // (Section III of the MTNN paper; the "transposeOnGPU" step of Algorithm 1).
 //
 // The operation is pure data movement, so the design is about HBM.  A 256-thread workgroup moves a
-// tile of TR input rows x TC input columns (TR = 128 or 256, TC = 32):
-//   read   a tile row is 128 bytes, one full cache line: 8 lanes x 16 B, 32 rows per pass;
+// tile of TR input rows x TC input columns:
+//   read   a tile row is TC words (128 or 256 bytes, whole cache lines), 16 bytes per lane;
 //   LDS    tile[TR][TC+1] words; the odd row stride spreads the column gather over the banks;
 //   write  an output row segment is TR words (512 B or 1 KB): each lane gathers 4 words of one
 //          tile column from LDS and stores 16 B, with non-temporal stores so that the stream of
 //          results does not evict the input from the caches;
-//   order  consecutive workgroups walk DOWN the input (tile-row index fastest), so their writes
-//          are neighbouring segments of the same output rows.  Measured on MI355X, long contiguous
-//          write runs matter more than contiguous reads: this order with the tall, narrow tile
-//          moves 5.1-6.8 TB/s where a square 64 x 64 tile in row order moved 4.0-5.2 TB/s.
+//   order  workgroup i takes tile row i mod tiles_r and tile column (i / tiles_r + tile row) mod
+//          tiles_c: a diagonal walk.  Workgroups that run at the same time then read different
+//          column strips and write different output row blocks, which spreads both streams over
+//          the memory channels (walking straight down one column strip keeps every concurrent
+//          read 128 bytes wide at one row pitch: measured 5.2 TB/s against 6.0 TB/s for the
+//          diagonal walk on an 8192 x 8192 matrix that comes from HBM).
+// Three tile shapes, chosen by size (measured on MI355X, see launch_transpose):
+//   128 x 32, ordinary loads      matrices up to 2^24 elements: source and result together fit the
+//                                 256 MB memory-side cache, where they usually still are when the
+//                                 transpose follows the kernel that produced its input;
+//   128 x 64, non-temporal loads  between 2^24 and 2^26 elements;
+//   256 x 64, non-temporal loads  from 2^26 elements: data streams from and to HBM, 1 KB write runs.
 // Words are moved as integers, so NaN payloads and signed zeros survive bit for bit.
 // Sizes or leading dimensions that are not multiples of 4 and unaligned bases take the guarded
-// one-word-per-access path of the same kernel; otherwise edge tiles only skip the 16-byte groups
-// that fall outside.
+// one-word-per-access path of the 128 x 32 kernel; otherwise edge tiles only skip the 16-byte
+// groups that fall outside.
 #include "mtnn_internal.h"
 
 namespace mtnn {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int TC = 32;          // tile columns (input) = output rows per tile
-constexpr int TP = TC + 1;      // padded LDS row stride
 constexpr int TR_THREADS = 256;
 
 // the 16-byte-group path of one tile; GUARD: skip the groups that fall outside the matrix (edge tiles)
-template <int TR, bool GUARD>
+template <int TR, int TC, bool NTL, bool GUARD>
 __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
                                                    uint32_t* tile, int rows, int cols, long ldin, long ldout,
                                                    int r0, int c0)
 {
+    constexpr int TP = TC + 1;               // padded LDS row stride
     const int t = threadIdx.x;
-    constexpr int QC = TC / 4;               // 16-byte groups per tile row (8)
-    constexpr int RP = TR_THREADS / QC;      // rows per pass (32)
+    constexpr int QC = TC / 4;               // 16-byte groups per tile row
+    constexpr int RP = TR_THREADS / QC;      // rows per pass
     const int q = t % QC;
     const int rr = t / QC;
     u32x4 v[TR / RP] = {};
 #pragma unroll
     for (int p = 0; p < TR / RP; ++p) {
         const int r = r0 + p * RP + rr;
-        if (!GUARD || (r < rows && c0 + q * 4 < cols))
-            v[p] = *reinterpret_cast<const u32x4*>(in + (size_t)r * ldin + c0 + q * 4);
+        if (!GUARD || (r < rows && c0 + q * 4 < cols)) {
+            const u32x4* src = reinterpret_cast<const u32x4*>(in + (size_t)r * ldin + c0 + q * 4);
+            v[p] = NTL ? __builtin_nontemporal_load(src) : *src;
+        }
     }
 #pragma unroll
     for (int p = 0; p < TR / RP; ++p) {
@@ -65,15 +74,16 @@ __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ 
     }
 }
 
-template <int TR, bool VEC>
+template <int TR, int TC, bool VEC, bool NTL>
 __global__ __launch_bounds__(TR_THREADS) void transpose_kernel(
     const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
-    int rows, int cols, long ldin, long ldout, int tiles_r)
+    int rows, int cols, long ldin, long ldout, int tiles_r, int tiles_c)
 {
-    __shared__ uint32_t tile[TR * TP];
+    constexpr int TP = TC + 1;
+    extern __shared__ uint32_t tile[];                   // TR * TP words
     const int t = threadIdx.x;
     const int tr = blockIdx.x % tiles_r;
-    const int tc = blockIdx.x / tiles_r;
+    const int tc = (blockIdx.x / tiles_r + tr) % tiles_c;   // for each tile row a rotation of the columns
     const int r0 = tr * TR;
     const int c0 = tc * TC;
 
@@ -81,13 +91,13 @@ __global__ __launch_bounds__(TR_THREADS) void transpose_kernel(
     // is entirely inside or entirely outside the matrix
     if (VEC) {
         if ((r0 + TR <= rows) && (c0 + TC <= cols))
-            transpose_tile_vec<TR, false>(in, out, tile, rows, cols, ldin, ldout, r0, c0);
+            transpose_tile_vec<TR, TC, NTL, false>(in, out, tile, rows, cols, ldin, ldout, r0, c0);
         else
-            transpose_tile_vec<TR, true>(in, out, tile, rows, cols, ldin, ldout, r0, c0);
+            transpose_tile_vec<TR, TC, NTL, true>(in, out, tile, rows, cols, ldin, ldout, r0, c0);
     } else {
         // guarded path: one word per access, still row-coalesced on both sides
         const int lane_c = t % TC;
-        const int rbase = t / TC;                        // 0 .. 7
+        const int rbase = t / TC;
         for (int r = rbase; r < TR; r += TR_THREADS / TC) {
             if (r0 + r < rows && c0 + lane_c < cols)
                 tile[r * TP + lane_c] = in[(size_t)(r0 + r) * ldin + c0 + lane_c];
@@ -102,20 +112,30 @@ __global__ __launch_bounds__(TR_THREADS) void transpose_kernel(
     }
 }
 
-template <int TR>
+template <int TR, int TC, bool VEC, bool NTL>
 static int launch_transpose_t(hipStream_t s, int rows, int cols, const uint32_t* in, long ldin,
-                              uint32_t* out, long ldout, bool vec)
+                              uint32_t* out, long ldout)
 {
     const int tiles_c = (cols + TC - 1) / TC;
     const int tiles_r = (rows + TR - 1) / TR;
     const long long nblocks = (long long)tiles_c * tiles_r;
     if (nblocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
-    if (vec)
-        hipLaunchKernelGGL((transpose_kernel<TR, true>), dim3((unsigned)nblocks), dim3(TR_THREADS), 0, s,
-                           in, out, rows, cols, ldin, ldout, tiles_r);
-    else
-        hipLaunchKernelGGL((transpose_kernel<TR, false>), dim3((unsigned)nblocks), dim3(TR_THREADS), 0, s,
-                           in, out, rows, cols, ldin, ldout, tiles_r);
+    constexpr size_t lds = (size_t)TR * (TC + 1) * sizeof(uint32_t);
+    auto kern = transpose_kernel<TR, TC, VEC, NTL>;
+    if (lds > 64 * 1024) {
+        // opt in to the large LDS carve-out once per device
+        static bool raised[16] = {};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return (int)hipGetLastError();
+        if (dev < 0 || dev >= 16 || !raised[dev]) {
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return (int)e;
+            if (dev >= 0 && dev < 16) raised[dev] = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(TR_THREADS), lds, s,
+                       in, out, rows, cols, ldin, ldout, tiles_r, tiles_c);
     return (int)hipGetLastError();
 }
 
@@ -127,10 +147,13 @@ int launch_transpose(hipStream_t s, int rows, int cols, const float* in, long ld
                      ((reinterpret_cast<uintptr_t>(out) & 15) == 0);
     const uint32_t* pin = reinterpret_cast<const uint32_t*>(in);
     uint32_t* pout = reinterpret_cast<uint32_t*>(out);
-    // the taller tile (1 KB write runs) pays off once the matrix is far larger than the caches
-    if ((long long)rows * cols >= (1LL << 27) && rows >= 256)
-        return launch_transpose_t<256>(s, rows, cols, pin, ldin, pout, ldout, vec);
-    return launch_transpose_t<128>(s, rows, cols, pin, ldin, pout, ldout, vec);
+    if (!vec) return launch_transpose_t<128, 32, false, false>(s, rows, cols, pin, ldin, pout, ldout);
+    const long long elems = (long long)rows * cols;
+    if (elems >= (1LL << 26) && rows >= 256 && cols >= 64)
+        return launch_transpose_t<256, 64, true, true>(s, rows, cols, pin, ldin, pout, ldout);
+    if (elems > (1LL << 24) && cols >= 64)
+        return launch_transpose_t<128, 64, true, true>(s, rows, cols, pin, ldin, pout, ldout);
+    return launch_transpose_t<128, 32, true, false>(s, rows, cols, pin, ldin, pout, ldout);
 }
 
 // ---- in-place transpose of a square matrix -------------------------------------------------------
@@ -196,19 +219,32 @@ int launch_fill_zero(hipStream_t s, int m, int n, float* C, long ldc)
     return (int)hipGetLastError();
 }
 
-// Plain streaming copy of 16-byte words (non-temporal stores, like the transpose): the reference point for HBM counters and for what a
-// pure read-once/write-once kernel reaches on this machine (not part of the paper's method).
+// Plain streaming copy of 16-byte words: the reference point for HBM counters and for what a pure
+// read-once / write-once kernel reaches on this machine (not part of the paper's method).  Each
+// thread keeps four independent 16-byte loads in flight; loads and stores are non-temporal.
 __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ in, u32x4* __restrict__ out, size_t nvec)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride)
-        __builtin_nontemporal_store(in[i], out + i);
+    const size_t stride = (size_t)gridDim.x * 1024;
+    size_t base = (size_t)blockIdx.x * 1024 + threadIdx.x;
+    for (; base + 768 < nvec; base += stride) {
+        u32x4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = __builtin_nontemporal_load(in + base + j * 256);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) __builtin_nontemporal_store(v[j], out + base + j * 256);
+    }
+    // the last, partial group of 1024 words (at most one workgroup gets here with work left)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const size_t i = base + (size_t)j * 256;
+        if (i < nvec) __builtin_nontemporal_store(__builtin_nontemporal_load(in + i), out + i);
+    }
 }
 
 int launch_copy(hipStream_t s, size_t nvec, const void* in, void* out)
 {
     if (nvec == 0) return 0;
-    size_t blocks = (nvec + 255) / 256;
+    size_t blocks = (nvec + 1023) / 1024;
     if (blocks > 256 * 64) blocks = 256 * 64;
     hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                        static_cast<const u32x4*>(in), static_cast<u32x4*>(out), nvec);

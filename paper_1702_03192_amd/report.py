@@ -97,15 +97,33 @@ def main(argv=None):
         print(f"[report] {cfg_name} {shape}: NT {row['nt_gflops'] / 1e3:.1f} TNN {row['tnn_gflops'] / 1e3:.1f} "
               f"MTNN {row['mtnn_gflops'] / 1e3:.1f} TFLOP/s  roofline {row['nt_roofline_frac']:.2f}", flush=True)
 
+    # transposes: timed on one buffer pair (small shapes then live in the 256 MB memory-side cache and
+    # the L2s) and again rotating over enough pairs that the footprint passes 1 GiB, so every call
+    # reads from and writes to HBM
     report["transposes"] = []
     for rows, cols in TRANSPOSES:
-        X = torch.rand((rows, cols), device="cuda")
-        Y = torch.empty((cols, rows), device="cuda")
-        t, tmin = _time_batches(lambda: mt.mtnn_transpose(X, Y), stream, args.samples, 2000.0)
-        report["transposes"].append({"rows": rows, "cols": cols, "t_us": t * 1e6, "gbs": 8.0 * rows * cols / t / 1e9,
-                                     "frac_of_peak": 8.0 * rows * cols / t / 1e9 / PEAK_GBS})
-        print(f"[report] transpose {rows}x{cols}: {8.0 * rows * cols / t / 1e9:.0f} GB/s", flush=True)
-        del X, Y
+        pair_bytes = 8.0 * rows * cols
+        nsets = int(max(1, min(64, -(-(1 << 30) // int(pair_bytes)))))
+        Xs = [torch.rand((rows, cols), device="cuda") for _ in range(nsets)]
+        Ys = [torch.empty((cols, rows), device="cuda") for _ in range(nsets)]
+        t, tmin = _time_batches(lambda: mt.mtnn_transpose(Xs[0], Ys[0]), stream, args.samples, 2000.0)
+        turn = [0]
+
+        def rotating():
+            i = turn[0]
+            turn[0] = (i + 1) % nsets
+            mt.mtnn_transpose(Xs[i], Ys[i])
+
+        t_rot, _ = _time_batches(rotating, stream, args.samples, 2000.0)
+        report["transposes"].append({"rows": rows, "cols": cols, "t_us": t * 1e6, "gbs": pair_bytes / t / 1e9,
+                                     "frac_of_peak": pair_bytes / t / 1e9 / PEAK_GBS,
+                                     "buffer_pairs_rotated": nsets, "footprint_mib": nsets * pair_bytes / 2 ** 20,
+                                     "cache_resident_when_repeated": pair_bytes <= 256e6,
+                                     "t_rotating_us": t_rot * 1e6, "gbs_rotating": pair_bytes / t_rot / 1e9,
+                                     "frac_of_peak_rotating": pair_bytes / t_rot / 1e9 / PEAK_GBS})
+        print(f"[report] transpose {rows}x{cols}: {pair_bytes / t / 1e9:.0f} GB/s on one buffer pair, "
+              f"{pair_bytes / t_rot / 1e9:.0f} GB/s rotating over {nsets}", flush=True)
+        del Xs, Ys
     src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     dst = torch.empty_like(src)
     t, _ = _time_batches(lambda: mt.mtnn_copy_bytes(src, dst), stream, args.samples, 2000.0)
@@ -167,9 +185,12 @@ def main(argv=None):
                 f.write(f"| {r['config']} | {r['m']} | {r['n']} | {r['k']} | {r['bound']} | {r['nt_gflops'] / 1e3:.1f} | "
                         f"{r['tnn_gflops'] / 1e3:.1f} | {r['mtnn_gflops'] / 1e3:.1f} | {r['label']:+d} | "
                         f"{r['nt_roofline_frac']:.2f} | {r['nt_cfg']} | {r['nt_splits']} |\n")
-            f.write("\n| transpose rows x cols | us | GB/s | of 8 TB/s |\n|---|---|---|---|\n")
+            f.write("\n| transpose rows x cols | us | GB/s | of 8 TB/s | fits the 256 MB cache | rotating pairs | us | GB/s | of 8 TB/s |\n")
+            f.write("|---|---|---|---|---|---|---|---|---|\n")
             for r in report["transposes"]:
-                f.write(f"| {r['rows']} x {r['cols']} | {r['t_us']:.1f} | {r['gbs']:.0f} | {r['frac_of_peak']:.2f} |\n")
+                f.write(f"| {r['rows']} x {r['cols']} | {r['t_us']:.1f} | {r['gbs']:.0f} | {r['frac_of_peak']:.2f} | "
+                        f"{'yes' if r['cache_resident_when_repeated'] else 'no'} | {r['buffer_pairs_rotated']} | "
+                        f"{r['t_rotating_us']:.1f} | {r['gbs_rotating']:.0f} | {r['frac_of_peak_rotating']:.2f} |\n")
             f.write(f"\ncopy kernel, 1 GiB: {report['copy_1gib_gbs']:.0f} GB/s\n\n")
             fc = report["fc_step"]
             f.write(f"FC step {fc['dims']} batch {fc['batch']} ({fc['gemm_flop'] / 1e9:.1f} GFLOP of GEMM work): "

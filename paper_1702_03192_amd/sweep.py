@@ -77,6 +77,26 @@ def paper_shapes():
     return out
 
 
+def irregular_shapes(count=384):
+    """Seeded shapes off the power-of-two grids: every dimension log-uniform on [64, 8192]; half of
+    the dimensions are rounded to a multiple of 4 (rows stay 16-byte aligned when ld = width), the
+    other half are left as drawn, so the table also holds shapes only the guarded kernels serve."""
+    from . import inputs
+    e = inputs.uniform_ints(30000, 0, 3 * count, 0, 7 * 1024 - 1).reshape(count, 3)
+    r = inputs.uniform_ints(30000, 1, 3 * count, 0, 1).reshape(count, 3)
+    out = []
+    for i in range(count):
+        dims = []
+        for j in range(3):
+            v = int(64.0 * 2.0 ** (int(e[i, j]) / 1024.0))
+            if r[i, j]:
+                v = max(64, (v // 4) * 4)
+            dims.append(v)
+        out.append((dims[0], dims[1], dims[2], 30000 + i))
+    out.sort(key=lambda s: (s[0] * s[1] * s[2], s))
+    return out
+
+
 def collect(out_path, samples, min_batch_us, limit=None, grid="bench", budget_s=None, mem_limit_gib=None):
     import torch
     from . import binding as mt
@@ -91,7 +111,7 @@ def collect(out_path, samples, min_batch_us, limit=None, grid="bench", budget_s=
                 done.add((int(rec["m"]), int(rec["n"]), int(rec["k"])))
     new_file = not os.path.exists(out_path)
     os.makedirs(os.path.dirname(os.path.abspath(out_path)), exist_ok=True)
-    shapes = paper_shapes() if grid == "paper" else inputs.sweep_shapes()
+    shapes = {"paper": paper_shapes, "irregular": irregular_shapes}.get(grid, inputs.sweep_shapes)()
     if limit:
         shapes = shapes[:limit]
     free_b, total_b = torch.cuda.mem_get_info()
@@ -173,8 +193,9 @@ def main(argv=None):
     c.add_argument("--samples", type=int, default=20)
     c.add_argument("--min-batch-us", type=float, default=2000.0)
     c.add_argument("--limit", type=int, default=None)
-    c.add_argument("--grid", choices=["bench", "paper"], default="bench",
-                   help="bench: {64..8192}^3 (512 shapes); paper: {2^7..2^16}^3 (1000 shapes, Section IV-A)")
+    c.add_argument("--grid", choices=["bench", "paper", "irregular"], default="bench",
+                   help="bench: {64..8192}^3 (512 shapes); paper: {2^7..2^16}^3 (1000 shapes, Section IV-A); "
+                        "irregular: 384 seeded shapes off the power-of-two grids")
     c.add_argument("--budget-s", type=float, default=None, help="cap on the time spent timing one path of one shape")
     c.add_argument("--mem-limit-gib", type=float, default=None, help="drop shapes needing more device memory")
     t = sub.add_parser("train")

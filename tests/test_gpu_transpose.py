@@ -64,6 +64,17 @@ def test_transpose_large_sampled_full_size():
     assert got.tobytes() == want.tobytes()
 
 
+@pytest.mark.parametrize("rows,cols,pad", [(4100, 4204, 0), (4100, 4204, 4),      # 128 x 64 tiles, ragged edges
+                                           (8196, 8260, 0), (8196, 8260, 8),      # 256 x 64 tiles, ragged edges
+                                           (300, 70000, 0), (70000, 300, 4),      # long and thin
+                                           (8195, 8201, 0)])                      # large and not 16-byte friendly
+def test_transpose_large_tile_shapes_with_edges(rows, cols, pad):
+    """The tile shapes used for matrices beyond 2^24 and 2^26 elements, with partial edge tiles and padded rows."""
+    x = I.uniform_pm1(6005, 0, rows, cols)
+    got = run_transpose(x, cols + pad, rows + 2 * pad)
+    assert got.tobytes() == np.ascontiguousarray(oracle.transpose_ref(x)).tobytes()
+
+
 def test_transpose_empty_is_a_noop():
     import torch
     out = Guarded(0, 5)
