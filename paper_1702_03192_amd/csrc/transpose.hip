@@ -167,6 +167,56 @@ int launch_transpose(hipStream_t s, int rows, int cols, const float* in, long ld
 constexpr int IT = 64;
 constexpr int ITP = IT + 1;
 
+// 16-byte-group helpers of the in-place kernel: a 64 x 64 tile at (r0, c0) to LDS, and the transposed
+// LDS tile to the 64 x 64 region at (r0, c0); groups outside the n x n matrix are skipped.
+template <bool NTL>
+__device__ __forceinline__ void inplace_load_tile(const uint32_t* __restrict__ X, long ld, int n, int r0, int c0,
+                                                  u32x4 (&v)[4])
+{
+    const int t = threadIdx.x;
+    const int q = t & 15, rr = t >> 4;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int r = r0 + p * 16 + rr;
+        v[p] = u32x4{0u, 0u, 0u, 0u};
+        if (r < n && c0 + q * 4 < n) {
+            const u32x4* src = reinterpret_cast<const u32x4*>(X + (size_t)r * ld + c0 + q * 4);
+            v[p] = NTL ? __builtin_nontemporal_load(src) : *src;
+        }
+    }
+}
+
+__device__ __forceinline__ void inplace_stash_tile(uint32_t* tile, const u32x4 (&v)[4])
+{
+    const int t = threadIdx.x;
+    const int q = t & 15, rr = t >> 4;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        uint32_t* dst = tile + (p * 16 + rr) * ITP + q * 4;
+        dst[0] = v[p].x; dst[1] = v[p].y; dst[2] = v[p].z; dst[3] = v[p].w;
+    }
+}
+
+// region (r0, c0) <- transpose of the LDS tile: row r of the region is column r of the tile
+__device__ __forceinline__ void inplace_store_transposed(uint32_t* __restrict__ X, long ld, int n, int r0, int c0,
+                                                         const uint32_t* tile)
+{
+    const int t = threadIdx.x;
+    const int q = t & 15, rr = t >> 4;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int r = p * 16 + rr;
+        const uint32_t* src = tile + (q * 4) * ITP + r;
+        u32x4 w;
+        w.x = src[0]; w.y = src[ITP]; w.z = src[2 * ITP]; w.w = src[3 * ITP];
+        if (r0 + r < n && c0 + q * 4 < n)
+            __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(X + (size_t)(r0 + r) * ld + c0 + q * 4));
+    }
+}
+
+// VEC: n and ld multiples of 4 and a 16-byte aligned base, so a 16-byte group is inside or outside
+// the matrix as a whole; otherwise one word per access.
+template <bool VEC, bool NTL>
 __global__ __launch_bounds__(256) void transpose_inplace_kernel(uint32_t* __restrict__ X, int n, long ld)
 {
     const int ti = blockIdx.y, tj = blockIdx.x;
@@ -174,9 +224,20 @@ __global__ __launch_bounds__(256) void transpose_inplace_kernel(uint32_t* __rest
     __shared__ uint32_t ta[IT * ITP];     // tile (ti, tj)
     __shared__ uint32_t tb[IT * ITP];     // tile (tj, ti)
     const int t = threadIdx.x;
+    const int r0 = ti * IT, c0 = tj * IT;
+    if (VEC) {
+        u32x4 va[4], vb[4];
+        inplace_load_tile<NTL>(X, ld, n, r0, c0, va);
+        if (ti != tj) inplace_load_tile<NTL>(X, ld, n, c0, r0, vb);
+        inplace_stash_tile(ta, va);
+        if (ti != tj) inplace_stash_tile(tb, vb);
+        __syncthreads();
+        inplace_store_transposed(X, ld, n, c0, r0, ta);
+        if (ti != tj) inplace_store_transposed(X, ld, n, r0, c0, tb);
+        return;
+    }
     const int lane_c = t & 63;
     const int rbase = t >> 6;
-    const int r0 = ti * IT, c0 = tj * IT;
     for (int r = rbase; r < IT; r += 4) {
         if (r0 + r < n && c0 + lane_c < n) ta[r * ITP + lane_c] = X[(size_t)(r0 + r) * ld + c0 + lane_c];
         if (ti != tj && c0 + r < n && r0 + lane_c < n) tb[r * ITP + lane_c] = X[(size_t)(c0 + r) * ld + r0 + lane_c];
@@ -194,7 +255,14 @@ int launch_transpose_inplace(hipStream_t s, int n, float* X, long ld)
     if (n <= 0) return 0;
     const int nt = (n + IT - 1) / IT;
     if (nt > 65535) return (int)hipErrorInvalidValue;
-    hipLaunchKernelGGL(transpose_inplace_kernel, dim3(nt, nt), dim3(256), 0, s, reinterpret_cast<uint32_t*>(X), n, ld);
+    uint32_t* p = reinterpret_cast<uint32_t*>(X);
+    const bool vec = (n % 4 == 0) && (ld % 4 == 0) && ((reinterpret_cast<uintptr_t>(X) & 15) == 0);
+    if (!vec)
+        hipLaunchKernelGGL((transpose_inplace_kernel<false, false>), dim3(nt, nt), dim3(256), 0, s, p, n, ld);
+    else if ((long long)n * n > (1LL << 24))              // beyond the caches: streaming loads
+        hipLaunchKernelGGL((transpose_inplace_kernel<true, true>), dim3(nt, nt), dim3(256), 0, s, p, n, ld);
+    else
+        hipLaunchKernelGGL((transpose_inplace_kernel<true, false>), dim3(nt, nt), dim3(256), 0, s, p, n, ld);
     return (int)hipGetLastError();
 }
 

@@ -1,7 +1,7 @@
 """Data collection and model fitting for the selector (Section IV-A / IV-B of the MTNN paper).
 
   python -m paper_1702_03192_amd.sweep collect --out gpurun_out/sweep_gfx950.csv     (needs the GPU)
-  python -m paper_1702_03192_amd.sweep train   --csv <table> --model <file>           (host only)
+  python -m paper_1702_03192_amd.sweep train   --csv <table> [<table> ...] --model <file>   (host only)
 
 collect: for every (m, n, k) of the grid {64, ..., 8192}^3 it times the direct NT kernel and TNN
 (transpose + NN through mtnn_tnn, workspace allocated beforehand) and writes one CSV row per
@@ -169,13 +169,21 @@ def collect(out_path, samples, min_batch_us, limit=None, grid="bench", budget_s=
     print(f"[sweep] wrote {out_path}", flush=True)
 
 
-def train(csv_path, model_path, report_path=None):
+def train(csv_paths, model_path, report_path=None):
+    """Fit and evaluate on the union of the given timing tables (a shape listed twice keeps its first row)."""
     from . import binding as mt
     from . import selector_data as sd
-    rows = sd.load_sweep(csv_path)
+    rows, seen = [], set()
+    for path in ([csv_paths] if isinstance(csv_paths, str) else csv_paths):
+        for row in sd.load_sweep(path):
+            key = (row["m"], row["n"], row["k"])
+            if key not in seen:
+                seen.add(key)
+                rows.append(row)
     report = sd.evaluate(rows)                                   # leaves the all-rows model installed
     mt.mtnn_save_model(model_path)
     report["model"] = model_path
+    report["tables"] = [csv_paths] if isinstance(csv_paths, str) else list(csv_paths)
     report["trees"] = mt.lib().mtnn_model_num_trees()
     text = json.dumps(report, indent=1, sort_keys=True)
     print(text)
@@ -199,7 +207,7 @@ def main(argv=None):
     c.add_argument("--budget-s", type=float, default=None, help="cap on the time spent timing one path of one shape")
     c.add_argument("--mem-limit-gib", type=float, default=None, help="drop shapes needing more device memory")
     t = sub.add_parser("train")
-    t.add_argument("--csv", required=True)
+    t.add_argument("--csv", required=True, nargs="+", help="one or more timing tables; the model is fitted on their union")
     t.add_argument("--model", required=True)
     t.add_argument("--report", default=None)
     args = ap.parse_args(argv)

@@ -97,7 +97,8 @@ def test_transpose_involution_on_device():
     assert t2.cpu().numpy().tobytes() == x.tobytes()
 
 
-@pytest.mark.parametrize("n,ld", [(64, 64), (1, 1), (5, 9), (130, 130), (257, 300), (1000, 1000), (4096, 4096)])
+@pytest.mark.parametrize("n,ld", [(64, 64), (1, 1), (5, 9), (130, 130), (257, 300), (1000, 1000), (4096, 4096),
+                                  (72, 76), (4100, 4104), (8192, 8192)])
 def test_inplace_square_transpose_bit_exact(n, ld):
     import torch
     x = I.normal01(6100, 0, n, n)
