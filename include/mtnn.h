@@ -219,6 +219,10 @@ MTNN_API int mtnn_fc_relu_backward(void *stream, long long count, float *dH, con
  * rows are summed in up to 32 chunks by many workgroups and the chunks added in order (NULL: one
  * workgroup per 64 columns walks all rows).  Either way the order is fixed. */
 MTNN_API int mtnn_fc_bias_grad(void *stream, int batch, int width, const float *dZ, float *db, float *scratch);
+/* Both of the above in one pass over the gradient: dH = (H > 0 ? dH : 0) in place, then
+ * db[j] = sum_i dH[i][j]; dH and H batch x width dense, scratch as for mtnn_fc_bias_grad. */
+MTNN_API int mtnn_fc_relu_backward_bias_grad(void *stream, int batch, int width, float *dH, const float *H,
+                                    float *db, float *scratch);
 /* P[e] -= lr * G[e] over `count` elements. */
 MTNN_API int mtnn_fc_sgd(void *stream, long long count, float *P, const float *G, float lr);
 /* dense device-to-device copy of a rows x cols matrix */

@@ -76,6 +76,7 @@ SIGNATURES = {
     "mtnn_fc_softmax_xent": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp, _c_vp, _c_vp, _c_vp]),
     "mtnn_fc_relu_backward": (_c_int, [_c_vp, _c_ll, _c_vp, _c_vp]),
     "mtnn_fc_bias_grad": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp, _c_vp]),
+    "mtnn_fc_relu_backward_bias_grad": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp, _c_vp, _c_vp]),
     "mtnn_fc_sgd": (_c_int, [_c_vp, _c_ll, _c_vp, _c_vp, _c_flt]),
     "mtnn_copy_rows": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp]),
     "mtnn_copy_bytes": (_c_int, [_c_vp, _c_sz, _c_vp, _c_vp]),
@@ -364,6 +365,13 @@ def mtnn_fc_relu_backward(dH, H, stream=None):
 def mtnn_fc_bias_grad(dZ, db, scratch=None, stream=None):
     _check(lib().mtnn_fc_bias_grad(_stream(stream), dZ.shape[0], dZ.shape[1], dZ.data_ptr(), db.data_ptr(),
                                    scratch.data_ptr() if scratch is not None else None), "mtnn_fc_bias_grad")
+
+
+def mtnn_fc_relu_backward_bias_grad(dH, H, db, scratch=None, stream=None):
+    """dH <- where(H > 0, dH, 0) in place and db <- column sums of the result, in one pass."""
+    _check(lib().mtnn_fc_relu_backward_bias_grad(_stream(stream), dH.shape[0], dH.shape[1], dH.data_ptr(), H.data_ptr(),
+                                                 db.data_ptr(), scratch.data_ptr() if scratch is not None else None),
+           "mtnn_fc_relu_backward_bias_grad")
 
 
 def mtnn_fc_sgd(P, G, lr: float, stream=None):

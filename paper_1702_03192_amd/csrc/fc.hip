@@ -127,6 +127,97 @@ __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ P, const f
         P[e] = P[e] - lr * G[e];
 }
 
+// ---- 16-byte versions (width a multiple of 4, 16-byte aligned bases) -----------------------------
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Z[i][c..c+3] += b[c..c+3] (then ReLU): a thread keeps its four bias values and walks the rows of
+// its row chunk, so there is no index division at all
+__global__ __launch_bounds__(256) void bias_act_vec_kernel(float* __restrict__ Z, const float* __restrict__ b,
+                                                           int batch, int width, int rows_per_block, int relu)
+{
+    const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (c >= width) return;
+    const f32x4 bias = *reinterpret_cast<const f32x4*>(b + c);
+    const int r0 = blockIdx.y * rows_per_block;
+    const int r1 = min(batch, r0 + rows_per_block);
+#pragma unroll 4
+    for (int i = r0; i < r1; ++i) {
+        f32x4* z = reinterpret_cast<f32x4*>(Z + (size_t)i * width + c);
+        f32x4 v = *z + bias;
+        if (relu) {
+            v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
+            v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
+        }
+        *z = v;
+    }
+}
+
+// Column sums of one row chunk into part[chunk][col].  A workgroup covers 256 columns (four per
+// lane) and one chunk of rows; its four waves take every fourth row of the chunk and their sums
+// are added in wave order, so the order of the additions is fixed.
+// RELU: first pass dZ through the ReLU mask of H in place (dZ = H > 0 ? dZ : 0), so the gradient
+// is read once for both steps.
+template <bool RELU>
+__global__ __launch_bounds__(256) void colsum_vec_kernel(float* __restrict__ dZ, const float* __restrict__ H,
+                                                         float* __restrict__ part, int batch, int width, int rows_per_chunk)
+{
+    __shared__ f32x4 acc[4][64];
+    const int lane = threadIdx.x & 63;
+    const int sub = threadIdx.x >> 6;
+    const int c = (blockIdx.x * 64 + lane) * 4;
+    const int r0 = blockIdx.y * rows_per_chunk;
+    const int r1 = min(batch, r0 + rows_per_chunk);
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (c < width) {
+#pragma unroll 8
+        for (int i = r0 + sub; i < r1; i += 4) {
+            const size_t off = (size_t)i * width + c;
+            f32x4 g = *reinterpret_cast<const f32x4*>(dZ + off);
+            if (RELU) {
+                const f32x4 h = *reinterpret_cast<const f32x4*>(H + off);
+                g.x = h.x > 0.f ? g.x : 0.f; g.y = h.y > 0.f ? g.y : 0.f;
+                g.z = h.z > 0.f ? g.z : 0.f; g.w = h.w > 0.f ? g.w : 0.f;
+                *reinterpret_cast<f32x4*>(dZ + off) = g;
+            }
+            s += g;
+        }
+    }
+    acc[sub][lane] = s;
+    __syncthreads();
+    if (sub == 0 && c < width)
+        *reinterpret_cast<f32x4*>(part + (size_t)blockIdx.y * width + c) =
+            (acc[0][lane] + acc[1][lane]) + (acc[2][lane] + acc[3][lane]);
+}
+
+// db[col] = sum over chunks of part[chunk][col]: 64 columns per workgroup, its four waves take a
+// quarter of the chunks each (in order), then the four sums are added in wave order
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, int chunks, int width,
+                                                           float* __restrict__ db)
+{
+    __shared__ float acc[4][64];
+    const int lane = threadIdx.x & 63;
+    const int sub = threadIdx.x >> 6;
+    const int col = blockIdx.x * 64 + lane;
+    const int per = (chunks + 3) / 4;
+    float s = 0.f;
+    if (col < width)
+        for (int ch = sub * per; ch < min(chunks, (sub + 1) * per); ++ch) s += part[(size_t)ch * width + col];
+    acc[sub][lane] = s;
+    __syncthreads();
+    if (sub == 0 && col < width) db[col] = (acc[0][lane] + acc[1][lane]) + (acc[2][lane] + acc[3][lane]);
+}
+
+__global__ __launch_bounds__(256) void sgd_vec_kernel(float* __restrict__ P, const float* __restrict__ G, long long total4, float lr)
+{
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total4;
+         e += (long long)gridDim.x * blockDim.x) {
+        f32x4* p = reinterpret_cast<f32x4*>(P) + e;
+        *p = *p - lr * reinterpret_cast<const f32x4*>(G)[e];
+    }
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
 static unsigned blocks_for(long long total)
 {
     long long b = (total + 255) / 256;
@@ -148,6 +239,14 @@ int mtnn_fc_bias_act(void* stream, int batch, int width, float* Z, const float* 
     if (batch == 0 || width == 0) return MTNN_OK;
     if (!Z || !b) return MTNN_ERR_NULL;
     const long long total = (long long)batch * width;
+    if (width % 4 == 0 && mtnn::aligned16(Z) && mtnn::aligned16(b)) {
+        int rows_per_block = 4;
+        if ((batch + rows_per_block - 1) / rows_per_block > 32768) rows_per_block = (batch + 32767) / 32768;
+        const dim3 grid((width / 4 + 255) / 256, (batch + rows_per_block - 1) / rows_per_block);
+        hipLaunchKernelGGL(mtnn::bias_act_vec_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
+                           Z, b, batch, width, rows_per_block, relu);
+        return status_of(hipGetLastError());
+    }
     hipLaunchKernelGGL(mtnn::bias_act_kernel, dim3(mtnn::blocks_for(total)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        Z, b, total, width, relu);
     return status_of(hipGetLastError());
@@ -174,11 +273,30 @@ int mtnn_fc_relu_backward(void* stream, long long count, float* dH, const float*
     return status_of(hipGetLastError());
 }
 
+// Row chunks for the two-stage column sums: at most 32 (the scratch holds 32 x width), at least 32
+// rows each (8 per wave).
+static int colsum_chunks(int batch, int* rows_per_chunk)
+{
+    int chunks = batch / 32;
+    if (chunks > 32) chunks = 32;
+    if (chunks < 1) chunks = 1;
+    *rows_per_chunk = (batch + chunks - 1) / chunks;
+    return (batch + *rows_per_chunk - 1) / *rows_per_chunk;
+}
+
 int mtnn_fc_bias_grad(void* stream, int batch, int width, const float* dZ, float* db, float* scratch)
 {
     if (batch <= 0 || width <= 0) return MTNN_ERR_DIM;
     if (!dZ || !db) return MTNN_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (scratch && width % 4 == 0 && mtnn::aligned16(dZ) && mtnn::aligned16(scratch)) {
+        int rows_per_chunk;
+        const int chunks = colsum_chunks(batch, &rows_per_chunk);
+        hipLaunchKernelGGL(mtnn::colsum_vec_kernel<false>, dim3((width / 4 + 63) / 64, chunks), dim3(256), 0, s,
+                           const_cast<float*>(dZ), static_cast<const float*>(nullptr), scratch, batch, width, rows_per_chunk);
+        hipLaunchKernelGGL(mtnn::colsum_final_kernel, dim3((width + 63) / 64), dim3(256), 0, s, scratch, chunks, width, db);
+        return status_of(hipGetLastError());
+    }
     const int col_blocks = (width + 63) / 64;
     // enough row chunks to put ~512 workgroups on the machine, at most 32, at least 32 rows each
     int chunks = 512 / col_blocks;
@@ -196,11 +314,34 @@ int mtnn_fc_bias_grad(void* stream, int batch, int width, const float* dZ, float
     return status_of(hipGetLastError());
 }
 
+int mtnn_fc_relu_backward_bias_grad(void* stream, int batch, int width, float* dH, const float* H, float* db, float* scratch)
+{
+    if (batch <= 0 || width <= 0) return MTNN_ERR_DIM;
+    if (!dH || !H || !db) return MTNN_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (scratch && width % 4 == 0 && mtnn::aligned16(dH) && mtnn::aligned16(H) && mtnn::aligned16(scratch)) {
+        int rows_per_chunk;
+        const int chunks = colsum_chunks(batch, &rows_per_chunk);
+        hipLaunchKernelGGL(mtnn::colsum_vec_kernel<true>, dim3((width / 4 + 63) / 64, chunks), dim3(256), 0, s,
+                           dH, H, scratch, batch, width, rows_per_chunk);
+        hipLaunchKernelGGL(mtnn::colsum_final_kernel, dim3((width + 63) / 64), dim3(256), 0, s, scratch, chunks, width, db);
+        return status_of(hipGetLastError());
+    }
+    const int st = mtnn_fc_relu_backward(stream, (long long)batch * width, dH, H);
+    if (st != MTNN_OK) return st;
+    return mtnn_fc_bias_grad(stream, batch, width, dH, db, scratch);
+}
+
 int mtnn_fc_sgd(void* stream, long long count, float* P, const float* G, float lr)
 {
     if (count < 0) return MTNN_ERR_DIM;
     if (count == 0) return MTNN_OK;
     if (!P || !G) return MTNN_ERR_NULL;
+    if (count % 4 == 0 && mtnn::aligned16(P) && mtnn::aligned16(G)) {
+        hipLaunchKernelGGL(mtnn::sgd_vec_kernel, dim3(mtnn::blocks_for(count / 4)), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), P, G, count / 4, lr);
+        return status_of(hipGetLastError());
+    }
     hipLaunchKernelGGL(mtnn::sgd_kernel, dim3(mtnn::blocks_for(count)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        P, G, count, lr);
     return status_of(hipGetLastError());
@@ -299,8 +440,10 @@ static int fc_run(void* stream, const mtnn_fc_step_desc* d, bool forward_only)
     // backward, last layer first
     for (int l = L - 1; l >= 0; --l) {
         const int in = dims[l], out = dims[l + 1];
-        st = mtnn_fc_bias_grad(stream, batch, out, dZ, d->db[l], bias_part);
-        if (st != MTNN_OK) return st;
+        if (l == L - 1) {                      // below, db comes with the ReLU mask of the layer above
+            st = mtnn_fc_bias_grad(stream, batch, out, dZ, d->db[l], bias_part);
+            if (st != MTNN_OK) return st;
+        }
         // dW_l = dZ^T x H_l : transpose dZ (batch x out -> out x batch), then an NN product
         st = mtnn_transpose(stream, batch, out, dZ, out, dZt, batch);
         if (st != MTNN_OK) return st;
@@ -310,7 +453,8 @@ static int fc_run(void* stream, const mtnn_fc_step_desc* d, bool forward_only)
             // dH_l = dZ x W_l (NN, with the weights before their update), then through the ReLU
             st = mtnn_nn(stream, batch, in, out, dZ, out, d->W[l], in, dNext, in);
             if (st != MTNN_OK) return st;
-            st = mtnn_fc_relu_backward(stream, (long long)batch * in, dNext, H[l]);
+            // ... which gives dZ_{l-1}; its column sums are db_{l-1}, taken in the same pass
+            st = mtnn_fc_relu_backward_bias_grad(stream, batch, in, dNext, H[l], d->db[l - 1], bias_part);
             if (st != MTNN_OK) return st;
         }
         st = mtnn_fc_sgd(stream, (long long)out * in, d->W[l], d->dW[l], d->lr);

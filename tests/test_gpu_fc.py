@@ -114,6 +114,38 @@ def test_config5_step(mode):
     check_step(cfg["dims"], cfg["batch"], cfg["seed"], mode)
 
 
+@pytest.mark.parametrize("batch,width", [(50, 72), (1000, 200), (1024, 4096), (33, 8)])
+def test_elementwise_16_byte_paths_against_numpy(batch, width):
+    """Widths that are multiples of 4 take the 16-byte kernels: bias + ReLU, ReLU mask with the bias
+    gradient in the same pass (with and without scratch), SGD."""
+    import torch
+    z = I.normal01(5310, 0, batch, width)
+    bias = I.normal01(5310, 1, 1, width)[0]
+    g = I.normal01(5310, 2, batch, width)
+    for relu in (True, False):
+        Z = torch.from_numpy(z.copy()).cuda()
+        mt.mtnn_fc_bias_act(Z, torch.from_numpy(bias).cuda(), relu)
+        want = z + bias
+        assert np.array_equal(Z.cpu().numpy(), np.maximum(want, np.float32(0)) if relu else want)
+    H = np.maximum(z, np.float32(0))
+    masked = np.where(H > 0, g, np.float32(0))
+    want_db = masked.astype(np.float64).sum(0)
+    # fp32 summation in any order: |error| <= (rows - 1) 2^-24 sum |x| per column
+    tol_db = batch * 2.0 ** -24 * np.abs(masked).astype(np.float64).sum(0).max()
+    for scratch in (torch.empty(32 * width, device="cuda"), None):
+        dH = torch.from_numpy(g.copy()).cuda()
+        db = torch.full((width,), float("nan"), device="cuda")
+        mt.mtnn_fc_relu_backward_bias_grad(dH, torch.from_numpy(H).cuda(), db, scratch)
+        assert np.array_equal(dH.cpu().numpy(), masked)
+        assert np.abs(db.cpu().numpy() - want_db).max() <= tol_db
+        db2 = torch.full((width,), float("nan"), device="cuda")
+        mt.mtnn_fc_bias_grad(dH, db2, scratch)
+        assert np.abs(db2.cpu().numpy() - want_db).max() <= tol_db
+    P = torch.from_numpy(z.copy()).cuda()
+    mt.mtnn_fc_sgd(P, torch.from_numpy(g).cuda(), 0.25)
+    assert np.array_equal(P.cpu().numpy(), z - np.float32(0.25) * g)
+
+
 def test_elementwise_steps_against_numpy():
     import torch
     rng_z = I.normal01(5300, 0, 50, 70)
