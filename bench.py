@@ -191,6 +191,14 @@ def main() -> int:
     selector["select_ns_per_call_incl_ctypes"] = (te - ts) / n_calls * 1e9
     selector["ctypes_call_overhead_ns"] = (tf - tb) / n_calls * 1e9
 
+    props = torch.cuda.get_device_properties(0)
+    cus, clock_khz = mt.mtnn_device_attribute(0), mt.mtnn_device_attribute(1)
+    mem_khz, bus_bits = mt.mtnn_device_attribute(2), mt.mtnn_device_attribute(3)
+    device = {"name": props.name, "compute_units": cus, "max_clock_mhz": clock_khz / 1e3,
+              # 256 fp32 matrix flop per clock per CU (4 SIMDs x one 32x32x2 MFMA per 16 passes of 4 clocks)
+              "fp32_mfma_peak_from_attributes_tflops": cus * clock_khz * 1e3 * 256 / 1e12 if cus > 0 and clock_khz > 0 else None,
+              "memory_clock_mhz": mem_khz / 1e3, "memory_bus_bits": bus_bits,
+              "hbm_gib": props.total_memory / 2 ** 30}
     nt_splits = [mt.mtnn_gemm_default_splits(mt.OP_NT, *w["shape"]) for w in work]
     out = {
         "metric": "NT GFLOP/s (2mnk/t, fp32)", "value": value, "unit": "GFLOP/s",
@@ -200,7 +208,7 @@ def main() -> int:
                                "mtnn_nt, mtnn_transpose+mtnn_nn, mtnn_tnn, mtnn_select+mtnn_auto",
                    "nt_products_per_step": products_per_shape * len(work), "nt_split_k": nt_splits},
         "roofline": roofline, "kernels": other, "per_shape": per_shape,
-        "copy_kernel_gbs": copy_gbs, "selector": selector,
+        "copy_kernel_gbs": copy_gbs, "selector": selector, "device": device,
     }
 
     if not args.no_cpu_baseline:

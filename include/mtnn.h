@@ -242,6 +242,10 @@ MTNN_API const char *mtnn_status_string(int status);
 /* The hipError_t behind the most recent MTNN_ERR_LAUNCH in this process (0 if none); diagnostics. */
 MTNN_API int mtnn_last_hip_error(void);
 MTNN_API int mtnn_version(void);
+/* A property of the current device, for reports: what = 0 compute units, 1 peak shader clock in kHz,
+ * 2 peak memory clock in kHz, 3 memory bus width in bits.  Returns -1 if it cannot be read (no device,
+ * unknown `what`). */
+MTNN_API int mtnn_device_attribute(int what);
 
 #ifdef __cplusplus
 }

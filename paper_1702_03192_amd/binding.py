@@ -7,6 +7,7 @@ been built the import of any entry point raises.
 from __future__ import annotations
 
 import ctypes
+import threading
 import os
 from typing import Optional
 
@@ -83,6 +84,7 @@ SIGNATURES = {
     "mtnn_status_string": (ctypes.c_char_p, [_c_int]),
     "mtnn_last_hip_error": (_c_int, []),
     "mtnn_version": (_c_int, []),
+    "mtnn_device_attribute": (_c_int, [_c_int]),
 }
 
 _lib = None
@@ -140,6 +142,9 @@ def _dev(t, name):
         raise TypeError(f"{name} must have unit column stride")
     ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], 1)
     return t.data_ptr(), int(ld)
+
+
+_tls = threading.local()      # per-thread out-parameter of mtnn_auto, allocated once
 
 
 def _ws(workspace):
@@ -229,9 +234,11 @@ def mtnn_auto(A, B, C, workspace=None, stream=None) -> int:
     m, k = A.shape
     n = B.shape[0]
     pw, wb = _ws(workspace)
-    chosen = ctypes.c_int(0)
-    _check(lib().mtnn_auto(_stream(stream), m, n, k, pa, lda, pb, ldb, pc, ldc, pw, wb, ctypes.byref(chosen)),
-           "mtnn_auto")
+    chosen = getattr(_tls, "chosen", None)
+    if chosen is None:
+        chosen = _tls.chosen = ctypes.c_int(0)
+        _tls.chosen_ref = ctypes.byref(chosen)
+    _check(lib().mtnn_auto(_stream(stream), m, n, k, pa, lda, pb, ldb, pc, ldc, pw, wb, _tls.chosen_ref), "mtnn_auto")
     return chosen.value
 
 
@@ -393,6 +400,11 @@ def mtnn_gemm_default_splits(op: int, m: int, n: int, k: int) -> int:
 
 def mtnn_status_string(status: int) -> str:
     return lib().mtnn_status_string(status).decode()
+
+
+def mtnn_device_attribute(what: int) -> int:
+    """0 compute units, 1 peak shader clock (kHz), 2 peak memory clock (kHz), 3 memory bus width (bits); -1 if unknown."""
+    return int(lib().mtnn_device_attribute(what))
 
 
 def mtnn_version() -> int:

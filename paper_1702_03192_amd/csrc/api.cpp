@@ -228,4 +228,17 @@ int mtnn_last_hip_error(void) { return g_last_hip_error; }
 
 int mtnn_version(void) { return 100; }
 
+int mtnn_device_attribute(int what)
+{
+    static const hipDeviceAttribute_t attrs[4] = {hipDeviceAttributeMultiprocessorCount, hipDeviceAttributeClockRate,
+                                                  hipDeviceAttributeMemoryClockRate, hipDeviceAttributeMemoryBusWidth};
+    if (what < 0 || what > 3) return -1;
+    int dev = 0, value = -1;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&value, attrs[what], dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return -1;
+    }
+    return value;
+}
+
 }  // extern "C"

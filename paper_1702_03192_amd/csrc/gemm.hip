@@ -28,6 +28,7 @@
 // results are bit-reproducible.
 #include "mtnn_internal.h"
 
+#include <cstdlib>
 #include <mutex>
 
 namespace mtnn {
@@ -767,7 +768,12 @@ struct Config {
     int nstage;
     int threads;
     int waves_n;
-    float eff;                        // measured fraction of the fp32 MFMA peak with every CU busy
+    // Fitted to measured times of the {64..8192}^3 grid with every CU busy:
+    // time of one CU = tiles x (2 bm bn k / (eff x peak per CU)) + rounds x round_s
+    // (separately for NN and NT: index = GemmOp)
+    float eff[2];                     // rate of the k loop as a fraction of the fp32 MFMA peak
+    float round_s[2];                 // seconds per round outside the k loop: first copies, result store
+    int max_wg;                       // workgroups per CU the launch allows (it sizes its LDS request to that)
     // LDS bytes of the guarded kernel: two buffers of an A slab and a B slab (layouts as in the kernel)
     size_t lds_bytes(int op) const
     {
@@ -788,8 +794,7 @@ struct Config {
     int wg_per_cu() const
     {
         const int by_lds = (int)((160 * 1024) / lds_bytes_dma());
-        const int by_thr = threads >= 512 ? 1 : 2;     // registers: one 8-wave or two 4-wave workgroups
-        const int r = by_lds < by_thr ? by_lds : by_thr;
+        const int r = by_lds < max_wg ? by_lds : max_wg;
         return r < 1 ? 1 : r;
     }
 };
@@ -799,22 +804,29 @@ struct Config {
      {gemm_kernel<BM, BN, BK, WMV, WNV, true, false>, gemm_kernel<BM, BN, BK, WMV, WNV, true, true>}}
 
 // pipelined kernel with NS slab buffers, and the guarded kernel (slab GBK) that serves what it cannot
-#define MTNN_CFG_DMA(BM, BN, BK, WMV, WNV, NS, GBK, EFF)                                      \
-    { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV "_dma" #NS, BM, BN, BK, MTNN_GUARDED(BM, BN, GBK, WMV, WNV), \
+#define MTNN_CFG_DMA(BM, BN, BK, WMV, WNV, NS, GBK, MAXWG, EFF_NN, RND_NN, EFF_NT, RND_NT)                                    \
+    { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV "_dma" #NS "_x" #MAXWG, BM, BN, BK, MTNN_GUARDED(BM, BN, GBK, WMV, WNV), \
       {gemm_dma_kernel<BM, BN, BK, WMV, WNV, false, NS>, gemm_dma_kernel<BM, BN, BK, WMV, WNV, true, NS>}, \
-      NS, WMV * WNV * 64, WNV, EFF }
+      NS, WMV * WNV * 64, WNV, {EFF_NN, EFF_NT}, {RND_NN, RND_NT}, MAXWG }
 
 static const Config kConfigs[] = {
-    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2, 16, 0.943f),   // 0: 8 waves of 64 x 128, 128 KB of LDS
-    MTNN_CFG_DMA(256, 128, 16, 2, 2, 3, 16, 0.940f),   // 1: 4 waves of 128 x 64, 72 KB: two per CU
-    MTNN_CFG_DMA(128, 128, 64, 4, 2, 2, 16, 0.900f),   // 2: 8 waves of 32 x 64, 128 KB
-    MTNN_CFG_DMA(64, 64, 64, 2, 2, 2, 16, 0.887f),     // 3: 4 waves of 32 x 32, 64 KB: two per CU
-    MTNN_CFG_DMA(32, 256, 32, 1, 4, 4, 16, 0.670f),    // 4: 4 waves of 32 x 64 (small m)
-    MTNN_CFG_DMA(256, 32, 32, 4, 1, 4, 16, 0.650f),    // 5: 4 waves of 64 x 32 (small n)
-    MTNN_CFG_DMA(128, 256, 32, 2, 4, 2, 16, 0.925f),   // 6: 8 waves of 64 x 64, 96 KB
-    MTNN_CFG_DMA(256, 128, 32, 4, 2, 2, 16, 0.920f),   // 7: 8 waves of 64 x 64, 96 KB
-    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16, 0.897f),    // 8: 4 waves of 64 x 32
-    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16, 0.928f),    // 9: 4 waves of 32 x 64
+    //           tile         waves stages    per CU   NN: eff, round      NT: eff, round
+    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2, 16,   1,   0.958f, 15.1e-6f,   0.956f, 15.1e-6f),  // 0: 8 waves of 64 x 128, 128 KB of LDS
+    // (1: the NN fit gave 0.959, level with configuration 0 inside the grid; beyond it the narrower tile
+    //  re-reads more of A and falls behind -- 135 against 148 TFLOP/s at 65536^3 -- so it is rated just below)
+    MTNN_CFG_DMA(256, 128, 16, 2, 2, 3, 16,   2,   0.952f, 13.0e-6f,   0.950f, 13.8e-6f),  // 1: 4 waves of 128 x 64, 72 KB
+    MTNN_CFG_DMA(128, 128, 64, 4, 2, 2, 16,   1,   0.890f, 4.7e-6f,    0.888f, 4.6e-6f),   // 2: 8 waves of 32 x 64, 128 KB
+    MTNN_CFG_DMA(64, 64, 64, 2, 2, 2, 16,     2,   0.859f, 3.1e-6f,    0.850f, 2.5e-6f),   // 3: 4 waves of 32 x 32, 64 KB
+    // (4, 5: fitted with four slab buffers and one workgroup per CU; two buffers and two per CU measured 4 % faster)
+    MTNN_CFG_DMA(32, 256, 32, 1, 4, 2, 16,    2,   0.688f, 2.5e-6f,    0.683f, 2.6e-6f),   // 4: 4 waves of 32 x 64 (small m), 72 KB
+    MTNN_CFG_DMA(256, 32, 32, 4, 1, 2, 16,    2,   0.672f, 3.4e-6f,    0.679f, 2.7e-6f),   // 5: 4 waves of 64 x 32 (small n), 72 KB
+    MTNN_CFG_DMA(128, 256, 32, 2, 4, 2, 16,   1,   0.936f, 7.9e-6f,    0.929f, 7.8e-6f),   // 6: 8 waves of 64 x 64, 96 KB
+    MTNN_CFG_DMA(256, 128, 32, 4, 2, 2, 16,   1,   0.930f, 8.3e-6f,    0.932f, 8.3e-6f),   // 7: 8 waves of 64 x 64, 96 KB
+    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16,    2,   0.881f, 4.4e-6f,    0.897f, 3.3e-6f),   // 8: 4 waves of 64 x 32, 48 KB
+    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16,    2,   0.899f, 3.6e-6f,    0.903f, 3.3e-6f),   // 9: 4 waves of 32 x 64, 48 KB
+    MTNN_CFG_DMA(128, 128, 32, 2, 2, 2, 16,   2,   0.943f, 6.2e-6f,    0.942f, 6.1e-6f),   // 10: 4 waves of 64 x 64, 64 KB
+    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16,    3,   0.843f, 4.1e-6f,    0.907f, 2.8e-6f),   // 11: as 8, three per CU (small k)
+    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16,    3,   0.907f, 3.6e-6f,    0.914f, 3.2e-6f),   // 12: as 9, three per CU (small k)
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 constexpr int kMaxSplits = 32;
@@ -854,13 +866,14 @@ float* scratch_for(hipStream_t s)
 //
 // A small cost model, evaluated for every configuration and split count; the cheapest wins, ties go
 // to the earlier (larger) configuration.  For a candidate: workgroups = tiles x splits are dealt
-// evenly to the 256 CUs; a CU works through its share at the configuration's measured rate, less if
-// it holds fewer workgroups than it could overlap; every workgroup pays a fixed prologue/epilogue;
+// evenly to the 256 CUs; a CU works through its share at the configuration's fitted k-loop rate, less if
+// it holds fewer workgroups than it could overlap; every round of resident workgroups pays the
+// configuration's fitted time outside the k loop (first copies, result store);
 // split-k adds the traffic of writing and re-reading the partial products.  The choice depends only
 // on (op, m, n, k), never on timing, so results stay reproducible.
 struct Choice { int cfg; int splits; };
 
-static double predicted_seconds(const Config& c, int m, int n, int k, int splits)
+static double predicted_seconds(const Config& c, int op, int m, int n, int k, int splits)
 {
     const double peak_cu = 157.3e12 / 256.0;
     const long long tiles = (long long)((m + c.bm - 1) / c.bm) * ((n + c.bn - 1) / c.bn);
@@ -871,18 +884,18 @@ static double predicted_seconds(const Config& c, int m, int n, int k, int splits
     if (splits == 1) kloc = k;
     const int occ = c.wg_per_cu();
     // a CU that holds a single 4-wave workgroup keeps only one wave per SIMD busy
-    const double solo = (c.threads < 512 && per_cu < occ) ? 0.90 : 1.0;
+    const double solo = (c.threads < 512 && per_cu < occ) ? 0.85 : 1.0;
     const double wg_flops = 2.0 * c.bm * c.bn * (double)kloc;
-    double t = (double)per_cu * wg_flops / (peak_cu * c.eff * solo);
-    t += 2.5e-6 * (double)((per_cu + occ - 1) / occ);            // prologue + epilogue per round
+    double t = (double)per_cu * wg_flops / (peak_cu * c.eff[op] * solo);
+    t += (double)c.round_s[op] * (double)((per_cu + occ - 1) / occ);  // first copies + result store per round
     // HBM floor: operands once, result once
     const double bytes = 4.0 * ((double)m * k + (double)n * k + (double)m * n);
     if (t < bytes / 5.0e12) t = bytes / 5.0e12;
-    if (splits > 1) t += 4.0e-6 + 0.2e-6 * splits + 4.0 * (double)m * n * (splits + 2) / 4.0e12;
+    if (splits > 1) t += 2.0e-6 + 0.3e-6 * splits + 4.0 * (double)m * n * (splits + 2) / 4.0e12;
     return t + 3.0e-6;
 }
 
-static Choice choose(int /*op*/, int m, int n, int k, bool allow_split)
+static Choice choose(int op, int m, int n, int k, bool allow_split)
 {
     Choice best = {0, 1};
     double best_t = 1e30;
@@ -893,7 +906,7 @@ static Choice choose(int /*op*/, int m, int n, int k, bool allow_split)
                 if ((size_t)m * n * splits * sizeof(float) > kScratchBytes) break;
                 if (k / splits < 2 * kSplitQuantum) break;
             }
-            const double t = predicted_seconds(kConfigs[c], m, n, k, splits);
+            const double t = predicted_seconds(kConfigs[c], op == OP_NT ? 1 : 0, m, n, k, splits);
             if (t < best_t * 0.999) { best_t = t; best = Choice{c, splits}; }
         }
     }
@@ -958,10 +971,15 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
     guarded.bk = 16;
     size_t lds = dma_ok ? c.lds_bytes_dma() : guarded.lds_bytes(op);
     if (dma_ok) {
-        // Ask for at least 1/wg_per_cu of the CU's LDS: no CU can then take more workgroups than the
-        // cost model assumed, so a grid of exactly 256 x wg_per_cu workgroups spreads evenly instead
-        // of piling three on some CUs and one on others.
-        const size_t share = ((160 * 1024) / (size_t)c.wg_per_cu()) & ~(size_t)1023;
+        // Ask for at least 1/want of the CU's LDS, want = the workgroups a CU should hold at a time (the
+        // configuration's limit, or fewer if the grid has fewer per CU): no CU can then take more than
+        // the cost model assumed, so a grid of exactly 256 x want workgroups spreads evenly instead of
+        // piling three on some CUs and one on others.
+        long long per_cu_wgs = (total + 255) / 256;
+        int want = c.wg_per_cu();
+        if (per_cu_wgs < want) want = (int)per_cu_wgs;
+        if (want < 1) want = 1;
+        const size_t share = ((160 * 1024) / (size_t)want) & ~(size_t)1023;
         const size_t floor_bytes = share > 1024 ? share - 1024 : share;
         if (lds < floor_bytes) lds = floor_bytes;
     }
@@ -972,8 +990,9 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess) return (int)hipGetLastError();
         if (dev < 0 || dev >= 16 || !raised[cfg][op][which][dev]) {
+            // (to the whole 160 KB: the request below varies with the grid)
             const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             if (e != hipSuccess) return (int)e;
             if (dev >= 0 && dev < 16) raised[cfg][op][which][dev] = true;
         }

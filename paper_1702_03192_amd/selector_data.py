@@ -22,6 +22,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 DATA = os.path.join(HERE, "data")
 SWEEP_CSV = os.path.join(DATA, "sweep_gfx950.csv")
 MODEL_FILE = os.path.join(DATA, "selector_gfx950.model")
+# the shipped model is fitted on the union of the three measured tables: the benchmark grid
+# {64..8192}^3, the paper's range {2^7..2^16}^3 and the seeded shapes off the power-of-two grids
+TRAINING_TABLES = (SWEEP_CSV, os.path.join(DATA, "sweep_irregular_gfx950.csv"),
+                   os.path.join(DATA, "sweep_paper_range_gfx950.csv"))
 TRAFFIC_JSON = os.path.join(DATA, "measured_traffic_gfx950.json")
 
 
@@ -39,6 +43,21 @@ def load_sweep(path: str = SWEEP_CSV) -> List[Dict[str, float]]:
                 else:
                     row[key] = float(val)
             rows.append(row)
+    return rows
+
+
+def load_training_rows(paths: Optional[Sequence[str]] = None) -> List[Dict[str, float]]:
+    """Union of the given timing tables (default: the shipped ones that exist); a shape listed in
+    more than one table keeps its first row."""
+    rows, seen = [], set()
+    for path in (TRAINING_TABLES if paths is None else paths):
+        if paths is None and not os.path.exists(path):
+            continue
+        for row in load_sweep(path):
+            key = (row["m"], row["n"], row["k"])
+            if key not in seen:
+                seen.add(key)
+                rows.append(row)
     return rows
 
 

@@ -173,17 +173,13 @@ def train(csv_paths, model_path, report_path=None):
     """Fit and evaluate on the union of the given timing tables (a shape listed twice keeps its first row)."""
     from . import binding as mt
     from . import selector_data as sd
-    rows, seen = [], set()
-    for path in ([csv_paths] if isinstance(csv_paths, str) else csv_paths):
-        for row in sd.load_sweep(path):
-            key = (row["m"], row["n"], row["k"])
-            if key not in seen:
-                seen.add(key)
-                rows.append(row)
+    if isinstance(csv_paths, str):
+        csv_paths = [csv_paths]
+    rows = sd.load_training_rows(csv_paths)
     report = sd.evaluate(rows)                                   # leaves the all-rows model installed
     mt.mtnn_save_model(model_path)
     report["model"] = model_path
-    report["tables"] = [csv_paths] if isinstance(csv_paths, str) else list(csv_paths)
+    report["tables"] = list(csv_paths) if csv_paths else [os.path.basename(p) for p in sd.TRAINING_TABLES if os.path.exists(p)]
     report["trees"] = mt.lib().mtnn_model_num_trees()
     text = json.dumps(report, indent=1, sort_keys=True)
     print(text)
@@ -207,7 +203,8 @@ def main(argv=None):
     c.add_argument("--budget-s", type=float, default=None, help="cap on the time spent timing one path of one shape")
     c.add_argument("--mem-limit-gib", type=float, default=None, help="drop shapes needing more device memory")
     t = sub.add_parser("train")
-    t.add_argument("--csv", required=True, nargs="+", help="one or more timing tables; the model is fitted on their union")
+    t.add_argument("--csv", nargs="+", default=None,
+                   help="one or more timing tables; the model is fitted on their union (default: the shipped tables)")
     t.add_argument("--model", required=True)
     t.add_argument("--report", default=None)
     args = ap.parse_args(argv)

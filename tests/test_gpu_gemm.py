@@ -14,7 +14,7 @@ from gpu_util import Guarded, check_gemm, dev_matrix
 
 pytestmark = pytest.mark.gpu
 
-NCFG = 10
+NCFG = 13
 
 
 def sync():
@@ -315,3 +315,15 @@ def test_huge_leading_dimensions(case):
     check_gemm(got, Cref, Sref, k, case)
     del dA, dB
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("op", [mt.OP_NT, mt.OP_NN], ids=["NT", "NN"])
+@pytest.mark.parametrize("cfg", [10, 11, 12])
+def test_several_workgroups_per_cu_on_a_full_grid(op, cfg):
+    """Configurations that put two or three workgroups on a CU, on a grid large enough that every CU
+    really holds that many (768+ tiles), with a ragged last slab."""
+    m, n, k = 3072, 2048, 72
+    A, B = operands(op, m, n, k, 900 + cfg)
+    got = run(op, cfg, A, B)
+    C, S = reference(op, A, B)
+    check_gemm(got, C, S, k, f"op{op} cfg{cfg}")

@@ -189,11 +189,12 @@ def test_shipped_model_agrees_with_an_independent_evaluator_on_grid_and_random_s
 
 
 def test_trained_on_the_shipped_sweep_table_trainer_parity():
-    """The library's trainer and the oracle's, on the real MI355X timing table."""
+    """The library's trainer and the oracle's, on the real MI355X timing tables (the union the shipped
+    model is fitted on)."""
     from paper_1702_03192_amd import selector_data as sd
     if not os.path.exists(sd.SWEEP_CSV):
         pytest.skip("no shipped sweep table")
-    rows = sd.load_sweep()
+    rows = sd.load_training_rows()
     shapes = [(r["m"], r["n"], r["k"]) for r in rows]
     labels = [S.label_from_times(r["t_nt"], r["t_tnn"]) for r in rows]
     assert labels == [sd.label_of(r["t_nt"], r["t_tnn"]) for r in rows]
