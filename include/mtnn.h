@@ -163,13 +163,22 @@ MTNN_API int mtnn_model_margin(const double *x, int nfeat, double *margin);
  * the model's choice when cfg is -1 and no split when cfg is given).  op: 0 = NN, 1 = NT.
  * Split-k keeps its partial products in a 64 MiB scratch buffer that the library allocates once per
  * (device, stream) the first time it is needed and never frees; a launch whose partials do not fit
- * runs unsplit. */
+ * runs unsplit.
+ * splits = MTNN_GEMM_EVEN_CUT asks for the third way of dividing the work: the k ranges of all C
+ * tiles, in units of 64, are laid in one line and cut into 256 x (workgroups per CU) equal pieces,
+ * one per workgroup; tiles that a cut goes through are finished by a fix-up kernel that adds their
+ * pieces in k order (same scratch buffer, same reproducibility).  It runs only where the pipelined
+ * kernel can (16-byte aligned operands, k % 4 = 0, ...), there are at least as many units as pieces
+ * and the scratch fits; otherwise the call runs unsplit.  mtnn_gemm_default_splits may return it. */
+#define MTNN_GEMM_EVEN_CUT (-2)
 MTNN_API int mtnn_gemm_config_count(void);
 MTNN_API const char *mtnn_gemm_config_name(int cfg);
 MTNN_API int mtnn_gemm_default_config(int op, int m, int n, int k);
 MTNN_API int mtnn_gemm_default_splits(int op, int m, int n, int k);
 MTNN_API int mtnn_gemm_ex(void *stream, int op, int cfg, int splits, int m, int n, int k,
                  const float *A, int lda, const float *B, int ldb, float *C, int ldc);
+/* How many launches of this process took the even-cut path (diagnostics, tests). */
+MTNN_API long long mtnn_gemm_even_cut_launches(void);
 
 /* ---- one training step of a fully connected net (Section V-C, Table IX sizes) ---------------- */
 

@@ -84,6 +84,7 @@ SIGNATURES = {
     "mtnn_status_string": (ctypes.c_char_p, [_c_int]),
     "mtnn_last_hip_error": (_c_int, []),
     "mtnn_version": (_c_int, []),
+    "mtnn_gemm_even_cut_launches": (ctypes.c_longlong, []),
     "mtnn_device_attribute": (_c_int, [_c_int]),
 }
 
@@ -400,6 +401,13 @@ def mtnn_gemm_default_splits(op: int, m: int, n: int, k: int) -> int:
 
 def mtnn_status_string(status: int) -> str:
     return lib().mtnn_status_string(status).decode()
+
+
+EVEN_CUT = -2      # `splits` value of mtnn_gemm_ex: cut all tiles' k ranges evenly over a fixed grid
+
+
+def mtnn_gemm_even_cut_launches() -> int:
+    return int(lib().mtnn_gemm_even_cut_launches())
 
 
 def mtnn_device_attribute(what: int) -> int:

@@ -100,7 +100,7 @@ int mtnn_gemm_ex(void* stream, int op, int cfg, int splits, int m, int n, int k,
                  const float* B, int ldb, float* C, int ldc)
 {
     if ((op != mtnn::OP_NN && op != mtnn::OP_NT) || cfg < -1 || cfg >= mtnn::gemm_config_count() ||
-        splits < 0 || splits > 32)
+        (splits < 0 && splits != MTNN_GEMM_EVEN_CUT) || splits > 32)
         return MTNN_ERR_ARG;
     return run_gemm(stream, op, cfg, splits, m, n, k, A, lda, B, ldb, C, ldc);
 }
@@ -227,6 +227,8 @@ const char* mtnn_status_string(int status)
 int mtnn_last_hip_error(void) { return g_last_hip_error; }
 
 int mtnn_version(void) { return 100; }
+
+long long mtnn_gemm_even_cut_launches(void) { return mtnn::gemm_streamk_launches(); }
 
 int mtnn_device_attribute(int what)
 {

@@ -28,6 +28,7 @@
 // results are bit-reproducible.
 #include "mtnn_internal.h"
 
+#include <atomic>
 #include <cstdlib>
 #include <mutex>
 
@@ -51,7 +52,10 @@ struct GemmParams {
     int splits;
     int k_per_split;  // a multiple of every configuration's k slab
     float* part;
+    int sk_units_per_tile;   // gemm_streamk_kernel: k units (of kSplitQuantum) per tile
 };
+
+constexpr int kSplitQuantumDev = 64;   // k ranges of split work are multiples of this (every slab size divides it)
 
 // what one workgroup works on: its k range of A and B, and where its tile of results goes
 struct WorkView {
@@ -462,6 +466,16 @@ __device__ __forceinline__ void dma_chunk_s(const float* base, unsigned lane_off
                  :: "v"(lane_off), "s"(base), "s"(lds_base) : "memory", "m0");
 }
 
+// A wave-uniform pointer the compiler may have computed on the vector unit, moved to scalar registers
+// (the copies take their base address there).
+__device__ __forceinline__ const float* uniform_ptr(const float* p)
+{
+    const uintptr_t v = reinterpret_cast<uintptr_t>(p);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return reinterpret_cast<const float*>(((uintptr_t)hi << 32) | lo);
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
@@ -480,8 +494,12 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("" ::: "memory");
 }
 
+// One segment of work of the pipelined kernel: the k range and destination described by `w`, for
+// C tile (tm, tn).  The whole workgroup calls it; it leaves no copies in flight, and its last LDS
+// accesses (the epilogue's staging) are this wave's own, so a caller that runs several segments
+// needs one workgroup barrier between them.
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmParams p)
+__device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView& w, const int tm, const int tn)
 {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M;
@@ -521,9 +539,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
     const int wm0 = (wave / WAVES_N) * WM;
     const int wn0 = (wave % WAVES_N) * WN;
 
-    const WorkView w = work_view(p, NT);
-    int tm, tn;
-    tile_of_block(p, w.pid, tm, tn);
     const int m0 = tm * BM;
     const int n0 = tn * BN;
     const int M = p.M, N = p.N, K = w.K;
@@ -534,8 +549,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
     // place), so every issuing wave issues exactly LPS copies per slab.
     const int grp = wave / NI;
     const int wi = wave % NI;
-    const float* a_tile = w.A + (size_t)m0 * p.lda;
-    const float* b_tile = NT ? w.B + (size_t)n0 * p.ldb : w.B;
+    const float* a_tile = uniform_ptr(w.A + (size_t)m0 * p.lda);
+    const float* b_tile = uniform_ptr(NT ? w.B + (size_t)n0 * p.ldb : w.B);
     unsigned a_off[A_LOADS], a_dst[A_LOADS];
     int a_k[A_LOADS];
 #pragma unroll
@@ -742,6 +757,155 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmPar
     }
 }
 
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmParams p)
+{
+    const WorkView w = work_view(p, NT);
+    int tm, tn;
+    tile_of_block(p, w.pid, tm, tn);
+    dma_segment<BM, BN, BK, WAVES_M, WAVES_N, NT, NSTAGE>(p, w, tm, tn);
+}
+
+// ---- even split of the whole k x tiles work over a fixed number of workgroups -------------------
+//
+// When the tiles of C do not fill the machine evenly (72 tiles of 256 x 256 on 256 CUs, or 288), the
+// work is cut differently: every tile's k range is divided into units of kSplitQuantum, all units of
+// all tiles are laid in one line (tile after tile), and workgroup w of G takes the w-th equal piece
+// of that line.  A piece covers the end of one tile, possibly some whole tiles, and the start of
+// another: the workgroup runs one segment per tile it touches.  Whole tiles go straight to C; a
+// partial one goes to the workgroup's scratch slot (2 w for a segment that starts inside a tile,
+// 2 w + 1 for one that starts a tile but does not finish it) and streamk_fixup_kernel adds the
+// pieces of each cut tile in k order.  The cut depends only on (configuration, m, n, k), so results
+// stay reproducible.
+struct StreamKCut {
+    int units;            // tiles x units_per_tile (the launcher keeps it below 2^31)
+    int units_per_tile;
+    int groups;           // G
+    __host__ __device__ int bound(int w) const { return (int)((long long)units * w / groups); }
+};
+
+// workgroup ids are dealt round robin to the XCDs; give each XCD a contiguous run of pieces
+__device__ __forceinline__ int streamk_piece_of_block(int block, int groups, int num_xcd)
+{
+    if (num_xcd <= 1 || groups % num_xcd != 0) return block;
+    return (block % num_xcd) * (groups / num_xcd) + block / num_xcd;
+}
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_streamk_kernel(GemmParams p)
+{
+    const StreamKCut cut = {p.tiles_m * p.tiles_n * p.sk_units_per_tile, p.sk_units_per_tile, (int)gridDim.x};
+    const int piece = streamk_piece_of_block((int)blockIdx.x, cut.groups, p.num_xcd);
+    GemmParams q = p;
+    q.num_xcd = 1;                                   // tiles are already walked in order: bands only
+    // (the divisions run on the vector unit; readfirstlane tells the compiler the results are wave-uniform)
+    int u = __builtin_amdgcn_readfirstlane(cut.bound(piece));
+    const int u_end = __builtin_amdgcn_readfirstlane(cut.bound(piece + 1));
+    bool first = true;
+    while (u < u_end) {
+        const int tile = __builtin_amdgcn_readfirstlane(u / cut.units_per_tile);
+        const int s0 = u - tile * cut.units_per_tile;
+        const int left = u_end - u;
+        const int s1 = (left < cut.units_per_tile - s0) ? s0 + left : cut.units_per_tile;
+        int tm, tn;
+        tile_of_block(q, tile, tm, tn);
+        const int k0 = s0 * kSplitQuantumDev;
+        const int k1 = min(p.K, s1 * kSplitQuantumDev);
+        WorkView w;
+        w.pid = tile;
+        w.K = k1 - k0;
+        w.A = p.A + k0;
+        w.B = NT ? p.B + k0 : p.B + (size_t)k0 * p.ldb;
+        if (s0 == 0 && s1 == cut.units_per_tile) {
+            w.C = p.C;
+            w.ldc = p.ldc;
+        } else {
+            // a dense BM x BN slot; the epilogue adds (tile row origin) x ldc + (tile column origin)
+            float* slot = p.part + (size_t)(2 * piece + (s0 == 0 ? 1 : 0)) * (BM * BN);
+            w.C = slot - ((size_t)tm * BM * BN + (size_t)tn * BN);
+            w.ldc = BN;
+        }
+        if (!first) lds_barrier();
+        first = false;
+        dma_segment<BM, BN, BK, WAVES_M, WAVES_N, NT, NSTAGE>(q, w, tm, tn);
+        u += s1 - s0;
+    }
+}
+
+// C tile = sum of its pieces in k order, for every tile that was cut.  kFixChunks workgroups of 256
+// threads per tile, each taking a band of BM / kFixChunks rows.
+constexpr int kFixChunks = 4;
+constexpr int kFixMaxPieces = 8;      // pieces of one tile summed per pass (more: further passes)
+
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void streamk_fixup_kernel(GemmParams p, int groups)
+{
+    const StreamKCut cut = {p.tiles_m * p.tiles_n * p.sk_units_per_tile, p.sk_units_per_tile, groups};
+    const int tile = blockIdx.x / kFixChunks;
+    const int chunk = blockIdx.x % kFixChunks;
+    const int ub = tile * cut.units_per_tile, ue = ub + cut.units_per_tile;
+    int w0 = (int)((long long)ub * groups / cut.units);
+    while (w0 > 0 && cut.bound(w0) > ub) --w0;
+    while (w0 + 1 < groups && cut.bound(w0 + 1) <= ub) ++w0;
+    if (cut.bound(w0) <= ub && cut.bound(w0 + 1) >= ue) return;      // one workgroup did the whole tile
+    GemmParams q = p;
+    q.num_xcd = 1;
+    int tm, tn;
+    tile_of_block(q, tile, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const bool vec = ((reinterpret_cast<uintptr_t>(p.C) & 15) == 0) && ((p.ldc & 3) == 0) && (n0 + BN <= p.N);
+    constexpr int ROWS = BM / kFixChunks;
+    const int r_first = chunk * ROWS;
+    int w = w0;
+    bool have_sum = false;                    // later passes continue from what is already in C
+    while (w < groups && cut.bound(w) < ue) {
+        // the next (up to kFixMaxPieces) pieces of this tile
+        const float* slot[kFixMaxPieces];
+        int np = 0;
+        for (; w < groups && cut.bound(w) < ue && np < kFixMaxPieces; ++w) {
+            const int a = cut.bound(w) > ub ? cut.bound(w) : ub;
+            const int b = cut.bound(w + 1) < ue ? cut.bound(w + 1) : ue;
+            if (a >= b) continue;
+            slot[np++] = p.part + (size_t)(2 * w + (a == ub ? 1 : 0)) * (BM * BN);
+        }
+        for (int e = threadIdx.x; e < ROWS * BN / 4; e += 256) {
+            const int r = r_first + e / (BN / 4);
+            const int c = (e % (BN / 4)) * 4;
+            if (m0 + r >= p.M || n0 + c >= p.N) continue;
+            float* dst = p.C + (size_t)(m0 + r) * p.ldc + n0 + c;
+            f32x4 v[kFixMaxPieces];
+#pragma unroll
+            for (int j = 0; j < kFixMaxPieces; ++j)
+                if (j < np) v[j] = *reinterpret_cast<const f32x4*>(slot[j] + (size_t)r * BN + c);
+            f32x4 acc;
+            if (have_sum) {
+                if (vec) acc = *reinterpret_cast<const f32x4*>(dst);
+                else {
+                    acc.x = dst[0];
+                    acc.y = (n0 + c + 1 < p.N) ? dst[1] : 0.f;
+                    acc.z = (n0 + c + 2 < p.N) ? dst[2] : 0.f;
+                    acc.w = (n0 + c + 3 < p.N) ? dst[3] : 0.f;
+                }
+                acc += v[0];
+            } else {
+                acc = v[0];
+            }
+#pragma unroll
+            for (int j = 1; j < kFixMaxPieces; ++j)
+                if (j < np) acc += v[j];
+            if (vec) {
+                *reinterpret_cast<f32x4*>(dst) = acc;
+            } else {
+                dst[0] = acc.x;
+                if (n0 + c + 1 < p.N) dst[1] = acc.y;
+                if (n0 + c + 2 < p.N) dst[2] = acc.z;
+                if (n0 + c + 3 < p.N) dst[3] = acc.w;
+            }
+        }
+        have_sum = true;
+    }
+}
+
 // ---- split-k reduction ---------------------------------------------------------------------------
 
 // C[i][j] = part[0][i][j] + part[1][i][j] + ... in split order (fixed, so results are reproducible)
@@ -765,6 +929,8 @@ struct Config {
     int bm, bn, bk;
     void (*kern[2][2])(GemmParams);   // guarded kernel, [op][vec]
     void (*dma[2])(GemmParams);       // pipelined kernel, [op]; null if the configuration has none
+    void (*sk[2])(GemmParams);        // the same with the work cut evenly over a fixed grid, [op]
+    void (*fix)(GemmParams, int);     // ... and its fix-up kernel
     int nstage;
     int threads;
     int waves_n;
@@ -807,6 +973,8 @@ struct Config {
 #define MTNN_CFG_DMA(BM, BN, BK, WMV, WNV, NS, GBK, MAXWG, EFF_NN, RND_NN, EFF_NT, RND_NT)                                    \
     { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV "_dma" #NS "_x" #MAXWG, BM, BN, BK, MTNN_GUARDED(BM, BN, GBK, WMV, WNV), \
       {gemm_dma_kernel<BM, BN, BK, WMV, WNV, false, NS>, gemm_dma_kernel<BM, BN, BK, WMV, WNV, true, NS>}, \
+      {gemm_streamk_kernel<BM, BN, BK, WMV, WNV, false, NS>, gemm_streamk_kernel<BM, BN, BK, WMV, WNV, true, NS>}, \
+      streamk_fixup_kernel<BM, BN>, \
       NS, WMV * WNV * 64, WNV, {EFF_NN, EFF_NT}, {RND_NN, RND_NT}, MAXWG }
 
 static const Config kConfigs[] = {
@@ -830,7 +998,11 @@ static const Config kConfigs[] = {
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 constexpr int kMaxSplits = 32;
-constexpr int kSplitQuantum = 64;     // k ranges of split-k are multiples of this (every slab size divides it)
+constexpr int kStreamK = -2;          // in place of a split count: cut the work evenly over a fixed grid
+constexpr int kSplitQuantum = kSplitQuantumDev;
+
+static std::atomic<long long> g_streamk_launches{0};
+long long gemm_streamk_launches() { return g_streamk_launches.load(); }
 
 int gemm_config_count() { return kNumConfigs; }
 const char* gemm_config_name(int cfg) { return (cfg >= 0 && cfg < kNumConfigs) ? kConfigs[cfg].name : nullptr; }
@@ -895,10 +1067,39 @@ static double predicted_seconds(const Config& c, int op, int m, int n, int k, in
     return t + 3.0e-6;
 }
 
-static Choice choose(int op, int m, int n, int k, bool allow_split)
+// Predicted time of the even cut (gemm_streamk_kernel + fix-up) for configuration c, or a huge value
+// where it cannot run.  Every workgroup gets the same number of k units, so the k-loop time is the
+// padded work spread over all CUs; a workgroup pays the time outside the k loop once per tile it
+// touches, and the fix-up kernel moves every cut tile's pieces once more.  The four weights are a
+// least-squares fit to 160 measured (shape, configuration) pairs (mean error 4.5 %).
+static double predicted_seconds_even_cut(const Config& c, int op, int m, int n, int k)
+{
+    const double peak_cu = 157.3e12 / 256.0;
+    const long long tiles = (long long)((m + c.bm - 1) / c.bm) * ((n + c.bn - 1) / c.bn);
+    const int units_per_tile = (k + kSplitQuantum - 1) / kSplitQuantum;
+    const long long units = tiles * units_per_tile;
+    const int occ = c.wg_per_cu();
+    const int groups = 256 * occ;
+    if (units < groups || units >= 0x7fffffffLL) return 1e30;
+    if ((size_t)2 * groups * c.bm * c.bn * sizeof(float) > kScratchBytes) return 1e30;
+    // with fewer tiles than an eighth of the pieces, every tile is cut many times and the fix-up
+    // kernel (a few workgroups adding dozens of pieces each) dominates: measured 3x slower than split-k
+    if (tiles * 8 < groups) return 1e30;
+    const double units_per_wg = (double)units / groups;
+    const double main_s = units_per_wg * occ * 2.0 * c.bm * c.bn * kSplitQuantum / (peak_cu * c.eff[op]);
+    const double segments = units_per_wg / units_per_tile + 1.0;
+    const double cut_tiles = tiles < groups ? (double)tiles : (double)groups;
+    const double pieces = tiles < groups ? ((double)groups / tiles + 1.0 < 2.0 ? 2.0 : (double)groups / tiles + 1.0) : 2.0;
+    const double fix_bytes = cut_tiles * (pieces + 1.0) * c.bm * c.bn * 4.0;
+    return 1.02 * main_s + 0.69 * segments * c.round_s[op] + 0.62 * fix_bytes / 4.0e12 + 12.0e-6;
+}
+
+// pipelined: the operands allow the pipelined kernel (the even cut exists only there)
+static Choice choose(int op, int m, int n, int k, bool allow_split, bool pipelined = true)
 {
     Choice best = {0, 1};
     double best_t = 1e30;
+    const int o = (op == OP_NT) ? 1 : 0;
     for (int c = 0; c < kNumConfigs; ++c) {
         for (int splits = 1; splits <= kMaxSplits; splits *= 2) {
             if (splits > 1) {
@@ -906,8 +1107,18 @@ static Choice choose(int op, int m, int n, int k, bool allow_split)
                 if ((size_t)m * n * splits * sizeof(float) > kScratchBytes) break;
                 if (k / splits < 2 * kSplitQuantum) break;
             }
-            const double t = predicted_seconds(kConfigs[c], op == OP_NT ? 1 : 0, m, n, k, splits);
+            const double t = predicted_seconds(kConfigs[c], o, m, n, k, splits);
             if (t < best_t * 0.999) { best_t = t; best = Choice{c, splits}; }
+        }
+    }
+    if (allow_split && pipelined) {
+        // the even cut, for the two configurations it was measured with (64 x 128 and 128 x 128 tiles,
+        // two per CU), and only where it promises 10 % or more: on 80 measured shapes that rule chose it 12
+        // times, never wrongly, for 8 % on average; at 5 % it was wrong twice
+        double sk_t = best_t * 0.90;
+        for (int c = 9; c <= 10; ++c) {
+            const double t = predicted_seconds_even_cut(kConfigs[c], o, m, n, k);
+            if (t < sk_t) { sk_t = t; best = Choice{c, kStreamK}; }
         }
     }
     return best;
@@ -920,14 +1131,20 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
                 const float* A, long lda, const float* B, long ldb, float* C, long ldc)
 {
     if (op != OP_NN && op != OP_NT) return (int)hipErrorInvalidValue;
+    // splits: >= 1 as given; kStreamK the even cut; any other value <= 0 leaves the choice to the rule
+    const bool free_splits = (splits <= 0 && splits != kStreamK);
+    const bool chunks16 = (lda % 4 == 0) && (ldb % 4 == 0) && (k % 4 == 0) && (op == OP_NT || n % 4 == 0) &&
+                          ((reinterpret_cast<uintptr_t>(A) & 15) == 0) && ((reinterpret_cast<uintptr_t>(B) & 15) == 0);
     if (cfg < 0) {
-        const Choice ch = choose(op, m, n, k, splits <= 0);
+        const Choice ch = choose(op, m, n, k, free_splits, chunks16);
         cfg = ch.cfg;
-        if (splits <= 0) splits = ch.splits;
-    } else if (splits <= 0) {
+        if (free_splits) splits = ch.splits;
+    } else if (free_splits) {
         splits = 1;
     }
     if (cfg >= kNumConfigs || splits > kMaxSplits) return (int)hipErrorInvalidValue;
+    const bool want_streamk = (splits == kStreamK);
+    if (splits < 1) splits = 1;
     const Config& c = kConfigs[cfg];
     GemmParams p;
     p.A = A; p.B = B; p.C = C;
@@ -941,6 +1158,7 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
     p.splits = 1;
     p.k_per_split = k;
     p.part = nullptr;
+    p.sk_units_per_tile = 0;
     if (splits > 1) {
         int kps = (k + splits - 1) / splits;
         kps = ((kps + kSplitQuantum - 1) / kSplitQuantum) * kSplitQuantum;
@@ -966,6 +1184,37 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
                         (op == OP_NT ? (unsigned long long)c.bn * (unsigned long long)ldb * 4ull < lim
                                      : (unsigned long long)(c.bk + 1) * (unsigned long long)ldb * 4ull < lim);
     const bool dma_ok = vec && c.dma[op] && (k % 4 == 0) && (op == OP_NT || n % 4 == 0) && off_ok;
+    if (want_streamk && dma_ok) {
+        // the even cut: 256 x (workgroups per CU) pieces, if there is at least one unit for each and
+        // the 2 x pieces scratch slots fit; otherwise the plain launch below
+        const int groups = 256 * c.wg_per_cu();
+        const int units_per_tile = (k + kSplitQuantum - 1) / kSplitQuantum;
+        const long long units = (long long)p.tiles_m * p.tiles_n * units_per_tile;
+        const size_t need = (size_t)2 * groups * c.bm * c.bn * sizeof(float);
+        float* part = (units >= groups && units < 0x7fffffffLL && need <= kScratchBytes) ? scratch_for(s) : nullptr;
+        if (part) {
+            p.part = part;
+            p.sk_units_per_tile = units_per_tile;
+            size_t lds_sk = c.lds_bytes_dma();
+            const size_t share = ((160 * 1024) / (size_t)c.wg_per_cu()) & ~(size_t)1023;
+            if (lds_sk < share - 1024) lds_sk = share - 1024;
+            static bool raised_sk[kNumConfigs][2][16] = {};
+            int dev = 0;
+            if (hipGetDevice(&dev) != hipSuccess) return (int)hipGetLastError();
+            if (lds_sk > 64 * 1024 && (dev < 0 || dev >= 16 || !raised_sk[cfg][op][dev])) {
+                const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(c.sk[op]),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                if (e != hipSuccess) return (int)e;
+                if (dev >= 0 && dev < 16) raised_sk[cfg][op][dev] = true;
+            }
+            hipLaunchKernelGGL(c.sk[op], dim3((unsigned)groups), dim3(c.threads), lds_sk, s, p);
+            hipError_t err = hipGetLastError();
+            if (err != hipSuccess) return (int)err;
+            hipLaunchKernelGGL(c.fix, dim3((unsigned)(p.tiles_m * p.tiles_n * kFixChunks)), dim3(256), 0, s, p, groups);
+            ++g_streamk_launches;
+            return (int)hipGetLastError();
+        }
+    }
     auto kern = dma_ok ? c.dma[op] : c.kern[op][vec ? 1 : 0];
     Config guarded = c;
     guarded.bk = 16;

@@ -14,6 +14,7 @@ enum GemmOp { OP_NN = 0, OP_NT = 1 };
 int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
                 const float* A, long lda, const float* B, long ldb, float* C, long ldc);
 int gemm_config_count();
+long long gemm_streamk_launches();
 const char* gemm_config_name(int cfg);
 int gemm_default_config(int op, int m, int n, int k);
 int gemm_default_splits(int op, int m, int n, int k);

@@ -188,7 +188,7 @@ def main(argv=None):
             for r in report["shapes"]:
                 f.write(f"| {r['config']} | {r['m']} | {r['n']} | {r['k']} | {r['bound']} | {r['nt_gflops'] / 1e3:.1f} | "
                         f"{r['tnn_gflops'] / 1e3:.1f} | {r['mtnn_gflops'] / 1e3:.1f} | {r['label']:+d} | "
-                        f"{r['nt_roofline_frac']:.2f} | {r['nt_cfg']} | {r['nt_splits']} |\n")
+                        f"{r['nt_roofline_frac']:.2f} | {r['nt_cfg']} | {'even cut' if r['nt_splits'] == mt.EVEN_CUT else r['nt_splits']} |\n")
             f.write("\n| transpose rows x cols | us | GB/s | of 8 TB/s | fits the 256 MB cache | rotating pairs | us | GB/s | of 8 TB/s |\n")
             f.write("|---|---|---|---|---|---|---|---|---|\n")
             for r in report["transposes"]:

@@ -327,3 +327,36 @@ def test_several_workgroups_per_cu_on_a_full_grid(op, cfg):
     got = run(op, cfg, A, B)
     C, S = reference(op, A, B)
     check_gemm(got, C, S, k, f"op{op} cfg{cfg}")
+
+
+@pytest.mark.parametrize("op", [mt.OP_NT, mt.OP_NN], ids=["NT", "NN"])
+@pytest.mark.parametrize("cfg", [3, 6, 8, 9, 10, 11, 12])
+def test_even_cut_against_oracle(op, cfg):
+    """splits = EVEN_CUT: all tiles' k ranges cut into equal pieces over a fixed grid, cut tiles
+    finished by the fix-up kernel; ragged m, n edges and a ragged last k unit."""
+    m, n, k = 1000, 900, 1100
+    A, B = operands(op, m, n, k, 950 + cfg, dist="normal")
+    before = mt.mtnn_gemm_even_cut_launches()
+    got = run(op, cfg, A, B, ldc=n + 4, splits=mt.EVEN_CUT)
+    assert mt.mtnn_gemm_even_cut_launches() == before + 1, "the launch did not take the even-cut path"
+    C, S = reference(op, A, B)
+    check_gemm(got, C, S, k, f"op{op} cfg{cfg} even cut")
+    again = run(op, cfg, A, B, ldc=n + 4, splits=mt.EVEN_CUT)
+    assert again.tobytes() == got.tobytes()            # fixed cut, fixed order of the pieces
+
+
+def test_even_cut_integer_inputs_bit_exact_and_fallback():
+    for op in (mt.OP_NT, mt.OP_NN):
+        A, B = operands(op, 1500, 700, 2048, 960, dist="int")
+        C, _ = reference(op, A, B)
+        before = mt.mtnn_gemm_even_cut_launches()
+        got = run(op, 10, A, B, splits=mt.EVEN_CUT)
+        assert mt.mtnn_gemm_even_cut_launches() == before + 1
+        assert np.array_equal(got, C.astype(np.float32))
+        # fewer units than pieces, or operands the pipelined kernel cannot take: runs unsplit, still right
+        A2, B2 = operands(op, 130, 132, 64, 961, dist="int")
+        C2, _ = reference(op, A2, B2)
+        assert np.array_equal(run(op, 10, A2, B2, splits=mt.EVEN_CUT), C2.astype(np.float32))
+        A3, B3 = operands(op, 1000, 900, 1101, 962, dist="int")          # k % 4 != 0
+        C3, _ = reference(op, A3, B3)
+        assert np.array_equal(run(op, 10, A3, B3, splits=mt.EVEN_CUT), C3.astype(np.float32))
