@@ -3,6 +3,13 @@
 //   NT (Eq. 2):                    C[i][j] = sum_l A[i][l] * B[j][l]   A m x k, B n x k
 // all row-major, alpha = 1, no beta term (Section II).
 //
+// Two kernels share the tile geometry below: gemm_dma_kernel, the pipelined one (slabs copied global
+// -> LDS directly, ring of slab buffers; 16-byte aligned operands with k % 4 = 0), and gemm_kernel,
+// the guarded one for everything else.  The work is divided one of three ways: one workgroup per C
+// tile; split-k (several workgroups per tile, partial products summed by reduce_splits_kernel); or
+// the even cut (gemm_streamk_kernel: all tiles' k ranges cut into equal pieces over a fixed grid,
+// cut tiles finished by streamk_fixup_kernel).  `choose` picks configuration and division per shape.
+//
 // Design (ours; the paper calls a closed library for both operations):
 //   * one workgroup computes a BM x BN tile of C, stepping through k in slabs of BK;
 //   * each 64-lane wave owns a WM x WN sub-tile built from 32x32 blocks, each block advanced

@@ -75,13 +75,22 @@ def test_gemm_ex_arguments(L):
     assert L.mtnn_gemm_ex(None, 1, -2, 1, 4, 4, 4, A, 4, B, 4, C, 4) == 8
     assert L.mtnn_gemm_ex(None, 1, 0, 33, 4, 4, 4, A, 4, B, 4, C, 4) == 8
     assert L.mtnn_gemm_ex(None, 1, 0, -1, 4, 4, 4, A, 4, B, 4, C, 4) == 8
+    assert L.mtnn_gemm_ex(None, 1, 0, -3, 4, 4, 4, A, 4, B, 4, C, 4) == 8
     assert L.mtnn_gemm_ex(None, 1, 0, 1, 4, 4, 4, A, 3, B, 4, C, 4) == 3
+    # the even cut is a legal request (validation goes on to the operands; an empty product is a success)
+    assert mt.EVEN_CUT == -2
+    assert L.mtnn_gemm_ex(None, 1, 0, mt.EVEN_CUT, 4, 4, 4, A, 3, B, 4, C, 4) == 3
+    assert L.mtnn_gemm_ex(None, 1, 0, mt.EVEN_CUT, 0, 4, 4, A, 4, B, 4, C, 4) == 0
+    assert mt.mtnn_gemm_even_cut_launches() >= 0
     names = mt.gemm_configs()
     assert len(set(names)) == n
     for op in (0, 1):
         for shape in [(256, 256, 256), (1024, 4096, 4096), (32, 8192, 8192), (8192, 32, 8192), (1000, 1000, 1000)]:
             assert 0 <= mt.mtnn_gemm_default_config(op, *shape) < n
             assert 1 <= mt.mtnn_gemm_default_splits(op, *shape) <= 32
+        # an irregular mid-size shape with a long k is where the rule may answer "even cut"
+        assert mt.mtnn_gemm_default_splits(op, 3000, 1500, 4500) in (mt.EVEN_CUT, 1, 2, 4)
+    assert mt.mtnn_device_attribute(7) == -1          # unknown attribute
     assert mt.mtnn_gemm_default_config(0, 0, 4, 4) == -1
 
 
