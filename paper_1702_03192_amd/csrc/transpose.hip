@@ -4,7 +4,8 @@
 // The operation is pure data movement, so the design is about HBM.  A 256-thread workgroup moves a
 // tile of TR input rows x TC input columns:
 //   read   a tile row is TC words (128 or 256 bytes, whole cache lines), 16 bytes per lane;
-//   LDS    tile[TR][TC+1] words; the odd row stride spreads the column gather over the banks;
+//   LDS    tile[TR][TC] words with the columns of each row XOR-swizzled, so that neither the row-wise
+//          stores nor the column gather meet a bank conflict;
 //   write  an output row segment is TR words (512 B or 1 KB): each lane gathers 4 words of one
 //          tile column from LDS and stores 16 B, with non-temporal stores so that the stream of
 //          results does not evict the input from the caches;
@@ -32,13 +33,27 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TR_THREADS = 256;
 
+// LDS layout of the 16-byte-group path: tile[row][col ^ swz(row)], rows of TC words with no padding.
+// The XOR keeps both phases free of bank conflicts (64 banks of 4 bytes; a 64-lane access takes
+// two passes of 32 lanes, and within each pass all lanes must hit different banks):
+//   store phase  a pass holds 4 or 8 consecutive rows x all 16-byte groups of a row; the low two
+//                bits of swz differ between the rows that share a bank half;
+//   gather phase lane i reads rows 4 i + e (e = 0..3 in turn) of one column; swz(4 i + e) is a
+//                bijection of i for fixed e, so the lanes spread over all banks.
+template <int TC>
+__device__ __forceinline__ int swz(int row)
+{
+    if (TC == 64) return ((row >> 2) ^ (row & 3)) & 63;
+    return ((row >> 2) ^ ((row >> 1) & 3)) & 31;          // TC == 32: row parity picks the bank half
+}
+
 // the 16-byte-group path of one tile; GUARD: skip the groups that fall outside the matrix (edge tiles)
 template <int TR, int TC, bool NTL, bool GUARD>
 __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
                                                    uint32_t* tile, int rows, int cols, long ldin, long ldout,
                                                    int r0, int c0)
 {
-    constexpr int TP = TC + 1;               // padded LDS row stride
+    static_assert(TC == 32 || TC == 64, "swz() knows these two widths");
     const int t = threadIdx.x;
     constexpr int QC = TC / 4;               // 16-byte groups per tile row
     constexpr int RP = TR_THREADS / QC;      // rows per pass
@@ -55,8 +70,11 @@ __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ 
     }
 #pragma unroll
     for (int p = 0; p < TR / RP; ++p) {
-        uint32_t* dst = tile + (p * RP + rr) * TP + q * 4;
-        dst[0] = v[p].x; dst[1] = v[p].y; dst[2] = v[p].z; dst[3] = v[p].w;
+        const int row = p * RP + rr;
+        const int x = swz<TC>(row);
+        uint32_t* dst = tile + row * TC;
+        dst[(q * 4 + 0) ^ x] = v[p].x; dst[(q * 4 + 1) ^ x] = v[p].y;
+        dst[(q * 4 + 2) ^ x] = v[p].z; dst[(q * 4 + 3) ^ x] = v[p].w;
     }
     __syncthreads();
     constexpr int QR = TR / 4;               // 16-byte groups per output row segment
@@ -66,9 +84,12 @@ __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ 
 #pragma unroll
     for (int p = 0; p < TC / CP; ++p) {
         const int c = p * CP + oc;           // tile column = output row
-        const uint32_t* src = tile + (oq * 4) * TP + c;
+        const uint32_t* src = tile + (oq * 4) * TC;
         u32x4 w;
-        w.x = src[0]; w.y = src[TP]; w.z = src[2 * TP]; w.w = src[3 * TP];
+        w.x = src[c ^ swz<TC>(oq * 4)];
+        w.y = src[TC + (c ^ swz<TC>(oq * 4 + 1))];
+        w.z = src[2 * TC + (c ^ swz<TC>(oq * 4 + 2))];
+        w.w = src[3 * TC + (c ^ swz<TC>(oq * 4 + 3))];
         if (!GUARD || (c0 + c < cols && r0 + oq * 4 < rows))
             __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * ldout + r0 + oq * 4));
     }
