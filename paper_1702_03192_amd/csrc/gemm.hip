@@ -43,6 +43,9 @@ namespace mtnn {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// four consecutive floats at any 4-byte aligned address: the compiler may still use one 16-byte
+// global load where the target allows unaligned vector access
+typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
 struct GemmParams {
     const float* A;
@@ -104,9 +107,7 @@ __device__ __forceinline__ f32x4 load_k4(const float* __restrict__ row, int kidx
 {
     if (FAST || kidx + 3 < K) {
         if (VEC) return *reinterpret_cast<const f32x4*>(row + kidx);
-        f32x4 v;
-        v.x = row[kidx]; v.y = row[kidx + 1]; v.z = row[kidx + 2]; v.w = row[kidx + 3];
-        return v;
+        return *reinterpret_cast<const f32x4_a4*>(row + kidx);
     }
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
     if (kidx < K) v.x = row[kidx];
@@ -126,8 +127,7 @@ __device__ __forceinline__ f32x4 load_n4(const float* __restrict__ B, long ldb, 
     const float* row = B + (size_t)krow * ldb;
     if (FAST || nidx + 3 < N) {
         if (VEC) return *reinterpret_cast<const f32x4*>(row + nidx);
-        v.x = row[nidx]; v.y = row[nidx + 1]; v.z = row[nidx + 2]; v.w = row[nidx + 3];
-        return v;
+        return *reinterpret_cast<const f32x4_a4*>(row + nidx);
     }
     const int last = N - 1;
     v.x = row[min(nidx, last)];
