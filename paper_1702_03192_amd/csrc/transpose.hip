@@ -22,9 +22,9 @@
 //   128 x 64, non-temporal loads  between 2^24 and 2^26 elements;
 //   256 x 64, non-temporal loads  from 2^26 elements: data streams from and to HBM, 1 KB write runs.
 // Words are moved as integers, so NaN payloads and signed zeros survive bit for bit.
-// Sizes or leading dimensions that are not multiples of 4 and unaligned bases take the guarded
-// one-word-per-access path of the 128 x 32 kernel; otherwise edge tiles only skip the 16-byte
-// groups that fall outside.
+// Rows that are not 16-byte aligned (odd leading dimensions, unaligned bases) take the same path
+// with the 16-byte accesses made at 4-byte alignment; groups of four that lie across the matrix
+// edge are moved word by word.
 #include "mtnn_internal.h"
 
 namespace mtnn {
@@ -47,13 +47,17 @@ __device__ __forceinline__ int swz(int row)
     return ((row >> 2) ^ ((row >> 1) & 3)) & 31;          // TC == 32: row parity picks the bank half
 }
 
-// the 16-byte-group path of one tile; GUARD: skip the groups that fall outside the matrix (edge tiles)
-template <int TR, int TC, bool NTL, bool GUARD>
+// One tile.  A16: rows of both matrices are 16-byte aligned (aligned bases, leading dimensions
+// multiples of 4); otherwise the same 16-byte accesses are made at 4-byte alignment, which gfx950
+// allows for global memory.  GUARD (edge tiles): a group of four that lies across the matrix edge
+// is moved word by word, one that lies outside is skipped.
+template <int TR, int TC, bool NTL, bool GUARD, bool A16>
 __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
                                                    uint32_t* tile, int rows, int cols, long ldin, long ldout,
                                                    int r0, int c0)
 {
     static_assert(TC == 32 || TC == 64, "swz() knows these two widths");
+    typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
     const int t = threadIdx.x;
     constexpr int QC = TC / 4;               // 16-byte groups per tile row
     constexpr int RP = TR_THREADS / QC;      // rows per pass
@@ -63,9 +67,16 @@ __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ 
 #pragma unroll
     for (int p = 0; p < TR / RP; ++p) {
         const int r = r0 + p * RP + rr;
-        if (!GUARD || (r < rows && c0 + q * 4 < cols)) {
-            const u32x4* src = reinterpret_cast<const u32x4*>(in + (size_t)r * ldin + c0 + q * 4);
-            v[p] = NTL ? __builtin_nontemporal_load(src) : *src;
+        const int cg = c0 + q * 4;
+        const uint32_t* src = in + (size_t)r * ldin + cg;
+        if (!GUARD || (r < rows && cg + 3 < cols)) {
+            if (A16) v[p] = NTL ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src))
+                                : *reinterpret_cast<const u32x4*>(src);
+            else v[p] = *reinterpret_cast<const u32x4_a4*>(src);
+        } else if (r < rows && cg < cols) {
+            v[p].x = src[0];
+            if (cg + 1 < cols) v[p].y = src[1];
+            if (cg + 2 < cols) v[p].z = src[2];
         }
     }
 #pragma unroll
@@ -90,8 +101,17 @@ __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ 
         w.y = src[TC + (c ^ swz<TC>(oq * 4 + 1))];
         w.z = src[2 * TC + (c ^ swz<TC>(oq * 4 + 2))];
         w.w = src[3 * TC + (c ^ swz<TC>(oq * 4 + 3))];
-        if (!GUARD || (c0 + c < cols && r0 + oq * 4 < rows))
-            __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * ldout + r0 + oq * 4));
+        const int orow = c0 + c;
+        const int og = r0 + oq * 4;
+        uint32_t* dst = out + (size_t)orow * ldout + og;
+        if (!GUARD || (orow < cols && og + 3 < rows)) {
+            if (A16) __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(dst));
+            else *reinterpret_cast<u32x4_a4*>(dst) = w;
+        } else if (orow < cols && og < rows) {
+            dst[0] = w.x;
+            if (og + 1 < rows) dst[1] = w.y;
+            if (og + 2 < rows) dst[2] = w.z;
+        }
     }
 }
 
@@ -100,37 +120,16 @@ __global__ __launch_bounds__(TR_THREADS) void transpose_kernel(
     const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
     int rows, int cols, long ldin, long ldout, int tiles_r, int tiles_c)
 {
-    constexpr int TP = TC + 1;
-    extern __shared__ uint32_t tile[];                   // TR * TP words
-    const int t = threadIdx.x;
+    extern __shared__ uint32_t tile[];                   // TR * TC words
     const int tr = blockIdx.x % tiles_r;
     const int tc = (blockIdx.x / tiles_r + tr) % tiles_c;   // for each tile row a rotation of the columns
     const int r0 = tr * TR;
     const int c0 = tc * TC;
-
-    // VEC: 16-byte aligned rows on both sides and rows, cols multiples of 4, so every 16-byte group
-    // is entirely inside or entirely outside the matrix
-    if (VEC) {
-        if ((r0 + TR <= rows) && (c0 + TC <= cols))
-            transpose_tile_vec<TR, TC, NTL, false>(in, out, tile, rows, cols, ldin, ldout, r0, c0);
-        else
-            transpose_tile_vec<TR, TC, NTL, true>(in, out, tile, rows, cols, ldin, ldout, r0, c0);
-    } else {
-        // guarded path: one word per access, still row-coalesced on both sides
-        const int lane_c = t % TC;
-        const int rbase = t / TC;
-        for (int r = rbase; r < TR; r += TR_THREADS / TC) {
-            if (r0 + r < rows && c0 + lane_c < cols)
-                tile[r * TP + lane_c] = in[(size_t)(r0 + r) * ldin + c0 + lane_c];
-        }
-        __syncthreads();
-        for (int e = t; e < TR * TC; e += TR_THREADS) {
-            const int c = e / TR;                        // output row within the tile
-            const int r = e % TR;                        // consecutive threads -> consecutive output words
-            if (c0 + c < cols && r0 + r < rows)
-                out[(size_t)(c0 + c) * ldout + r0 + r] = tile[r * TP + c];
-        }
-    }
+    // VEC: 16-byte aligned rows on both sides
+    if ((r0 + TR <= rows) && (c0 + TC <= cols))
+        transpose_tile_vec<TR, TC, NTL, false, VEC>(in, out, tile, rows, cols, ldin, ldout, r0, c0);
+    else
+        transpose_tile_vec<TR, TC, NTL, true, VEC>(in, out, tile, rows, cols, ldin, ldout, r0, c0);
 }
 
 template <int TR, int TC, bool VEC, bool NTL>
@@ -141,7 +140,7 @@ static int launch_transpose_t(hipStream_t s, int rows, int cols, const uint32_t*
     const int tiles_r = (rows + TR - 1) / TR;
     const long long nblocks = (long long)tiles_c * tiles_r;
     if (nblocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
-    constexpr size_t lds = (size_t)TR * (TC + 1) * sizeof(uint32_t);
+    constexpr size_t lds = (size_t)TR * TC * sizeof(uint32_t);
     auto kern = transpose_kernel<TR, TC, VEC, NTL>;
     if (lds > 64 * 1024) {
         // opt in to the large LDS carve-out once per device
@@ -163,18 +162,20 @@ static int launch_transpose_t(hipStream_t s, int rows, int cols, const uint32_t*
 int launch_transpose(hipStream_t s, int rows, int cols, const float* in, long ldin, float* out, long ldout)
 {
     if (rows <= 0 || cols <= 0) return 0;
-    const bool vec = (ldin % 4 == 0) && (ldout % 4 == 0) && (rows % 4 == 0) && (cols % 4 == 0) &&
+    const bool vec = (ldin % 4 == 0) && (ldout % 4 == 0) &&
                      ((reinterpret_cast<uintptr_t>(in) & 15) == 0) &&
                      ((reinterpret_cast<uintptr_t>(out) & 15) == 0);
     const uint32_t* pin = reinterpret_cast<const uint32_t*>(in);
     uint32_t* pout = reinterpret_cast<uint32_t*>(out);
-    if (!vec) return launch_transpose_t<128, 32, false, false>(s, rows, cols, pin, ldin, pout, ldout);
     const long long elems = (long long)rows * cols;
     if (elems >= (1LL << 26) && rows >= 256 && cols >= 64)
-        return launch_transpose_t<256, 64, true, true>(s, rows, cols, pin, ldin, pout, ldout);
+        return vec ? launch_transpose_t<256, 64, true, true>(s, rows, cols, pin, ldin, pout, ldout)
+                   : launch_transpose_t<256, 64, false, true>(s, rows, cols, pin, ldin, pout, ldout);
     if (elems > (1LL << 24) && cols >= 64)
-        return launch_transpose_t<128, 64, true, true>(s, rows, cols, pin, ldin, pout, ldout);
-    return launch_transpose_t<128, 32, true, false>(s, rows, cols, pin, ldin, pout, ldout);
+        return vec ? launch_transpose_t<128, 64, true, true>(s, rows, cols, pin, ldin, pout, ldout)
+                   : launch_transpose_t<128, 64, false, true>(s, rows, cols, pin, ldin, pout, ldout);
+    return vec ? launch_transpose_t<128, 32, true, false>(s, rows, cols, pin, ldin, pout, ldout)
+               : launch_transpose_t<128, 32, false, false>(s, rows, cols, pin, ldin, pout, ldout);
 }
 
 // ---- in-place transpose of a square matrix -------------------------------------------------------
