@@ -946,6 +946,8 @@ struct Config {
     // (separately for NN and NT: index = GemmOp)
     float eff[2];                     // rate of the k loop as a fraction of the fp32 MFMA peak
     float round_s[2];                 // seconds per round outside the k loop: first copies, result store
+    float eff_guarded[2];             // the same two for the guarded kernel (fitted with odd leading dimensions)
+    float round_guarded_s[2];
     int max_wg;                       // workgroups per CU the launch allows (it sizes its LDS request to that)
     // LDS bytes of the guarded kernel: two buffers of an A slab and a B slab (layouts as in the kernel)
     size_t lds_bytes(int op) const
@@ -977,31 +979,31 @@ struct Config {
      {gemm_kernel<BM, BN, BK, WMV, WNV, true, false>, gemm_kernel<BM, BN, BK, WMV, WNV, true, true>}}
 
 // pipelined kernel with NS slab buffers, and the guarded kernel (slab GBK) that serves what it cannot
-#define MTNN_CFG_DMA(BM, BN, BK, WMV, WNV, NS, GBK, MAXWG, EFF_NN, RND_NN, EFF_NT, RND_NT)                                    \
+#define MTNN_CFG_DMA(BM, BN, BK, WMV, WNV, NS, GBK, MAXWG, EFF_NN, RND_NN, EFF_NT, RND_NT, GEFF_NN, GRND_NN, GEFF_NT, GRND_NT)                                    \
     { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV "_dma" #NS "_x" #MAXWG, BM, BN, BK, MTNN_GUARDED(BM, BN, GBK, WMV, WNV), \
       {gemm_dma_kernel<BM, BN, BK, WMV, WNV, false, NS>, gemm_dma_kernel<BM, BN, BK, WMV, WNV, true, NS>}, \
       {gemm_streamk_kernel<BM, BN, BK, WMV, WNV, false, NS>, gemm_streamk_kernel<BM, BN, BK, WMV, WNV, true, NS>}, \
       streamk_fixup_kernel<BM, BN>, \
-      NS, WMV * WNV * 64, WNV, {EFF_NN, EFF_NT}, {RND_NN, RND_NT}, MAXWG }
+      NS, WMV * WNV * 64, WNV, {EFF_NN, EFF_NT}, {RND_NN, RND_NT}, {GEFF_NN, GEFF_NT}, {GRND_NN, GRND_NT}, MAXWG }
 
 static const Config kConfigs[] = {
-    //           tile         waves stages    per CU   NN: eff, round      NT: eff, round
-    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2, 16,   1,   0.958f, 15.1e-6f,   0.956f, 15.1e-6f),  // 0: 8 waves of 64 x 128, 128 KB of LDS
+    //           tile         waves stages    per CU   NN: eff, round      NT: eff, round       guarded kernel: NN, NT
+    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2, 16,   1,   0.958f, 15.1e-6f,   0.956f, 15.1e-6f,   0.883f, 13.6e-6f, 0.857f, 12.6e-6f),  // 0: 8 waves of 64 x 128, 128 KB of LDS
     // (1: the NN fit gave 0.959, level with configuration 0 inside the grid; beyond it the narrower tile
     //  re-reads more of A and falls behind -- 135 against 148 TFLOP/s at 65536^3 -- so it is rated just below)
-    MTNN_CFG_DMA(256, 128, 16, 2, 2, 3, 16,   2,   0.952f, 13.0e-6f,   0.950f, 13.8e-6f),  // 1: 4 waves of 128 x 64, 72 KB
-    MTNN_CFG_DMA(128, 128, 64, 4, 2, 2, 16,   1,   0.890f, 4.7e-6f,    0.888f, 4.6e-6f),   // 2: 8 waves of 32 x 64, 128 KB
-    MTNN_CFG_DMA(64, 64, 64, 2, 2, 2, 16,     2,   0.859f, 3.1e-6f,    0.850f, 2.5e-6f),   // 3: 4 waves of 32 x 32, 64 KB
+    MTNN_CFG_DMA(256, 128, 16, 2, 2, 3, 16,   2,   0.952f, 13.0e-6f,   0.950f, 13.8e-6f,   0.850f, 10.4e-6f, 0.859f, 11.1e-6f),  // 1: 4 waves of 128 x 64, 72 KB
+    MTNN_CFG_DMA(128, 128, 64, 4, 2, 2, 16,   1,   0.890f, 4.7e-6f,    0.888f, 4.6e-6f,   0.803f, 2.6e-6f, 0.778f, 2.6e-6f),   // 2: 8 waves of 32 x 64, 128 KB
+    MTNN_CFG_DMA(64, 64, 64, 2, 2, 2, 16,     2,   0.859f, 3.1e-6f,    0.850f, 2.5e-6f,   0.681f, 1.4e-6f, 0.671f, 1.4e-6f),   // 3: 4 waves of 32 x 32, 64 KB
     // (4, 5: fitted with four slab buffers and one workgroup per CU; two buffers and two per CU measured 4 % faster)
-    MTNN_CFG_DMA(32, 256, 32, 1, 4, 2, 16,    2,   0.688f, 2.5e-6f,    0.683f, 2.6e-6f),   // 4: 4 waves of 32 x 64 (small m), 72 KB
-    MTNN_CFG_DMA(256, 32, 32, 4, 1, 2, 16,    2,   0.672f, 3.4e-6f,    0.679f, 2.7e-6f),   // 5: 4 waves of 64 x 32 (small n), 72 KB
-    MTNN_CFG_DMA(128, 256, 32, 2, 4, 2, 16,   1,   0.936f, 7.9e-6f,    0.929f, 7.8e-6f),   // 6: 8 waves of 64 x 64, 96 KB
-    MTNN_CFG_DMA(256, 128, 32, 4, 2, 2, 16,   1,   0.930f, 8.3e-6f,    0.932f, 8.3e-6f),   // 7: 8 waves of 64 x 64, 96 KB
-    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16,    2,   0.881f, 4.4e-6f,    0.897f, 3.3e-6f),   // 8: 4 waves of 64 x 32, 48 KB
-    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16,    2,   0.899f, 3.6e-6f,    0.903f, 3.3e-6f),   // 9: 4 waves of 32 x 64, 48 KB
-    MTNN_CFG_DMA(128, 128, 32, 2, 2, 2, 16,   2,   0.943f, 6.2e-6f,    0.942f, 6.1e-6f),   // 10: 4 waves of 64 x 64, 64 KB
-    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16,    3,   0.843f, 4.1e-6f,    0.907f, 2.8e-6f),   // 11: as 8, three per CU (small k)
-    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16,    3,   0.907f, 3.6e-6f,    0.914f, 3.2e-6f),   // 12: as 9, three per CU (small k)
+    MTNN_CFG_DMA(32, 256, 32, 1, 4, 2, 16,    2,   0.688f, 2.5e-6f,    0.683f, 2.6e-6f,   0.708f, 2.4e-6f, 0.628f, 2.6e-6f),   // 4: 4 waves of 32 x 64 (small m), 72 KB
+    MTNN_CFG_DMA(256, 32, 32, 4, 1, 2, 16,    2,   0.672f, 3.4e-6f,    0.679f, 2.7e-6f,   0.576f, 2.8e-6f, 0.543f, 2.3e-6f),   // 5: 4 waves of 64 x 32 (small n), 72 KB
+    MTNN_CFG_DMA(128, 256, 32, 2, 4, 2, 16,   1,   0.936f, 7.9e-6f,    0.929f, 7.8e-6f,   0.832f, 6.8e-6f, 0.803f, 4.8e-6f),   // 6: 8 waves of 64 x 64, 96 KB
+    MTNN_CFG_DMA(256, 128, 32, 4, 2, 2, 16,   1,   0.930f, 8.3e-6f,    0.932f, 8.3e-6f,   0.848f, 5.6e-6f, 0.817f, 5.4e-6f),   // 7: 8 waves of 64 x 64, 96 KB
+    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16,    2,   0.881f, 4.4e-6f,    0.897f, 3.3e-6f,   0.746f, 2.6e-6f, 0.735f, 2.8e-6f),   // 8: 4 waves of 64 x 32, 48 KB
+    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16,    2,   0.899f, 3.6e-6f,    0.903f, 3.3e-6f,   0.791f, 2.6e-6f, 0.749f, 2.5e-6f),   // 9: 4 waves of 32 x 64, 48 KB
+    MTNN_CFG_DMA(128, 128, 32, 2, 2, 2, 16,   2,   0.943f, 6.2e-6f,    0.942f, 6.1e-6f,   0.834f, 4.9e-6f, 0.802f, 5.3e-6f),   // 10: 4 waves of 64 x 64, 64 KB
+    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16,    3,   0.843f, 4.1e-6f,    0.907f, 2.8e-6f,   0.746f, 2.6e-6f, 0.735f, 2.8e-6f),   // 11: as 8, three per CU (small k)
+    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16,    3,   0.907f, 3.6e-6f,    0.914f, 3.2e-6f,   0.791f, 2.6e-6f, 0.749f, 2.5e-6f),   // 12: as 9, three per CU (small k)
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 constexpr int kMaxSplits = 32;
@@ -1052,7 +1054,7 @@ float* scratch_for(hipStream_t s)
 // on (op, m, n, k), never on timing, so results stay reproducible.
 struct Choice { int cfg; int splits; };
 
-static double predicted_seconds(const Config& c, int op, int m, int n, int k, int splits)
+static double predicted_seconds(const Config& c, int op, int m, int n, int k, int splits, bool pipelined)
 {
     const double peak_cu = 157.3e12 / 256.0;
     const long long tiles = (long long)((m + c.bm - 1) / c.bm) * ((n + c.bn - 1) / c.bn);
@@ -1065,8 +1067,8 @@ static double predicted_seconds(const Config& c, int op, int m, int n, int k, in
     // a CU that holds a single 4-wave workgroup keeps only one wave per SIMD busy
     const double solo = (c.threads < 512 && per_cu < occ) ? 0.85 : 1.0;
     const double wg_flops = 2.0 * c.bm * c.bn * (double)kloc;
-    double t = (double)per_cu * wg_flops / (peak_cu * c.eff[op] * solo);
-    t += (double)c.round_s[op] * (double)((per_cu + occ - 1) / occ);  // first copies + result store per round
+    double t = (double)per_cu * wg_flops / (peak_cu * (pipelined ? c.eff[op] : c.eff_guarded[op]) * solo);
+    t += (double)(pipelined ? c.round_s[op] : c.round_guarded_s[op]) * (double)((per_cu + occ - 1) / occ);  // first copies + result store per round
     // HBM floor: operands once, result once
     const double bytes = 4.0 * ((double)m * k + (double)n * k + (double)m * n);
     if (t < bytes / 5.0e12) t = bytes / 5.0e12;
@@ -1101,7 +1103,8 @@ static double predicted_seconds_even_cut(const Config& c, int op, int m, int n, 
     return 1.02 * main_s + 0.69 * segments * c.round_s[op] + 0.62 * fix_bytes / 4.0e12 + 12.0e-6;
 }
 
-// pipelined: the operands allow the pipelined kernel (the even cut exists only there)
+// pipelined: the operands allow the pipelined kernel; otherwise the guarded kernel's own rates are
+// used (and the even cut, which exists only in the pipelined kernel, is not considered)
 static Choice choose(int op, int m, int n, int k, bool allow_split, bool pipelined = true)
 {
     Choice best = {0, 1};
@@ -1114,7 +1117,7 @@ static Choice choose(int op, int m, int n, int k, bool allow_split, bool pipelin
                 if ((size_t)m * n * splits * sizeof(float) > kScratchBytes) break;
                 if (k / splits < 2 * kSplitQuantum) break;
             }
-            const double t = predicted_seconds(kConfigs[c], o, m, n, k, splits);
+            const double t = predicted_seconds(kConfigs[c], o, m, n, k, splits, pipelined);
             if (t < best_t * 0.999) { best_t = t; best = Choice{c, splits}; }
         }
     }
