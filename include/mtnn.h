@@ -163,7 +163,8 @@ MTNN_API int mtnn_model_margin(const double *x, int nfeat, double *margin);
  * the model's choice when cfg is -1 and no split when cfg is given).  op: 0 = NN, 1 = NT.
  * Split-k keeps its partial products in a 64 MiB scratch buffer that the library allocates once per
  * (device, stream) the first time it is needed and never frees; a launch whose partials do not fit
- * runs unsplit.
+ * runs unsplit, and so does one issued while its stream is being captured into a HIP graph before the
+ * buffer exists (the library never allocates under capture; run the call once on that stream first).
  * splits = MTNN_GEMM_EVEN_CUT asks for the third way of dividing the work: the k ranges of all C
  * tiles, in units of 64, are laid in one line and cut into 256 x (workgroups per CU) equal pieces,
  * one per workgroup; tiles that a cut goes through are finished by a fix-up kernel that adds their

@@ -218,6 +218,13 @@ __global__ __launch_bounds__(256) void sgd_vec_kernel(float* __restrict__ P, con
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+__global__ __launch_bounds__(256) void copy_words_kernel(const float* __restrict__ in, float* __restrict__ out, long long total)
+{
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long long)gridDim.x * blockDim.x)
+        out[e] = in[e];
+}
+
 static unsigned blocks_for(long long total)
 {
     long long b = (total + 255) / 256;
@@ -475,7 +482,12 @@ int mtnn_copy_rows(void* stream, int rows, int cols, const float* in, float* out
     if (rows < 0 || cols < 0) return MTNN_ERR_DIM;
     if (rows == 0 || cols == 0) return MTNN_OK;
     if (!in || !out) return MTNN_ERR_NULL;
-    return status_of(hipMemcpyAsync(out, in, (size_t)rows * cols * 4, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
+    // a kernel rather than a runtime copy, so that a caller capturing the step into a HIP graph gets
+    // kernel nodes only
+    const long long total = (long long)rows * cols;
+    hipLaunchKernelGGL(mtnn::copy_words_kernel, dim3(mtnn::blocks_for(total)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), in, out, total);
+    return status_of(hipGetLastError());
 }
 
 }  // extern "C"

@@ -1036,6 +1036,11 @@ float* scratch_for(hipStream_t s)
     for (int i = 0; i < g_scratch_used; ++i)
         if (g_scratch[i].dev == dev && g_scratch[i].stream == s) return g_scratch[i].ptr;
     if (g_scratch_used == 8) return nullptr;
+    // never allocate under stream capture (it would invalidate the capture): the launch then runs
+    // without scratch, i.e. unsplit; a caller who wants the split paths in a graph warms the stream up first
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &capturing) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    if (capturing != hipStreamCaptureStatusNone) return nullptr;
     float* ptr = nullptr;
     if (hipMalloc(&ptr, kScratchBytes) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
     g_scratch[g_scratch_used++] = ScratchSlot{dev, s, ptr};

@@ -44,6 +44,7 @@ def main(argv=None):
     torch.cuda.set_device(0)
     mt.lib()
     stream = torch.cuda.current_stream()
+    side = torch.cuda.Stream()                                 # capture stream of the graph timings
     gen = torch.Generator(device="cuda")
     rows = []
     for family, spec in NETS.items():
@@ -76,10 +77,22 @@ def main(argv=None):
                     rec[name] = {"forward_ms": t_f * 1e3, "backward_ms": (t_s - t_f) * 1e3, "total_ms": t_s * 1e3,
                                  "forward_tflops": fwd_flop / t_f / 1e12,
                                  "total_tflops": (fwd_flop + bwd_flop) / t_s / 1e12}
+                    if name == "mtnn":
+                        # the same step captured once into a HIP graph and replayed: what the launch path costs
+                        # (lr is 0 here, so replays leave the weights alone)
+                        with torch.cuda.stream(side):          # one-time set-up of this stream (split-k scratch)
+                            mt.mtnn_fc_train_step(desc)
+                        side.synchronize()
+                        graph = torch.cuda.CUDAGraph()
+                        with torch.cuda.graph(graph, stream=side):
+                            mt.mtnn_fc_train_step(desc)
+                        t_g, _ = _time_batches(graph.replay, stream, args.samples, 2000.0)
+                        rec[name]["total_graph_ms"] = t_g * 1e3
+                        del graph
                 rows.append(rec)
                 print(f"[fcnet] {family} {hidden} batch {batch}: fwd NT {rec['nt']['forward_ms']:.3f} "
                       f"MTNN {rec['mtnn']['forward_ms']:.3f} TNN {rec['tnn']['forward_ms']:.3f} ms; "
-                      f"step NT {rec['nt']['total_ms']:.3f} MTNN {rec['mtnn']['total_ms']:.3f} ms "
+                      f"step NT {rec['nt']['total_ms']:.3f} MTNN {rec['mtnn']['total_ms']:.3f} (graph {rec['mtnn']['total_graph_ms']:.3f}) ms "
                       f"({rec['mtnn']['total_tflops']:.1f} TFLOP/s)", flush=True)
                 del X, labels, ws
             del W, b, gW, gb
@@ -104,11 +117,12 @@ def main(argv=None):
                     s = summary[family][phase]
                     f.write(f"| {family} | {phase[:-3]} | {s['nt']:.3f} | {s['mtnn']:.3f} | {s['tnn']:.3f} | "
                             f"{s['speedup_mtnn_over_nt']:.2f} |\n")
-            f.write("\n| family | hidden | batch | fwd NT ms | fwd MTNN ms | fwd TNN ms | step MTNN ms | step TFLOP/s | labels |\n")
-            f.write("|---|---|---|---|---|---|---|---|---|\n")
+            f.write("\n| family | hidden | batch | fwd NT ms | fwd MTNN ms | fwd TNN ms | step MTNN ms | step from a HIP graph ms | step TFLOP/s | labels |\n")
+            f.write("|---|---|---|---|---|---|---|---|---|---|\n")
             for r in rows:
                 f.write(f"| {r['family']} | {'-'.join(map(str, r['hidden']))} | {r['batch']} | {r['nt']['forward_ms']:.3f} | "
                         f"{r['mtnn']['forward_ms']:.3f} | {r['tnn']['forward_ms']:.3f} | {r['mtnn']['total_ms']:.3f} | "
+                        f"{r['mtnn']['total_graph_ms']:.3f} | "
                         f"{r['mtnn']['total_tflops']:.1f} | {r['labels']} |\n")
     return 0
 
