@@ -37,7 +37,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (the NT path needs no exchange between "
-              "GPUs; see DESIGN.md, 'More than one GPU'); run with --gpus 1", file=sys.stderr)
+              "GPUs: split A by rows or B by rows and run one process per GPU); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np

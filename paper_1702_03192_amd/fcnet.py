@@ -1,6 +1,6 @@
 """The paper's fully connected networks as a shape workload (Section V-C, Tables IX and X).  Needs the GPU.
 
-  python -m paper_1702_03192_amd.fcnet --out gpurun_out/fcnet_report.json [--md gpurun_out/fcnet_report.md]
+  python -m paper_1702_03192_amd.fcnet --out <dir>/fcnet_report.json [--md <dir>/fcnet_report.md]
 
 Table IX: two families -- "MNIST" (784 inputs, 10 outputs, hidden 2048-1024 / 2048-2048-1024 /
 2048-2048-2048-1024) and "synthetic" (26752 inputs and outputs, hidden 4096 x 2 / 3 / 4) -- each

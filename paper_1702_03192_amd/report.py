@@ -1,6 +1,6 @@
 """Measurement report over all benchmark configurations (needs the GPU).
 
-  python -m paper_1702_03192_amd.report --out gpurun_out/shape_report.json [--md gpurun_out/shape_report.md]
+  python -m paper_1702_03192_amd.report --out <dir>/shape_report.json [--md <dir>/shape_report.md]
 
 For every shape of configs 1, 2 and 4 and a spread of the config-3 grid it times the direct NT kernel,
 TNN (pre-allocated workspace) and the selected path (mtnn_select + mtnn_auto), and reports

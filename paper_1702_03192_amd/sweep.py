@@ -1,6 +1,6 @@
 """Data collection and model fitting for the selector (Section IV-A / IV-B of the MTNN paper).
 
-  python -m paper_1702_03192_amd.sweep collect --out gpurun_out/sweep_gfx950.csv     (needs the GPU)
+  python -m paper_1702_03192_amd.sweep collect --out <dir>/sweep_gfx950.csv          (needs the GPU)
   python -m paper_1702_03192_amd.sweep train   --csv <table> [<table> ...] --model <file>   (host only)
 
 collect: for every (m, n, k) of the grid {64, ..., 8192}^3 it times the direct NT kernel and TNN
