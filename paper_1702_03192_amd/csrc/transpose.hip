@@ -4,8 +4,8 @@
 // The operation is pure data movement, so the design is about HBM.  A 256-thread workgroup moves a
 // tile of TR input rows x TC input columns:
 //   read   a tile row is TC words (128 or 256 bytes, whole cache lines), 16 bytes per lane;
-//   LDS    tile[TR][TC] words with the columns of each row XOR-swizzled, so that neither the row-wise
-//          stores nor the column gather meet a bank conflict;
+//   LDS    tile[TR][TC] words with the columns of each row XOR-swizzled, which spreads the row-wise
+//          stores and the column gather over the banks;
 //   write  an output row segment is TR words (512 B or 1 KB): each lane gathers 4 words of one
 //          tile column from LDS and stores 16 B, with non-temporal stores so that the stream of
 //          results does not evict the input from the caches;
@@ -34,8 +34,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int TR_THREADS = 256;
 
 // LDS layout of the 16-byte-group path: tile[row][col ^ swz(row)], rows of TC words with no padding.
-// The XOR keeps both phases free of bank conflicts (64 banks of 4 bytes; a 64-lane access takes
-// two passes of 32 lanes, and within each pass all lanes must hit different banks):
+// The XOR spreads both phases over the banks (64 banks of 4 bytes; reasoning per pass of 32 lanes).
+// Measured SQ_LDS_BANK_CONFLICT per 128 x 32 tile: 384 cycles with a padded [TR][TC+1] tile, 128 with
+// this layout; a variant laid out for 64 lanes per pass measured 256, so this is the one kept:
 //   store phase  a pass holds 4 or 8 consecutive rows x all 16-byte groups of a row; the low two
 //                bits of swz differ between the rows that share a bank half;
 //   gather phase lane i reads rows 4 i + e (e = 0..3 in turn) of one column; swz(4 i + e) is a
