@@ -941,7 +941,7 @@ struct Config {
     int nstage;
     int threads;
     int waves_n;
-    // Fitted to measured times of the {64..8192}^3 grid with every CU busy:
+    // Fitted to measured times of the {64..8192}^3 grid with every CU busy (tune.py collect / fit):
     // time of one CU = tiles x (2 bm bn k / (eff x peak per CU)) + rounds x round_s
     // (separately for NN and NT: index = GemmOp)
     float eff[2];                     // rate of the k loop as a fraction of the fp32 MFMA peak
@@ -988,22 +988,21 @@ struct Config {
 
 static const Config kConfigs[] = {
     //           tile         waves stages    per CU   NN: eff, round      NT: eff, round       guarded kernel: NN, NT
-    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2, 16,   1,   0.958f, 15.1e-6f,   0.956f, 15.1e-6f,   0.883f, 13.6e-6f, 0.857f, 12.6e-6f),  // 0: 8 waves of 64 x 128, 128 KB of LDS
-    // (1: the NN fit gave 0.959, level with configuration 0 inside the grid; beyond it the narrower tile
+    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2, 16,   1,   0.949f, 13.8e-6f,   0.943f, 13.3e-6f,   0.871f, 12.7e-6f, 0.842f, 11.5e-6f),  // 0: 8 waves of 64 x 128, 128 KB of LDS
+    // (1: the NN fit puts it level with configuration 0 inside the grid; beyond it the narrower tile
     //  re-reads more of A and falls behind -- 135 against 148 TFLOP/s at 65536^3 -- so it is rated just below)
-    MTNN_CFG_DMA(256, 128, 16, 2, 2, 3, 16,   2,   0.952f, 13.0e-6f,   0.950f, 13.8e-6f,   0.850f, 10.4e-6f, 0.859f, 11.1e-6f),  // 1: 4 waves of 128 x 64, 72 KB
-    MTNN_CFG_DMA(128, 128, 64, 4, 2, 2, 16,   1,   0.890f, 4.7e-6f,    0.888f, 4.6e-6f,   0.803f, 2.6e-6f, 0.778f, 2.6e-6f),   // 2: 8 waves of 32 x 64, 128 KB
-    MTNN_CFG_DMA(64, 64, 64, 2, 2, 2, 16,     2,   0.859f, 3.1e-6f,    0.850f, 2.5e-6f,   0.681f, 1.4e-6f, 0.671f, 1.4e-6f),   // 3: 4 waves of 32 x 32, 64 KB
-    // (4, 5: fitted with four slab buffers and one workgroup per CU; two buffers and two per CU measured 4 % faster)
-    MTNN_CFG_DMA(32, 256, 32, 1, 4, 2, 16,    2,   0.688f, 2.5e-6f,    0.683f, 2.6e-6f,   0.708f, 2.4e-6f, 0.628f, 2.6e-6f),   // 4: 4 waves of 32 x 64 (small m), 72 KB
-    MTNN_CFG_DMA(256, 32, 32, 4, 1, 2, 16,    2,   0.672f, 3.4e-6f,    0.679f, 2.7e-6f,   0.576f, 2.8e-6f, 0.543f, 2.3e-6f),   // 5: 4 waves of 64 x 32 (small n), 72 KB
-    MTNN_CFG_DMA(128, 256, 32, 2, 4, 2, 16,   1,   0.936f, 7.9e-6f,    0.929f, 7.8e-6f,   0.832f, 6.8e-6f, 0.803f, 4.8e-6f),   // 6: 8 waves of 64 x 64, 96 KB
-    MTNN_CFG_DMA(256, 128, 32, 4, 2, 2, 16,   1,   0.930f, 8.3e-6f,    0.932f, 8.3e-6f,   0.848f, 5.6e-6f, 0.817f, 5.4e-6f),   // 7: 8 waves of 64 x 64, 96 KB
-    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16,    2,   0.881f, 4.4e-6f,    0.897f, 3.3e-6f,   0.746f, 2.6e-6f, 0.735f, 2.8e-6f),   // 8: 4 waves of 64 x 32, 48 KB
-    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16,    2,   0.899f, 3.6e-6f,    0.903f, 3.3e-6f,   0.791f, 2.6e-6f, 0.749f, 2.5e-6f),   // 9: 4 waves of 32 x 64, 48 KB
-    MTNN_CFG_DMA(128, 128, 32, 2, 2, 2, 16,   2,   0.943f, 6.2e-6f,    0.942f, 6.1e-6f,   0.834f, 4.9e-6f, 0.802f, 5.3e-6f),   // 10: 4 waves of 64 x 64, 64 KB
-    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16,    3,   0.843f, 4.1e-6f,    0.907f, 2.8e-6f,   0.746f, 2.6e-6f, 0.735f, 2.8e-6f),   // 11: as 8, three per CU (small k)
-    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16,    3,   0.907f, 3.6e-6f,    0.914f, 3.2e-6f,   0.791f, 2.6e-6f, 0.749f, 2.5e-6f),   // 12: as 9, three per CU (small k)
+    MTNN_CFG_DMA(256, 128, 16, 2, 2, 3, 16,   2,   0.943f, 11.9e-6f,   0.944f, 12.8e-6f,   0.840f, 9.8e-6f, 0.848f, 10.6e-6f),  // 1: 4 waves of 128 x 64, 72 KB
+    MTNN_CFG_DMA(128, 128, 64, 4, 2, 2, 16,   1,   0.884f, 4.0e-6f,   0.886f, 3.7e-6f,   0.802f, 2.1e-6f, 0.776f, 2.0e-6f),   // 2: 8 waves of 32 x 64, 128 KB
+    MTNN_CFG_DMA(64, 64, 64, 2, 2, 2, 16,     2,   0.886f, 2.9e-6f,   0.865f, 2.2e-6f,   0.688f, 1.1e-6f, 0.680f, 1.1e-6f),   // 3: 4 waves of 32 x 32, 64 KB
+    MTNN_CFG_DMA(32, 256, 32, 1, 4, 2, 16,    2,   0.903f, 2.9e-6f,   0.892f, 3.0e-6f,   0.698f, 1.7e-6f, 0.621f, 2.0e-6f),   // 4: 4 waves of 32 x 64 (small m), 72 KB
+    MTNN_CFG_DMA(256, 32, 32, 4, 1, 2, 16,    2,   0.869f, 3.9e-6f,   0.885f, 3.0e-6f,   0.567f, 1.9e-6f, 0.535f, 1.4e-6f),   // 5: 4 waves of 64 x 32 (small n), 72 KB
+    MTNN_CFG_DMA(128, 256, 32, 2, 4, 2, 16,   1,   0.927f, 6.9e-6f,   0.926f, 6.8e-6f,   0.822f, 5.9e-6f, 0.795f, 4.0e-6f),   // 6: 8 waves of 64 x 64, 96 KB
+    MTNN_CFG_DMA(256, 128, 32, 4, 2, 2, 16,   1,   0.920f, 7.1e-6f,   0.925f, 7.2e-6f,   0.837f, 4.8e-6f, 0.805f, 4.5e-6f),   // 7: 8 waves of 64 x 64, 96 KB
+    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16,    2,   0.885f, 3.6e-6f,   0.910f, 2.7e-6f,   0.740f, 1.9e-6f, 0.728f, 2.0e-6f),   // 8: 4 waves of 64 x 32, 48 KB
+    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16,    2,   0.904f, 2.9e-6f,   0.913f, 2.7e-6f,   0.783f, 2.0e-6f, 0.743f, 1.8e-6f),   // 9: 4 waves of 32 x 64, 48 KB
+    MTNN_CFG_DMA(128, 128, 32, 2, 2, 2, 16,   2,   0.906f, 5.0e-6f,   0.933f, 5.3e-6f,   0.820f, 4.2e-6f, 0.789f, 4.3e-6f),   // 10: 4 waves of 64 x 64, 64 KB
+    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16,    3,   0.839f, 3.4e-6f,   0.897f, 2.1e-6f,   0.753f, 2.1e-6f, 0.734f, 2.3e-6f),   // 11: as 8, three per CU (small k)
+    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16,    3,   0.907f, 3.0e-6f,   0.898f, 2.4e-6f,   0.807f, 2.2e-6f, 0.745f, 1.9e-6f),   // 12: as 9, three per CU (small k)
 };
 constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
 constexpr int kMaxSplits = 32;
@@ -1085,7 +1084,7 @@ static double predicted_seconds(const Config& c, int op, int m, int n, int k, in
 // where it cannot run.  Every workgroup gets the same number of k units, so the k-loop time is the
 // padded work spread over all CUs; a workgroup pays the time outside the k loop once per tile it
 // touches, and the fix-up kernel moves every cut tile's pieces once more.  The four weights are a
-// least-squares fit to 160 measured (shape, configuration) pairs (mean error 4.5 %).
+// least-squares fit to 130 measured (shape, configuration) pairs (tune.py even-cut; mean error 5 %).
 static double predicted_seconds_even_cut(const Config& c, int op, int m, int n, int k)
 {
     const double peak_cu = 157.3e12 / 256.0;
@@ -1105,7 +1104,7 @@ static double predicted_seconds_even_cut(const Config& c, int op, int m, int n, 
     const double cut_tiles = tiles < groups ? (double)tiles : (double)groups;
     const double pieces = tiles < groups ? ((double)groups / tiles + 1.0 < 2.0 ? 2.0 : (double)groups / tiles + 1.0) : 2.0;
     const double fix_bytes = cut_tiles * (pieces + 1.0) * c.bm * c.bn * 4.0;
-    return 1.02 * main_s + 0.69 * segments * c.round_s[op] + 0.62 * fix_bytes / 4.0e12 + 12.0e-6;
+    return 1.04 * main_s + 1.01 * segments * c.round_s[op] + 0.41 * fix_bytes / 4.0e12 + 11.0e-6;
 }
 
 // pipelined: the operands allow the pipelined kernel; otherwise the guarded kernel's own rates are
@@ -1128,9 +1127,10 @@ static Choice choose(int op, int m, int n, int k, bool allow_split, bool pipelin
     }
     if (allow_split && pipelined) {
         // the even cut, for the two configurations it was measured with (64 x 128 and 128 x 128 tiles,
-        // two per CU), and only where it promises 10 % or more: on 80 measured shapes that rule chose it 12
-        // times, never wrongly, for 8 % on average; at 5 % it was wrong twice
-        double sk_t = best_t * 0.90;
+        // two per CU), and only where it promises 5 % or more: on 65 measured shapes (tune.py even-cut)
+        // it beat the best ordinary launch of all configurations and split counts on 19, by 2-10 %; this
+        // rule took it on 13, once wrongly (5 % slower)
+        double sk_t = best_t * 0.95;
         for (int c = 9; c <= 10; ++c) {
             const double t = predicted_seconds_even_cut(kConfigs[c], o, m, n, k);
             if (t < sk_t) { sk_t = t; best = Choice{c, kStreamK}; }
