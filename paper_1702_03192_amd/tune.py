@@ -89,21 +89,23 @@ def _config_geometry(name):
     return bm, bn, occ
 
 
-def fit(table_path):
-    import numpy as np
-    from . import binding as mt
-    names = mt.gemm_configs()
-    geo = [_config_geometry(nm) for nm in names]
+def load_table(table_path):
     table = {}
     with open(table_path, newline="") as f:
         for r in csv.DictReader(f):
             key = (int(r["op"]), int(r["m"]), int(r["n"]), int(r["k"]))
             table.setdefault(key, {})[(int(r["cfg"]), int(r["splits"]))] = float(r["seconds"])
-    print("configuration: NN eff, round_s | NT eff, round_s   (shapes used, mean / max relative error of the fit)")
+    return table
+
+
+def fit_table(table, names):
+    """{(cfg, op): (eff, round_s, shapes used, mean relative error, max relative error)} -- None where a
+    configuration has fewer than four usable shapes."""
+    import numpy as np
+    out = {}
     for c, nm in enumerate(names):
-        bm, bn, occ = geo[c]
-        parts = []
-        for op in (mt.OP_NN, mt.OP_NT):
+        bm, bn, occ = _config_geometry(nm)
+        for op in (0, 1):
             X, y = [], []
             for (o, m, n, k), tab in table.items():
                 if o != op or (c, 1) not in tab or m % bm or n % bn:
@@ -115,13 +117,29 @@ def fit(table_path):
                 X.append([per_cu * 2.0 * bm * bn * k / PEAK_PER_CU, -(-per_cu // occ)])
                 y.append(tab[(c, 1)] - 3e-6)
             if len(y) < 4:
-                parts.append("(too few shapes)")
+                out[(c, op)] = None
                 continue
             X, y = np.array(X), np.array(y)
             w = 1.0 / y
             co = np.linalg.lstsq(X * w[:, None], y * w, rcond=None)[0]
             err = np.abs(X @ co / y - 1.0)
-            parts.append(f"{1.0 / co[0]:.3f}, {co[1] * 1e6:.1f}e-6  (n={len(y)}, {err.mean() * 100:.1f} % / {err.max() * 100:.1f} %)")
+            out[(c, op)] = (1.0 / co[0], co[1], len(y), float(err.mean()), float(err.max()))
+    return out
+
+
+def fit(table_path):
+    import numpy as np
+    from . import binding as mt
+    names = mt.gemm_configs()
+    table = load_table(table_path)
+    fitted = fit_table(table, names)
+    print("configuration: NN eff, round_s | NT eff, round_s   (shapes used, mean / max relative error of the fit)")
+    for c, nm in enumerate(names):
+        parts = []
+        for op in (mt.OP_NN, mt.OP_NT):
+            r = fitted[(c, op)]
+            parts.append("(too few shapes)" if r is None else
+                         f"{r[0]:.3f}, {r[1] * 1e6:.1f}e-6  (n={r[2]}, {r[3] * 100:.1f} % / {r[4] * 100:.1f} %)")
         print(f"  {c:2d} {nm}: " + " | ".join(parts))
     regrets = []
     for (op, m, n, k), tab in table.items():
