@@ -5,13 +5,14 @@
 #include "mtnn_internal.h"
 #include "selector.h"
 
+#include <atomic>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
 
 namespace {
 
-int g_last_hip_error = 0;   // last non-zero HIP error a launcher reported (diagnostics only)
+std::atomic<int> g_last_hip_error{0};   // last non-zero HIP error a launcher reported (diagnostics only)
 
 int launch_status(int err)
 {
@@ -224,7 +225,7 @@ const char* mtnn_status_string(int status)
     }
 }
 
-int mtnn_last_hip_error(void) { return g_last_hip_error; }
+int mtnn_last_hip_error(void) { return g_last_hip_error.load(); }
 
 int mtnn_version(void) { return 100; }
 

@@ -1213,7 +1213,7 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
             size_t lds_sk = c.lds_bytes_dma();
             const size_t share = ((160 * 1024) / (size_t)c.wg_per_cu()) & ~(size_t)1023;
             if (lds_sk < share - 1024) lds_sk = share - 1024;
-            static bool raised_sk[kNumConfigs][2][16] = {};
+            static std::atomic<bool> raised_sk[kNumConfigs][2][16] = {};
             int dev = 0;
             if (hipGetDevice(&dev) != hipSuccess) return (int)hipGetLastError();
             if (lds_sk > 64 * 1024 && (dev < 0 || dev >= 16 || !raised_sk[cfg][op][dev])) {
@@ -1249,7 +1249,7 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
     }
     if (lds > 64 * 1024) {
         // opt in to the large LDS carve-out once per kernel and device
-        static bool raised[kNumConfigs][2][3][16] = {};
+        static std::atomic<bool> raised[kNumConfigs][2][3][16] = {};   // (racing callers at worst set the attribute twice)
         const int which = dma_ok ? 2 : (vec ? 1 : 0);
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess) return (int)hipGetLastError();

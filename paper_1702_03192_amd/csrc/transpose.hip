@@ -27,6 +27,8 @@
 // edge are moved word by word.
 #include "mtnn_internal.h"
 
+#include <atomic>
+
 namespace mtnn {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -145,7 +147,7 @@ static int launch_transpose_t(hipStream_t s, int rows, int cols, const uint32_t*
     auto kern = transpose_kernel<TR, TC, VEC, NTL>;
     if (lds > 64 * 1024) {
         // opt in to the large LDS carve-out once per device
-        static bool raised[16] = {};
+        static std::atomic<bool> raised[16] = {};
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess) return (int)hipGetLastError();
         if (dev < 0 || dev >= 16 || !raised[dev]) {
