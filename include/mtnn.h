@@ -180,6 +180,9 @@ MTNN_API int mtnn_gemm_ex(void *stream, int op, int cfg, int splits, int m, int 
                  const float *A, int lda, const float *B, int ldb, float *C, int ldc);
 /* How many launches of this process took the even-cut path (diagnostics, tests). */
 MTNN_API long long mtnn_gemm_even_cut_launches(void);
+/* How many products of this process ran with a fused epilogue (mtnn_fc_layer_forward,
+ * mtnn_fc_weight_grad_sgd) rather than with the separate pass (diagnostics, tests). */
+MTNN_API long long mtnn_gemm_fused_epilogue_launches(void);
 
 /* ---- one training step of a fully connected net (Section V-C, Table IX sizes) ---------------- */
 
@@ -233,8 +236,32 @@ MTNN_API int mtnn_fc_bias_grad(void *stream, int batch, int width, const float *
  * db[j] = sum_i dH[i][j]; dH and H batch x width dense, scratch as for mtnn_fc_bias_grad. */
 MTNN_API int mtnn_fc_relu_backward_bias_grad(void *stream, int batch, int width, float *dH, const float *H,
                                     float *db, float *scratch);
-/* P[e] -= lr * G[e] over `count` elements. */
+/* P[e] = fma(-lr, G[e], P[e]) over `count` elements. */
 MTNN_API int mtnn_fc_sgd(void *stream, long long count, float *P, const float *G, float lr);
+
+/* The two products of a layer with the elementwise step that follows them done in the product's
+ * epilogue, so that the result makes one trip to memory instead of three (Section V-C: the forward
+ * product of a layer is the NT operation, the weight gradient an NN operation; bias, ReLU and SGD are
+ * this library's reading, as above).  Both give, bit for bit, what the separate calls give.
+ *
+ * mtnn_fc_layer_forward: Y = act(X x W^T + b), X m x k (mini-batch x inputs), W n x k, b n values,
+ * Y m x n; relu = 1 clamps at zero, 0 does not.  mode: +1 the NT kernel, -1 TNN (Algorithm 1; needs
+ * the workspace of mtnn_tnn), 0 the predictor's choice exactly as in mtnn_auto (Algorithm 2); the
+ * path taken (+1 / -1) is stored in *chosen if it is non-NULL.  Arguments and errors as for
+ * mtnn_nt / mtnn_tnn; b must not overlap Y (MTNN_ERR_ALIAS).
+ *
+ * mtnn_fc_weight_grad_sgd: dW = A x B (NN: A m x k, B k x n, dW m x n) and W = fma(-lr, dW, W) for the
+ * m x n matrix W, which must not overlap A, B or dW.  In a layer: A = the transposed output
+ * gradient (outputs x mini-batch), B = the layer's input activations.
+ *
+ * The epilogue is fused where the pipelined kernel runs (16-byte aligned operands, k % 4 = 0; for
+ * the forward product also in the reduction kernel of a split-k launch); elsewhere the call runs the
+ * plain product followed by the separate pass, with the same results. */
+MTNN_API int mtnn_fc_layer_forward(void *stream, int mode, int m, int n, int k, const float *X, int ldx,
+                          const float *W, int ldw, const float *b, int relu, float *Y, int ldy,
+                          void *workspace, size_t workspace_bytes, int *chosen);
+MTNN_API int mtnn_fc_weight_grad_sgd(void *stream, int m, int n, int k, const float *A, int lda,
+                            const float *B, int ldb, float *dW, int lddw, float *W, int ldw, float lr);
 /* dense device-to-device copy of a rows x cols matrix */
 MTNN_API int mtnn_copy_rows(void *stream, int rows, int cols, const float *in, float *out);
 

@@ -79,12 +79,17 @@ SIGNATURES = {
     "mtnn_fc_bias_grad": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp, _c_vp]),
     "mtnn_fc_relu_backward_bias_grad": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp, _c_vp, _c_vp]),
     "mtnn_fc_sgd": (_c_int, [_c_vp, _c_ll, _c_vp, _c_vp, _c_flt]),
+    "mtnn_fc_layer_forward": (_c_int, [_c_vp, _c_int, _c_int, _c_int, _c_int, _c_vp, _c_int, _c_vp, _c_int, _c_vp, _c_int,
+                                       _c_vp, _c_int, _c_vp, _c_sz, _p_int]),
+    "mtnn_fc_weight_grad_sgd": (_c_int, [_c_vp, _c_int, _c_int, _c_int, _c_vp, _c_int, _c_vp, _c_int, _c_vp, _c_int,
+                                         _c_vp, _c_int, _c_flt]),
     "mtnn_copy_rows": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp]),
     "mtnn_copy_bytes": (_c_int, [_c_vp, _c_sz, _c_vp, _c_vp]),
     "mtnn_status_string": (ctypes.c_char_p, [_c_int]),
     "mtnn_last_hip_error": (_c_int, []),
     "mtnn_version": (_c_int, []),
     "mtnn_gemm_even_cut_launches": (ctypes.c_longlong, []),
+    "mtnn_gemm_fused_epilogue_launches": (ctypes.c_longlong, []),
     "mtnn_device_attribute": (_c_int, [_c_int]),
 }
 
@@ -386,6 +391,29 @@ def mtnn_fc_sgd(P, G, lr: float, stream=None):
     _check(lib().mtnn_fc_sgd(_stream(stream), P.numel(), P.data_ptr(), G.data_ptr(), lr), "mtnn_fc_sgd")
 
 
+def mtnn_fc_layer_forward(X, W, b, Y, relu: bool, mode: int = 0, workspace=None, stream=None) -> int:
+    """Y = act(X x W^T + b) with the bias and the clamp in the product's epilogue.  mode: +1 NT, -1 TNN,
+    0 the predictor's choice; returns the path that ran (+1 / -1)."""
+    (px, ldx), (pw_, ldw), (py, ldy) = _dev(X, "X"), _dev(W, "W"), _dev(Y, "Y")
+    m, k = X.shape
+    n = W.shape[0]
+    pw, wb = _ws(workspace)
+    chosen = ctypes.c_int(0)
+    _check(lib().mtnn_fc_layer_forward(_stream(stream), mode, m, n, k, px, ldx, pw_, ldw, b.data_ptr(), 1 if relu else 0,
+                                       py, ldy, pw, wb, ctypes.byref(chosen)), "mtnn_fc_layer_forward")
+    return chosen.value
+
+
+def mtnn_fc_weight_grad_sgd(A, B, dW, W, lr: float, stream=None):
+    """dW = A x B (NN) and W = fma(-lr, dW, W), the update in the product's epilogue."""
+    (pa, lda), (pb, ldb), (pg, ldg), (pw_, ldw) = _dev(A, "A"), _dev(B, "B"), _dev(dW, "dW"), _dev(W, "W")
+    m, k = A.shape
+    n = B.shape[1]
+    _check(lib().mtnn_fc_weight_grad_sgd(_stream(stream), m, n, k, pa, lda, pb, ldb, pg, ldg, pw_, ldw, lr),
+           "mtnn_fc_weight_grad_sgd")
+    return dW
+
+
 def mtnn_copy_bytes(src, dst, stream=None):
     """Streaming device copy of a whole tensor (the known-traffic calibration kernel)."""
     nbytes = src.numel() * src.element_size()
@@ -408,6 +436,10 @@ EVEN_CUT = -2      # `splits` value of mtnn_gemm_ex: cut all tiles' k ranges eve
 
 def mtnn_gemm_even_cut_launches() -> int:
     return int(lib().mtnn_gemm_even_cut_launches())
+
+
+def mtnn_gemm_fused_epilogue_launches() -> int:
+    return int(lib().mtnn_gemm_fused_epilogue_launches())
 
 
 def mtnn_device_attribute(what: int) -> int:

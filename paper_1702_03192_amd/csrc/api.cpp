@@ -58,17 +58,58 @@ int check_gemm(int op, int m, int n, int k, const float* A, int lda, const float
     return MTNN_OK;
 }
 
+// epi: work to fuse into the product where the launch can, done as a separate pass over C where it cannot
 int run_gemm(void* stream, int op, int cfg, int splits, int m, int n, int k, const float* A, int lda,
-             const float* B, int ldb, float* C, int ldc)
+             const float* B, int ldb, float* C, int ldc, const mtnn::Epilogue* epi = nullptr)
 {
     const int st = check_gemm(op, m, n, k, A, lda, B, ldb, C, ldc);
     if (st != MTNN_OK) return st;
     if (m == 0 || n == 0) return MTNN_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int err;
+    bool fused = false;
     if (k == 0) err = mtnn::launch_fill_zero(s, m, n, C, ldc);
-    else err = mtnn::launch_gemm(s, op, cfg, splits, m, n, k, A, lda, B, ldb, C, ldc);
+    else err = mtnn::launch_gemm(s, op, cfg, splits, m, n, k, A, lda, B, ldb, C, ldc, epi, &fused);
+    if (err == 0 && epi && !fused) {
+        if (epi->kind == 1) err = mtnn::launch_bias_act(s, m, n, C, ldc, epi->bias, epi->relu);
+        else err = mtnn::launch_sgd_2d(s, m, n, epi->W, epi->ldw, C, ldc, epi->lr);
+    }
     return launch_status(err);
+}
+
+// Algorithm 1 with an optional epilogue on the NN product
+int tnn_impl(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
+             float* C, int ldc, void* workspace, size_t workspace_bytes, const mtnn::Epilogue* epi)
+{
+    int st = check_gemm(mtnn::OP_NT, m, n, k, A, lda, B, ldb, C, ldc);
+    if (st != MTNN_OK) return st;
+    if (m == 0 || n == 0) return MTNN_OK;
+    if (k == 0) return run_gemm(stream, mtnn::OP_NT, -1, 0, m, n, k, A, lda, B, ldb, C, ldc, epi);
+    if (!workspace || workspace_bytes < mtnn_tnn_workspace_bytes(n, k)) return MTNN_ERR_WORKSPACE;
+    float* Bt = static_cast<float*>(workspace);
+    const Range rw = span(Bt, k, n, n);
+    if (overlap(rw, span(A, m, k, lda)) || overlap(rw, span(B, n, k, ldb)) || overlap(rw, span(C, m, n, ldc)))
+        return MTNN_ERR_ALIAS;
+    // Algorithm 1: B (n x k) -> B^T (k x n), then the NN product on the same stream
+    st = mtnn_transpose(stream, n, k, B, ldb, Bt, n);
+    if (st != MTNN_OK) return st;
+    return run_gemm(stream, mtnn::OP_NN, -1, 0, m, n, k, A, lda, Bt, n, C, ldc, epi);
+}
+
+// The choice of Algorithm 2: the predictor, overridden by the memory rule of Section II (no room for
+// B^T: NT) and, for experiments, by the environment variable MTNN_FORCE=nt|tnn (read once).
+int pick_label(int m, int n, int k, const void* workspace, size_t workspace_bytes)
+{
+    static const int forced = [] {
+        const char* e = getenv("MTNN_FORCE");
+        if (!e) return 0;
+        if (!strcmp(e, "nt") || !strcmp(e, "NT")) return 1;
+        if (!strcmp(e, "tnn") || !strcmp(e, "TNN")) return -1;
+        return 0;
+    }();
+    int label = (m > 0 && n > 0 && k > 0) ? (forced ? forced : mtnn_select(m, n, k)) : 1;
+    if (label == -1 && (!workspace || workspace_bytes < mtnn_tnn_workspace_bytes(n, k))) label = 1;
+    return label;
 }
 
 int check_transpose(int rows, int cols, const float* in, int ldin, const float* out, int ldout)
@@ -173,39 +214,51 @@ size_t mtnn_tnn_workspace_bytes(int n, int k)
 int mtnn_tnn(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
              float* C, int ldc, void* workspace, size_t workspace_bytes)
 {
-    int st = check_gemm(mtnn::OP_NT, m, n, k, A, lda, B, ldb, C, ldc);
-    if (st != MTNN_OK) return st;
-    if (m == 0 || n == 0) return MTNN_OK;
-    if (k == 0) return run_gemm(stream, mtnn::OP_NT, -1, 0, m, n, k, A, lda, B, ldb, C, ldc);
-    if (!workspace || workspace_bytes < mtnn_tnn_workspace_bytes(n, k)) return MTNN_ERR_WORKSPACE;
-    float* Bt = static_cast<float*>(workspace);
-    const Range rw = span(Bt, k, n, n);
-    if (overlap(rw, span(A, m, k, lda)) || overlap(rw, span(B, n, k, ldb)) || overlap(rw, span(C, m, n, ldc)))
-        return MTNN_ERR_ALIAS;
-    // Algorithm 1: B (n x k) -> B^T (k x n), then the NN product on the same stream
-    st = mtnn_transpose(stream, n, k, B, ldb, Bt, n);
-    if (st != MTNN_OK) return st;
-    return run_gemm(stream, mtnn::OP_NN, -1, 0, m, n, k, A, lda, Bt, n, C, ldc);
+    return tnn_impl(stream, m, n, k, A, lda, B, ldb, C, ldc, workspace, workspace_bytes, nullptr);
 }
 
 int mtnn_auto(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
               float* C, int ldc, void* workspace, size_t workspace_bytes, int* chosen)
 {
-    // Algorithm 2.  The memory rule of Section II overrides the predictor; the environment variable
-    // MTNN_FORCE=nt|tnn (read once) overrides the predictor for experiments.
-    static const int forced = [] {
-        const char* e = getenv("MTNN_FORCE");
-        if (!e) return 0;
-        if (!strcmp(e, "nt") || !strcmp(e, "NT")) return 1;
-        if (!strcmp(e, "tnn") || !strcmp(e, "TNN")) return -1;
-        return 0;
-    }();
-    int label = (m > 0 && n > 0 && k > 0) ? (forced ? forced : mtnn_select(m, n, k)) : 1;
-    if (label == -1 && (!workspace || workspace_bytes < mtnn_tnn_workspace_bytes(n, k))) label = 1;
+    // Algorithm 2
+    const int label = pick_label(m, n, k, workspace, workspace_bytes);
     if (chosen) *chosen = label;
     if (label == -1)
         return mtnn_tnn(stream, m, n, k, A, lda, B, ldb, C, ldc, workspace, workspace_bytes);
     return mtnn_nt(stream, m, n, k, A, lda, B, ldb, C, ldc);
+}
+
+int mtnn_fc_layer_forward(void* stream, int mode, int m, int n, int k, const float* X, int ldx, const float* W, int ldw,
+                          const float* b, int relu, float* Y, int ldy, void* workspace, size_t workspace_bytes, int* chosen)
+{
+    if ((mode != 1 && mode != 0 && mode != -1) || (relu != 0 && relu != 1)) return MTNN_ERR_ARG;
+    const int st = check_gemm(mtnn::OP_NT, m, n, k, X, ldx, W, ldw, Y, ldy);
+    if (st != MTNN_OK) return st;
+    int label = mode;
+    if (mode == 0) label = pick_label(m, n, k, workspace, workspace_bytes);
+    if (chosen) *chosen = label;
+    if (m == 0 || n == 0) return MTNN_OK;
+    if (!b) return MTNN_ERR_NULL;
+    if (overlap(span(Y, m, n, ldy), span(b, 1, n, n))) return MTNN_ERR_ALIAS;
+    const mtnn::Epilogue epi = {1, b, relu, nullptr, 0, 0.f};
+    if (label == -1)
+        return tnn_impl(stream, m, n, k, X, ldx, W, ldw, Y, ldy, workspace, workspace_bytes, &epi);
+    return run_gemm(stream, mtnn::OP_NT, -1, 0, m, n, k, X, ldx, W, ldw, Y, ldy, &epi);
+}
+
+int mtnn_fc_weight_grad_sgd(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
+                            float* dW, int lddw, float* W, int ldw, float lr)
+{
+    const int st = check_gemm(mtnn::OP_NN, m, n, k, A, lda, B, ldb, dW, lddw);
+    if (st != MTNN_OK) return st;
+    if (m == 0 || n == 0) return MTNN_OK;
+    if (!W) return MTNN_ERR_NULL;
+    if (ldw < n) return MTNN_ERR_LD;
+    const Range rw = span(W, m, n, ldw);
+    if (overlap(rw, span(dW, m, n, lddw)) || (k > 0 && (overlap(rw, span(A, m, k, lda)) || overlap(rw, span(B, k, n, ldb)))))
+        return MTNN_ERR_ALIAS;
+    const mtnn::Epilogue epi = {2, nullptr, 0, W, ldw, lr};
+    return run_gemm(stream, mtnn::OP_NN, -1, 0, m, n, k, A, lda, B, ldb, dW, lddw, &epi);
 }
 
 const char* mtnn_status_string(int status)
@@ -230,6 +283,7 @@ int mtnn_last_hip_error(void) { return g_last_hip_error.load(); }
 int mtnn_version(void) { return 100; }
 
 long long mtnn_gemm_even_cut_launches(void) { return mtnn::gemm_streamk_launches(); }
+long long mtnn_gemm_fused_epilogue_launches(void) { return mtnn::gemm_fused_launches(); }
 
 int mtnn_device_attribute(int what)
 {

@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ P, const f
 {
     for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
          e += (long long)gridDim.x * blockDim.x)
-        P[e] = P[e] - lr * G[e];
+        P[e] = __builtin_fmaf(-lr, G[e], P[e]);      // (the fused update in the product's epilogue is the same fma)
 }
 
 // ---- 16-byte versions (width a multiple of 4, 16-byte aligned bases) -----------------------------
@@ -191,8 +191,9 @@ __global__ __launch_bounds__(256) void colsum_vec_kernel(float* __restrict__ dZ,
 
 // db[col] = sum over chunks of part[chunk][col]: 64 columns per workgroup, its four waves take a
 // quarter of the chunks each (in order), then the four sums are added in wave order
+// P (optional): the parameter the sums are the gradient of; it takes its SGD step here, P = fma(-lr, db, P)
 __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, int chunks, int width,
-                                                           float* __restrict__ db)
+                                                           float* __restrict__ db, float* __restrict__ P, float lr)
 {
     __shared__ float acc[4][64];
     const int lane = threadIdx.x & 63;
@@ -204,7 +205,11 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
         for (int ch = sub * per; ch < min(chunks, (sub + 1) * per); ++ch) s += part[(size_t)ch * width + col];
     acc[sub][lane] = s;
     __syncthreads();
-    if (sub == 0 && col < width) db[col] = (acc[0][lane] + acc[1][lane]) + (acc[2][lane] + acc[3][lane]);
+    if (sub == 0 && col < width) {
+        const float g = (acc[0][lane] + acc[1][lane]) + (acc[2][lane] + acc[3][lane]);
+        db[col] = g;
+        if (P) P[col] = __builtin_fmaf(-lr, g, P[col]);
+    }
 }
 
 __global__ __launch_bounds__(256) void sgd_vec_kernel(float* __restrict__ P, const float* __restrict__ G, long long total4, float lr)
@@ -212,7 +217,37 @@ __global__ __launch_bounds__(256) void sgd_vec_kernel(float* __restrict__ P, con
     for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total4;
          e += (long long)gridDim.x * blockDim.x) {
         f32x4* p = reinterpret_cast<f32x4*>(P) + e;
-        *p = *p - lr * reinterpret_cast<const f32x4*>(G)[e];
+        const f32x4 g = reinterpret_cast<const f32x4*>(G)[e];
+        f32x4 v = *p;
+        v.x = __builtin_fmaf(-lr, g.x, v.x); v.y = __builtin_fmaf(-lr, g.y, v.y);
+        v.z = __builtin_fmaf(-lr, g.z, v.z); v.w = __builtin_fmaf(-lr, g.w, v.w);
+        *p = v;
+    }
+}
+
+// The same two passes for matrices whose rows are further apart than their width
+__global__ __launch_bounds__(256) void bias_act_ld_kernel(float* __restrict__ Z, long ld, const float* __restrict__ b,
+                                                          long long total, int width, int relu)
+{
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long long)gridDim.x * blockDim.x) {
+        const long long i = e / width;
+        const int j = (int)(e - i * width);
+        float v = Z[(size_t)i * ld + j] + b[j];
+        if (relu) v = v > 0.f ? v : 0.f;
+        Z[(size_t)i * ld + j] = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void sgd_ld_kernel(float* __restrict__ P, long ldp, const float* __restrict__ G, long ldg,
+                                                     long long total, int width, float lr)
+{
+    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+         e += (long long)gridDim.x * blockDim.x) {
+        const long long i = e / width;
+        const int j = (int)(e - i * width);
+        float* p = P + (size_t)i * ldp + j;
+        *p = __builtin_fmaf(-lr, G[(size_t)i * ldg + j], *p);
     }
 }
 
@@ -229,6 +264,30 @@ static unsigned blocks_for(long long total)
 {
     long long b = (total + 255) / 256;
     return (unsigned)(b > 8192 ? 8192 : (b < 1 ? 1 : b));
+}
+
+// Z (rows x width, leading dimension ld) += b per column, then the clamp
+int launch_bias_act(hipStream_t s, int rows, int width, float* Z, long ld, const float* b, int relu)
+{
+    if (ld == width) {
+        const int st = mtnn_fc_bias_act(s, rows, width, Z, b, relu);
+        return st == MTNN_OK ? 0 : (int)hipErrorLaunchFailure;
+    }
+    const long long total = (long long)rows * width;
+    hipLaunchKernelGGL(bias_act_ld_kernel, dim3(blocks_for(total)), dim3(256), 0, s, Z, ld, b, total, width, relu);
+    return (int)hipGetLastError();
+}
+
+// P (rows x width, leading dimension ldp) = fma(-lr, G, P)
+int launch_sgd_2d(hipStream_t s, int rows, int width, float* P, long ldp, const float* G, long ldg, float lr)
+{
+    if (ldp == width && ldg == width) {
+        const int st = mtnn_fc_sgd(s, (long long)rows * width, P, G, lr);
+        return st == MTNN_OK ? 0 : (int)hipErrorLaunchFailure;
+    }
+    const long long total = (long long)rows * width;
+    hipLaunchKernelGGL(sgd_ld_kernel, dim3(blocks_for(total)), dim3(256), 0, s, P, ldp, G, ldg, total, width, lr);
+    return (int)hipGetLastError();
 }
 
 }  // namespace mtnn
@@ -291,7 +350,9 @@ static int colsum_chunks(int batch, int* rows_per_chunk)
     return (batch + *rows_per_chunk - 1) / *rows_per_chunk;
 }
 
-int mtnn_fc_bias_grad(void* stream, int batch, int width, const float* dZ, float* db, float* scratch)
+// The column sums, and (P non-null) the SGD step of the bias they are the gradient of: in the same
+// launch where the 16-byte path runs, as a separate small pass otherwise.
+static int bias_grad_impl(void* stream, int batch, int width, const float* dZ, float* db, float* scratch, float* P, float lr)
 {
     if (batch <= 0 || width <= 0) return MTNN_ERR_DIM;
     if (!dZ || !db) return MTNN_ERR_NULL;
@@ -301,7 +362,7 @@ int mtnn_fc_bias_grad(void* stream, int batch, int width, const float* dZ, float
         const int chunks = colsum_chunks(batch, &rows_per_chunk);
         hipLaunchKernelGGL(mtnn::colsum_vec_kernel<false>, dim3((width / 4 + 63) / 64, chunks), dim3(256), 0, s,
                            const_cast<float*>(dZ), static_cast<const float*>(nullptr), scratch, batch, width, rows_per_chunk);
-        hipLaunchKernelGGL(mtnn::colsum_final_kernel, dim3((width + 63) / 64), dim3(256), 0, s, scratch, chunks, width, db);
+        hipLaunchKernelGGL(mtnn::colsum_final_kernel, dim3((width + 63) / 64), dim3(256), 0, s, scratch, chunks, width, db, P, lr);
         return status_of(hipGetLastError());
     }
     const int col_blocks = (width + 63) / 64;
@@ -311,17 +372,25 @@ int mtnn_fc_bias_grad(void* stream, int batch, int width, const float* dZ, float
     if (chunks > batch / 32) chunks = batch / 32;
     if (!scratch || chunks < 2) {
         hipLaunchKernelGGL(mtnn::bias_grad_kernel, dim3(col_blocks), dim3(256), 0, s, dZ, db, batch, width);
-        return status_of(hipGetLastError());
+    } else {
+        const int rows_per_chunk = (batch + chunks - 1) / chunks;
+        chunks = (batch + rows_per_chunk - 1) / rows_per_chunk;
+        hipLaunchKernelGGL(mtnn::bias_grad_partial_kernel, dim3(col_blocks, chunks), dim3(256), 0, s, dZ, scratch, batch,
+                           width, rows_per_chunk);
+        hipLaunchKernelGGL(mtnn::bias_grad_final_kernel, dim3((width + 255) / 256), dim3(256), 0, s, scratch, chunks, width, db);
     }
-    const int rows_per_chunk = (batch + chunks - 1) / chunks;
-    chunks = (batch + rows_per_chunk - 1) / rows_per_chunk;
-    hipLaunchKernelGGL(mtnn::bias_grad_partial_kernel, dim3(col_blocks, chunks), dim3(256), 0, s, dZ, scratch, batch,
-                       width, rows_per_chunk);
-    hipLaunchKernelGGL(mtnn::bias_grad_final_kernel, dim3((width + 255) / 256), dim3(256), 0, s, scratch, chunks, width, db);
-    return status_of(hipGetLastError());
+    const int st = status_of(hipGetLastError());
+    if (st != MTNN_OK || !P) return st;
+    return mtnn_fc_sgd(stream, width, P, db, lr);
 }
 
-int mtnn_fc_relu_backward_bias_grad(void* stream, int batch, int width, float* dH, const float* H, float* db, float* scratch)
+int mtnn_fc_bias_grad(void* stream, int batch, int width, const float* dZ, float* db, float* scratch)
+{
+    return bias_grad_impl(stream, batch, width, dZ, db, scratch, nullptr, 0.f);
+}
+
+static int relu_backward_bias_grad_impl(void* stream, int batch, int width, float* dH, const float* H, float* db,
+                                        float* scratch, float* P, float lr)
 {
     if (batch <= 0 || width <= 0) return MTNN_ERR_DIM;
     if (!dH || !H || !db) return MTNN_ERR_NULL;
@@ -331,12 +400,17 @@ int mtnn_fc_relu_backward_bias_grad(void* stream, int batch, int width, float* d
         const int chunks = colsum_chunks(batch, &rows_per_chunk);
         hipLaunchKernelGGL(mtnn::colsum_vec_kernel<true>, dim3((width / 4 + 63) / 64, chunks), dim3(256), 0, s,
                            dH, H, scratch, batch, width, rows_per_chunk);
-        hipLaunchKernelGGL(mtnn::colsum_final_kernel, dim3((width + 63) / 64), dim3(256), 0, s, scratch, chunks, width, db);
+        hipLaunchKernelGGL(mtnn::colsum_final_kernel, dim3((width + 63) / 64), dim3(256), 0, s, scratch, chunks, width, db, P, lr);
         return status_of(hipGetLastError());
     }
     const int st = mtnn_fc_relu_backward(stream, (long long)batch * width, dH, H);
     if (st != MTNN_OK) return st;
-    return mtnn_fc_bias_grad(stream, batch, width, dH, db, scratch);
+    return bias_grad_impl(stream, batch, width, dH, db, scratch, P, lr);
+}
+
+int mtnn_fc_relu_backward_bias_grad(void* stream, int batch, int width, float* dH, const float* H, float* db, float* scratch)
+{
+    return relu_backward_bias_grad_impl(stream, batch, width, dH, H, db, scratch, nullptr, 0.f);
 }
 
 int mtnn_fc_sgd(void* stream, long long count, float* P, const float* G, float lr)
@@ -424,14 +498,9 @@ static int fc_run(void* stream, const mtnn_fc_step_desc* d, bool forward_only)
     // forward: H_l = act(H_{l-1} x W_l^T + b_l) -- the NT operation of each layer
     for (int l = 0; l < L; ++l) {
         const int in = dims[l], out = dims[l + 1];
-        if (d->forward_mode == 1)
-            st = mtnn_nt(stream, batch, out, in, H[l], in, d->W[l], in, H[l + 1], out);
-        else if (d->forward_mode == -1)
-            st = mtnn_tnn(stream, batch, out, in, H[l], in, d->W[l], in, H[l + 1], out, Bt, bt_bytes);
-        else
-            st = mtnn_auto(stream, batch, out, in, H[l], in, d->W[l], in, H[l + 1], out, Bt, bt_bytes, nullptr);
-        if (st != MTNN_OK) return st;
-        st = mtnn_fc_bias_act(stream, batch, out, H[l + 1], d->b[l], l < L - 1 ? 1 : 0);
+        // (bias and ReLU in the product's epilogue)
+        st = mtnn_fc_layer_forward(stream, d->forward_mode, batch, out, in, H[l], in, d->W[l], in, d->b[l],
+                                   l < L - 1 ? 1 : 0, H[l + 1], out, Bt, bt_bytes, nullptr);
         if (st != MTNN_OK) return st;
     }
     if (d->logits) {
@@ -448,25 +517,23 @@ static int fc_run(void* stream, const mtnn_fc_step_desc* d, bool forward_only)
     for (int l = L - 1; l >= 0; --l) {
         const int in = dims[l], out = dims[l + 1];
         if (l == L - 1) {                      // below, db comes with the ReLU mask of the layer above
-            st = mtnn_fc_bias_grad(stream, batch, out, dZ, d->db[l], bias_part);
+            st = bias_grad_impl(stream, batch, out, dZ, d->db[l], bias_part, d->b[l], d->lr);   // (and b_l takes its step)
             if (st != MTNN_OK) return st;
         }
-        // dW_l = dZ^T x H_l : transpose dZ (batch x out -> out x batch), then an NN product
-        st = mtnn_transpose(stream, batch, out, dZ, out, dZt, batch);
-        if (st != MTNN_OK) return st;
-        st = mtnn_nn(stream, out, in, batch, dZt, batch, H[l], in, d->dW[l], in);
-        if (st != MTNN_OK) return st;
         if (l > 0) {
             // dH_l = dZ x W_l (NN, with the weights before their update), then through the ReLU
             st = mtnn_nn(stream, batch, in, out, dZ, out, d->W[l], in, dNext, in);
             if (st != MTNN_OK) return st;
-            // ... which gives dZ_{l-1}; its column sums are db_{l-1}, taken in the same pass
-            st = mtnn_fc_relu_backward_bias_grad(stream, batch, in, dNext, H[l], d->db[l - 1], bias_part);
+            // ... which gives dZ_{l-1}; its column sums are db_{l-1}, taken in the same pass, and
+            // b_{l-1}, which the backward pass does not read, takes its step there too
+            st = relu_backward_bias_grad_impl(stream, batch, in, dNext, H[l], d->db[l - 1], bias_part, d->b[l - 1], d->lr);
             if (st != MTNN_OK) return st;
         }
-        st = mtnn_fc_sgd(stream, (long long)out * in, d->W[l], d->dW[l], d->lr);
+        // dW_l = dZ^T x H_l : transpose dZ (batch x out -> out x batch), then an NN product whose
+        // epilogue also takes the step of W_l (after the product above has read the old weights)
+        st = mtnn_transpose(stream, batch, out, dZ, out, dZt, batch);
         if (st != MTNN_OK) return st;
-        st = mtnn_fc_sgd(stream, out, d->b[l], d->db[l], d->lr);
+        st = mtnn_fc_weight_grad_sgd(stream, out, in, batch, dZt, batch, H[l], in, d->dW[l], in, d->W[l], in, d->lr);
         if (st != MTNN_OK) return st;
         float* t = dZ; dZ = dNext; dNext = t;
     }

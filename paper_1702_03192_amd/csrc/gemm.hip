@@ -63,7 +63,18 @@ struct GemmParams {
     int k_per_split;  // a multiple of every configuration's k slab
     float* part;
     int sk_units_per_tile;   // gemm_streamk_kernel: k units (of kSplitQuantum) per tile
+    // fused epilogues (read only by the kernel instances built for them)
+    const float* bias;       // kEpiBiasAct: C = act(A x B + bias[column])
+    int relu;
+    float* W;                // kEpiSgd: C = A x B and W -= lr * C (W: M x N, leading dimension ldw)
+    long ldw;
+    float lr;
 };
+
+// what a kernel instance does with its accumulators besides storing them
+constexpr int kEpiNone = 0;
+constexpr int kEpiBiasAct = 1;   // every launch shape; with split-k the reduction kernel applies it
+constexpr int kEpiSgd = 2;       // pipelined NN kernel, unsplit launches only
 
 constexpr int kSplitQuantumDev = 64;   // k ranges of split work are multiples of this (every slab size divides it)
 
@@ -168,9 +179,24 @@ __device__ __forceinline__ void tile_of_block(const GemmParams& p, int pid, int&
 // Register r of lane l of a 32x32 block is row 8*(r/4) + 4*(l/32) + r%4, column l%32: one store
 // instruction writes two full 128-byte row segments.  Results are not read again by the kernel, so
 // the stores are non-temporal; tiles entirely inside C skip the per-element guards.
-template <int TM, int TN>
+// BIAS: each value first takes its column's bias (bv[j] for block j of this lane) and, if relu, the clamp at zero
+template <bool BIAS, int TN>
+__device__ __forceinline__ float with_bias(float v, const float (&bv)[TN], int j, int relu)
+{
+    if (BIAS) {
+        v += bv[j];
+        // (a select, not a branch on `relu`: a branch would be merged across the whole unrolled epilogue
+        // and every addition hoisted above it, with all accumulators live in VGPRs at once)
+        const bool keep = (v > 0.f) | (relu == 0);
+        v = keep ? v : 0.f;
+    }
+    return v;
+}
+
+template <int TM, int TN, bool BIAS = false>
 __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], float* __restrict__ C, long ldc,
-                                           int M, int N, int row0, int col0, int lr, int lh)
+                                           int M, int N, int row0, int col0, int lr, int lh,
+                                           const float (&bv)[TN], int relu)
 {
     if (row0 + TM * 32 <= M && col0 + TN * 32 <= N) {
 #pragma unroll
@@ -179,7 +205,9 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], float* _
             for (int r = 0; r < 16; ++r) {
                 float* dst = C + (size_t)(row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4)) * ldc + col0 + lr;
 #pragma unroll
-                for (int j = 0; j < TN; ++j) __builtin_nontemporal_store(acc[i][j][r], dst + j * 32);
+                for (int j = 0; j < TN; ++j)
+                    __builtin_nontemporal_store(with_bias<BIAS, TN>(acc[i][j][r], bv, j, relu), dst + j * 32);
+                if (BIAS && r % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // (keeps the additions next to their stores)
             }
         return;
     }
@@ -192,7 +220,7 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], float* _
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int row = row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
-                    if (row < M) C[(size_t)row * ldc + col] = acc[i][j][r];
+                    if (row < M) C[(size_t)row * ldc + col] = with_bias<BIAS, TN>(acc[i][j][r], bv, j, relu);
                 }
             }
         }
@@ -203,9 +231,10 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], float* _
 // columns (block j, lane l <-> column TN * (l % 32) + j, see the B fragment reads), so for interior
 // tiles of an aligned C one store per accumulator register writes TN words: lanes 0-31 cover
 // 32 * TN consecutive words of one row.
-template <int TM, int TN>
+template <int TM, int TN, bool BIAS = false>
 __device__ __forceinline__ void store_tile_interleaved(const f32x16 (&acc)[TM][TN], float* __restrict__ C, long ldc,
-                                                       int M, int N, int row0, int col0, int lr, int lh, bool aligned)
+                                                       int M, int N, int row0, int col0, int lr, int lh, bool aligned,
+                                                       const float (&bv)[TN], int relu)
 {
     typedef float vecN __attribute__((ext_vector_type(TN)));
     if (TN > 1 && aligned && row0 + TM * 32 <= M && col0 + TN * 32 <= N) {
@@ -215,9 +244,10 @@ __device__ __forceinline__ void store_tile_interleaved(const f32x16 (&acc)[TM][T
             for (int r = 0; r < 16; ++r) {
                 vecN v;
 #pragma unroll
-                for (int j = 0; j < TN; ++j) v[j] = acc[i][j][r];
+                for (int j = 0; j < TN; ++j) v[j] = with_bias<BIAS, TN>(acc[i][j][r], bv, j, relu);
                 float* dst = C + (size_t)(row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4)) * ldc + col0 + TN * lr;
                 __builtin_nontemporal_store(v, reinterpret_cast<vecN*>(dst));
+                if (BIAS && r % 4 == 3) __builtin_amdgcn_sched_barrier(0);
             }
         return;
     }
@@ -230,7 +260,67 @@ __device__ __forceinline__ void store_tile_interleaved(const f32x16 (&acc)[TM][T
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int col = col0 + TN * lr + j;
-                    if (col < N) C[(size_t)row * ldc + col] = acc[i][j][r];
+                    if (col < N) C[(size_t)row * ldc + col] = with_bias<BIAS, TN>(acc[i][j][r], bv, j, relu);
+                }
+            }
+        }
+}
+
+// store_tile_interleaved plus the plain SGD step on a second matrix of the same shape:
+// G = acc (the gradient, not read again here: non-temporal) and W = fma(-lr, acc, W), the same
+// arithmetic as the separate update kernel, so fusing the step changes no bit of either result.
+template <int TM, int TN>
+__device__ __forceinline__ void store_tile_interleaved_sgd(const f32x16 (&acc)[TM][TN], float* __restrict__ G, long ldg,
+                                                           float* __restrict__ W, long ldw, float lr,
+                                                           int M, int N, int row0, int col0, int lr_, int lh, bool aligned)
+{
+    typedef float vecN __attribute__((ext_vector_type(TN)));
+    if (TN > 1 && aligned && row0 + TM * 32 <= M && col0 + TN * 32 <= N) {
+        // eight rows at a time (their loads of W in flight together), so that the loads of the whole
+        // tile are not all hoisted to the front at the cost of as many registers
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                vecN w[8];
+#pragma unroll
+                for (int rr = 0; rr < 8; ++rr) {
+                    const int r = h * 8 + rr;
+                    const size_t row = (size_t)(row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4));
+                    w[rr] = *reinterpret_cast<const vecN*>(W + row * ldw + col0 + TN * lr_);
+                }
+#pragma unroll
+                for (int rr = 0; rr < 8; ++rr) {
+                    const int r = h * 8 + rr;
+                    const size_t row = (size_t)(row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4));
+                    vecN g;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        g[j] = acc[i][j][r];
+                        w[rr][j] = __builtin_fmaf(-lr, g[j], w[rr][j]);
+                    }
+                    *reinterpret_cast<vecN*>(W + row * ldw + col0 + TN * lr_) = w[rr];
+                    __builtin_nontemporal_store(g, reinterpret_cast<vecN*>(G + row * ldg + col0 + TN * lr_));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4);
+            if (row < M) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int col = col0 + TN * lr_ + j;
+                    if (col < N) {
+                        const float g = acc[i][j][r];
+                        float* wp = W + (size_t)row * ldw + col;
+                        *wp = __builtin_fmaf(-lr, g, *wp);
+                        G[(size_t)row * ldg + col] = g;
+                    }
                 }
             }
         }
@@ -240,9 +330,10 @@ __device__ __forceinline__ void store_tile_interleaved(const f32x16 (&acc)[TM][T
 // wave's sub-tile at a time are written to a wave-private LDS patch (row stride WN + 8 words: the two
 // lane halves, 4 rows apart, land 32 banks apart) and read back as 128-bit row pieces, so every
 // store instruction writes whole 512-byte (WN = 128) row segments, 16 bytes per lane.
-template <int TM, int TN>
+template <int TM, int TN, bool BIAS = false>
 __device__ __forceinline__ void store_tile_staged(const f32x16 (&acc)[TM][TN], float* __restrict__ C, long ldc,
-                                                  int row0, int col0, int lane, float* patch)
+                                                  int row0, int col0, int lane, float* patch,
+                                                  const float (&bv)[TN], int relu)
 {
     constexpr int WN = TN * 32;
     constexpr int S = WN + 8;
@@ -259,7 +350,7 @@ __device__ __forceinline__ void store_tile_staged(const f32x16 (&acc)[TM][TN], f
                 const int r = h * 8 + rr;                                   // rows 16h .. 16h+15 of the block
                 const int prow = (rr / 4) * 8 + lh * 4 + (rr % 4);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) patch[prow * S + j * 32 + lr] = acc[i][j][r];
+                for (int j = 0; j < TN; ++j) patch[prow * S + j * 32 + lr] = with_bias<BIAS, TN>(acc[i][j][r], bv, j, relu);
             }
 #pragma unroll
             for (int t = 0; t < (PIECES + 63) / 64; ++t) {
@@ -272,6 +363,7 @@ __device__ __forceinline__ void store_tile_staged(const f32x16 (&acc)[TM][TN], f
                         v, reinterpret_cast<f32x4*>(C + (size_t)(row0 + i * 32 + h * 16 + prow) * ldc + col0 + c4 * 4));
                 }
             }
+            if (BIAS) __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
@@ -441,7 +533,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_kernel(GemmParams 
     }
 
     // store: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its block
-    store_tile<TM, TN>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh);
+    const float no_bias[TN] = {};
+    store_tile<TM, TN>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh, no_bias, 0);
 }
 
 // ---- the pipelined kernel: global -> LDS by DMA, NSTAGE slabs in flight --------------------------
@@ -505,7 +598,7 @@ __device__ __forceinline__ void lds_barrier()
 // C tile (tm, tn).  The whole workgroup calls it; it leaves no copies in flight, and its last LDS
 // accesses (the epilogue's staging) are this wave's own, so a caller that runs several segments
 // needs one workgroup barrier between them.
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE, int EPI = kEpiNone>
 __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView& w, const int tm, const int tn)
 {
     constexpr int NW = WAVES_M * WAVES_N;
@@ -753,24 +846,42 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
     // epilogue: interior tiles of a 16-byte-aligned C go through wave-private LDS patches (the slab
     // buffers are free once every wave has passed this barrier)
     const bool c_vec = ((reinterpret_cast<uintptr_t>(w.C) & 15) == 0) && ((w.ldc & 3) == 0);
-    if (!NT) {
-        store_tile_interleaved<TM, TN>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh, c_vec);
+    // kEpiBiasAct: the bias of the lane's column of each block (the block -> column mapping of the stores),
+    // added, and the clamp applied, as each value is stored: the same two operations on the same fp32
+    // values as a separate pass over C
+    constexpr bool BIAS = (EPI == kEpiBiasAct);
+    float bv[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        bv[j] = 0.f;
+        if (BIAS) {
+            const int col = NT ? n0 + wn0 + j * 32 + lr : n0 + wn0 + TN * lr + j;
+            if (col < N) bv[j] = p.bias[col];
+        }
+    }
+    const int relu = BIAS ? p.relu : 0;
+    if constexpr (EPI == kEpiSgd) {
+        static_assert(!NT, "the fused update exists for the NN kernel only");
+        const bool w_vec = c_vec && ((reinterpret_cast<uintptr_t>(p.W) & 15) == 0) && ((p.ldw & 3) == 0);
+        store_tile_interleaved_sgd<TM, TN>(acc, w.C, w.ldc, p.W, p.ldw, p.lr, M, N, m0 + wm0, n0 + wn0, lr, lh, w_vec);
+    } else if (!NT) {
+        store_tile_interleaved<TM, TN, BIAS>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh, c_vec, bv, relu);
     } else {
         lds_barrier();
         if (c_vec && m0 + BM <= M && n0 + BN <= N)
-            store_tile_staged<TM, TN>(acc, w.C, w.ldc, m0 + wm0, n0 + wn0, lane, lds + wave * (16 * (WN + 8)));
+            store_tile_staged<TM, TN, BIAS>(acc, w.C, w.ldc, m0 + wm0, n0 + wn0, lane, lds + wave * (16 * (WN + 8)), bv, relu);
         else
-            store_tile<TM, TN>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh);
+            store_tile<TM, TN, BIAS>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh, bv, relu);
     }
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE, int EPI = kEpiNone>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmParams p)
 {
     const WorkView w = work_view(p, NT);
     int tm, tn;
     tile_of_block(p, w.pid, tm, tn);
-    dma_segment<BM, BN, BK, WAVES_M, WAVES_N, NT, NSTAGE>(p, w, tm, tn);
+    dma_segment<BM, BN, BK, WAVES_M, WAVES_N, NT, NSTAGE, EPI>(p, w, tm, tn);
 }
 
 // ---- even split of the whole k x tiles work over a fixed number of workgroups -------------------
@@ -916,8 +1027,11 @@ __global__ __launch_bounds__(256) void streamk_fixup_kernel(GemmParams p, int gr
 // ---- split-k reduction ---------------------------------------------------------------------------
 
 // C[i][j] = part[0][i][j] + part[1][i][j] + ... in split order (fixed, so results are reproducible)
+// EPI = kEpiBiasAct: ... then the column's bias and the clamp, as in the fused epilogue of the kernel
+template <int EPI>
 __global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ part, int splits,
-                                                            int M, int N, float* __restrict__ C, long ldc)
+                                                            int M, int N, float* __restrict__ C, long ldc,
+                                                            const float* __restrict__ bias, int relu)
 {
     const long long total = (long long)M * N;
     for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
@@ -925,7 +1039,12 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restr
         float acc = part[e];
         for (int s = 1; s < splits; ++s) acc += part[(size_t)s * total + e];
         const long long i = e / N;
-        C[(size_t)i * ldc + (e - i * N)] = acc;
+        const long long j = e - i * N;
+        if (EPI == kEpiBiasAct) {
+            acc += bias[j];
+            if (relu) acc = acc > 0.f ? acc : 0.f;
+        }
+        C[(size_t)i * ldc + j] = acc;
     }
 }
 
@@ -936,6 +1055,8 @@ struct Config {
     int bm, bn, bk;
     void (*kern[2][2])(GemmParams);   // guarded kernel, [op][vec]
     void (*dma[2])(GemmParams);       // pipelined kernel, [op]; null if the configuration has none
+    void (*dma_bias[2])(GemmParams);  // pipelined kernel with the bias + activation epilogue, [op]
+    void (*dma_sgd)(GemmParams);      // pipelined NN kernel with the fused SGD step
     void (*sk[2])(GemmParams);        // the same with the work cut evenly over a fixed grid, [op]
     void (*fix)(GemmParams, int);     // ... and its fix-up kernel
     int nstage;
@@ -974,6 +1095,17 @@ struct Config {
     }
 };
 
+// The pipelined kernel with a fused epilogue, or null for the 16-wide-slab configuration: there the
+// epilogue's arithmetic makes the compiler move all 128 accumulators from AGPRs to VGPRs in one block
+// at the loop exit, and the registers that takes no longer allow the two workgroups per CU the
+// configuration is rated for (its launches run the plain kernel and the separate pass instead).
+template <int BM, int BN, int BK, int WMV, int WNV, bool NT, int NS, int EPI>
+constexpr void (*epilogue_kernel())(GemmParams)
+{
+    if constexpr (BK == 16) return nullptr;
+    else return &gemm_dma_kernel<BM, BN, BK, WMV, WNV, NT, NS, EPI>;
+}
+
 #define MTNN_GUARDED(BM, BN, BK, WMV, WNV)                                                    \
     {{gemm_kernel<BM, BN, BK, WMV, WNV, false, false>, gemm_kernel<BM, BN, BK, WMV, WNV, false, true>},   \
      {gemm_kernel<BM, BN, BK, WMV, WNV, true, false>, gemm_kernel<BM, BN, BK, WMV, WNV, true, true>}}
@@ -982,6 +1114,8 @@ struct Config {
 #define MTNN_CFG_DMA(BM, BN, BK, WMV, WNV, NS, GBK, MAXWG, EFF_NN, RND_NN, EFF_NT, RND_NT, GEFF_NN, GRND_NN, GEFF_NT, GRND_NT)                                    \
     { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV "_dma" #NS "_x" #MAXWG, BM, BN, BK, MTNN_GUARDED(BM, BN, GBK, WMV, WNV), \
       {gemm_dma_kernel<BM, BN, BK, WMV, WNV, false, NS>, gemm_dma_kernel<BM, BN, BK, WMV, WNV, true, NS>}, \
+      {epilogue_kernel<BM, BN, BK, WMV, WNV, false, NS, kEpiBiasAct>(), epilogue_kernel<BM, BN, BK, WMV, WNV, true, NS, kEpiBiasAct>()}, \
+      epilogue_kernel<BM, BN, BK, WMV, WNV, false, NS, kEpiSgd>(), \
       {gemm_streamk_kernel<BM, BN, BK, WMV, WNV, false, NS>, gemm_streamk_kernel<BM, BN, BK, WMV, WNV, true, NS>}, \
       streamk_fixup_kernel<BM, BN>, \
       NS, WMV * WNV * 64, WNV, {EFF_NN, EFF_NT}, {RND_NN, RND_NT}, {GEFF_NN, GEFF_NT}, {GRND_NN, GRND_NT}, MAXWG }
@@ -1011,6 +1145,8 @@ constexpr int kSplitQuantum = kSplitQuantumDev;
 
 static std::atomic<long long> g_streamk_launches{0};
 long long gemm_streamk_launches() { return g_streamk_launches.load(); }
+static std::atomic<long long> g_fused_launches{0};
+long long gemm_fused_launches() { return g_fused_launches.load(); }
 
 int gemm_config_count() { return kNumConfigs; }
 const char* gemm_config_name(int cfg) { return (cfg >= 0 && cfg < kNumConfigs) ? kConfigs[cfg].name : nullptr; }
@@ -1143,9 +1279,13 @@ int gemm_default_config(int op, int m, int n, int k) { return choose(op, m, n, k
 int gemm_default_splits(int op, int m, int n, int k) { return choose(op, m, n, k, true).splits; }
 
 int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
-                const float* A, long lda, const float* B, long ldb, float* C, long ldc)
+                const float* A, long lda, const float* B, long ldb, float* C, long ldc,
+                const Epilogue* epi, bool* fused)
 {
+    if (fused) *fused = false;
     if (op != OP_NN && op != OP_NT) return (int)hipErrorInvalidValue;
+    const int kind = epi ? epi->kind : kEpiNone;
+    if (kind != kEpiNone && kind != kEpiBiasAct && kind != kEpiSgd) return (int)hipErrorInvalidValue;
     // splits: >= 1 as given; kStreamK the even cut; any other value <= 0 leaves the choice to the rule
     const bool free_splits = (splits <= 0 && splits != kStreamK);
     const bool chunks16 = (lda % 4 == 0) && (ldb % 4 == 0) && (k % 4 == 0) && (op == OP_NT || n % 4 == 0) &&
@@ -1174,6 +1314,11 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
     p.k_per_split = k;
     p.part = nullptr;
     p.sk_units_per_tile = 0;
+    p.bias = (kind == kEpiBiasAct) ? epi->bias : nullptr;
+    p.relu = (kind == kEpiBiasAct) ? epi->relu : 0;
+    p.W = (kind == kEpiSgd) ? epi->W : nullptr;
+    p.ldw = (kind == kEpiSgd) ? epi->ldw : 0;
+    p.lr = (kind == kEpiSgd) ? epi->lr : 0.f;
     if (splits > 1) {
         int kps = (k + splits - 1) / splits;
         kps = ((kps + kSplitQuantum - 1) / kSplitQuantum) * kSplitQuantum;
@@ -1230,7 +1375,13 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
             return (int)hipGetLastError();
         }
     }
-    auto kern = dma_ok ? c.dma[op] : c.kern[op][vec ? 1 : 0];
+    // A fused epilogue runs in the pipelined kernel's instance built for it (unsplit launches), or, for
+    // the bias + activation, in the reduction kernel of a split launch; anything else is left to the caller.
+    const bool fuse_reduce = (kind == kEpiBiasAct) && p.splits > 1;
+    const bool fuse_main = p.splits == 1 && dma_ok &&
+                           ((kind == kEpiBiasAct && c.dma_bias[op]) || (kind == kEpiSgd && op == OP_NN && c.dma_sgd));
+    auto kern = fuse_main ? (kind == kEpiBiasAct ? c.dma_bias[op] : c.dma_sgd)
+                          : dma_ok ? c.dma[op] : c.kern[op][vec ? 1 : 0];
     Config guarded = c;
     guarded.bk = 16;
     size_t lds = dma_ok ? c.lds_bytes_dma() : guarded.lds_bytes(op);
@@ -1249,8 +1400,8 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
     }
     if (lds > 64 * 1024) {
         // opt in to the large LDS carve-out once per kernel and device
-        static std::atomic<bool> raised[kNumConfigs][2][3][16] = {};   // (racing callers at worst set the attribute twice)
-        const int which = dma_ok ? 2 : (vec ? 1 : 0);
+        static std::atomic<bool> raised[kNumConfigs][2][5][16] = {};   // (racing callers at worst set the attribute twice)
+        const int which = fuse_main ? 2 + kind : dma_ok ? 2 : (vec ? 1 : 0);
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess) return (int)hipGetLastError();
         if (dev < 0 || dev >= 16 || !raised[cfg][op][which][dev]) {
@@ -1268,9 +1419,17 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
         const long long elems = (long long)m * n;
         long long blocks = (elems + 255) / 256;
         if (blocks > 2048) blocks = 2048;
-        hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
-                           p.part, p.splits, m, n, C, ldc);
+        if (fuse_reduce)
+            hipLaunchKernelGGL(reduce_splits_kernel<kEpiBiasAct>, dim3((unsigned)blocks), dim3(256), 0, s,
+                               p.part, p.splits, m, n, C, ldc, p.bias, p.relu);
+        else
+            hipLaunchKernelGGL(reduce_splits_kernel<kEpiNone>, dim3((unsigned)blocks), dim3(256), 0, s,
+                               p.part, p.splits, m, n, C, ldc, nullptr, 0);
         err = hipGetLastError();
+    }
+    if (err == hipSuccess && (fuse_main || fuse_reduce)) {
+        ++g_fused_launches;
+        if (fused) *fused = true;
     }
     return (int)err;
 }

@@ -94,6 +94,29 @@ def test_gemm_ex_arguments(L):
     assert mt.mtnn_gemm_default_config(0, 0, 4, 4) == -1
 
 
+def test_fused_layer_calls_validation(L):
+    Bias, W2 = 0x500000, 0x600000
+    fwd = L.mtnn_fc_layer_forward
+    ok_args = (4, 6, 8, A, 8, B, 8, Bias, 1, C, 6, W, 1 << 20, None)
+    assert fwd(None, 2, *ok_args) == 8                                   # mode not in {-1, 0, +1}
+    assert fwd(None, 1, 4, 6, 8, A, 8, B, 8, Bias, 2, C, 6, W, 1 << 20, None) == 8     # relu not 0 / 1
+    assert fwd(None, 1, 4, 6, 8, A, 7, B, 8, Bias, 1, C, 6, W, 1 << 20, None) == 3     # ldx < k
+    assert fwd(None, 1, 4, 6, 8, A, 8, B, 8, None, 1, C, 6, W, 1 << 20, None) == 2     # no bias
+    assert fwd(None, 1, 4, 6, 8, A, 8, B, 8, C + 8, 1, C, 6, W, 1 << 20, None) == 4    # bias inside Y
+    assert fwd(None, -1, 4, 6, 8, A, 8, B, 8, Bias, 1, C, 6, None, 0, None) == 5       # TNN without its workspace
+    chosen = ctypes.c_int(0)
+    assert fwd(None, 0, 0, 6, 8, None, 8, None, 8, None, 1, None, 6, None, 0, ctypes.byref(chosen)) == 0
+    assert chosen.value == 1                                             # empty product: nothing to select
+    upd = L.mtnn_fc_weight_grad_sgd
+    assert upd(None, 4, 6, 8, A, 8, B, 5, C, 6, W2, 6, 0.1) == 3          # NN: ldb < n
+    assert upd(None, 4, 6, 8, A, 8, B, 6, C, 6, None, 6, 0.1) == 2        # no W
+    assert upd(None, 4, 6, 8, A, 8, B, 6, C, 6, W2, 5, 0.1) == 3          # ldw < n
+    assert upd(None, 4, 6, 8, A, 8, B, 6, C, 6, C + 16, 6, 0.1) == 4      # W overlaps dW
+    assert upd(None, 4, 6, 8, A, 8, B, 6, C, 6, A, 6, 0.1) == 4           # W is A
+    assert upd(None, 0, 6, 8, None, 8, None, 6, None, 6, None, 6, 0.1) == 0
+    assert L.mtnn_gemm_fused_epilogue_launches() >= 0
+
+
 def test_transpose_validation_codes(L):
     assert L.mtnn_transpose(None, -1, 4, A, 4, B, 4) == 1
     assert L.mtnn_transpose(None, 4, 6, None, 6, B, 4) == 2

@@ -226,3 +226,148 @@ def test_forward_only_entry_matches_the_step_and_leaves_the_weights():
     assert logits.cpu().numpy().tobytes() == full["logits"].tobytes()
     for l in range(3):
         assert dW_[l].cpu().numpy().tobytes() == W[l].tobytes()
+
+
+# ---- the two products with their elementwise step in the epilogue ---------------------------------
+
+def rule_allows_fusing(op, m, n, k, split_ok):
+    """Whether the launch the cost model picks for an aligned (op, m, n, k) has a fused epilogue: not the
+    16-wide-slab configuration (no fused instances), not the even cut, and for the update no split-k."""
+    name = mt.gemm_configs()[mt.mtnn_gemm_default_config(op, m, n, k)]
+    splits = mt.mtnn_gemm_default_splits(op, m, n, k)
+    return "x16_" not in name and splits != mt.EVEN_CUT and (split_ok or splits == 1)
+
+
+# (m, n, k, ldx pad, ldw pad, ldy pad, operands fit the pipelined kernel)
+FORWARD_CASES = [
+    (128, 2048, 784, 0, 0, 0, True),       # a Table IX layer at mini-batch 128: pipelined kernel
+    (1024, 4096, 4096, 0, 0, 0, True),     # a config-2 shape
+    (200, 328, 1000, 0, 0, 0, True),       # ragged tiles, operands still in 16-byte chunks
+    (256, 512, 260, 4, 8, 4, True),        # padded leading dimensions (multiples of 4)
+    (64, 128, 8192, 0, 0, 0, True),        # split-k: the reduction kernel carries the epilogue
+    (100, 37, 51, 0, 0, 0, False),         # nothing aligned: guarded kernel + separate pass
+    (96, 130, 64, 0, 0, 3, True),          # n % 4 != 0 with a padded Y: word-wise stores (NT); not for the NN product of TNN
+    (5, 7, 0, 0, 0, 0, False),             # k = 0: Y = act(b) in every row
+]
+
+
+@pytest.mark.parametrize("mode", [1, -1], ids=["nt", "tnn"])
+@pytest.mark.parametrize("relu", [True, False], ids=["relu", "linear"])
+@pytest.mark.parametrize("case", FORWARD_CASES, ids=lambda c: "x".join(map(str, c[:3])))
+def test_layer_forward_is_the_product_then_bias_then_clamp(case, relu, mode):
+    """mtnn_fc_layer_forward against (a) the library's own separate calls, bit for bit, and (b) the fp64
+    oracle product with the bias and clamp applied in float64, to the product's tolerance."""
+    import torch
+    from oracle import gemm as og
+    from tests.gpu_util import Guarded, dev_matrix, tol
+    m, n, k, px, pw, py, expect_fused = case
+    seed = 500 + m + n + k
+    A = I.uniform_pm1(seed, 0, m, max(k, 1))[:, :k]
+    B = I.uniform_pm1(seed, 1, n, max(k, 1))[:, :k]
+    b = (I.uniform_pm1(seed, 2, 1, n)[0] * np.float32(0.5 * np.sqrt(max(k, 1)))).astype(np.float32)
+    dA = dev_matrix(np.ascontiguousarray(A), max(k + px, 1))
+    dB = dev_matrix(np.ascontiguousarray(B), max(k + pw, 1))
+    db = torch.from_numpy(b).cuda()
+    ws = torch.empty(max(mt.mtnn_tnn_workspace_bytes(n, k), 256), dtype=torch.uint8, device="cuda")
+    plain = Guarded(m, n, n + py)
+    (mt.mtnn_nt if mode == 1 else lambda a_, b_, c_: mt.mtnn_tnn(a_, b_, c_, ws))(dA, dB, plain.view)
+    want_bits = plain.view + db
+    if relu:
+        want_bits = torch.where(want_bits > 0, want_bits, torch.zeros_like(want_bits))
+    out = Guarded(m, n, n + py)
+    before = mt.mtnn_gemm_fused_epilogue_launches()
+    chosen = mt.mtnn_fc_layer_forward(dA, dB, db, out.view, relu, mode, ws)
+    torch.cuda.synchronize()
+    assert chosen == mode
+    if k > 0:
+        # (the NN product of TNN also needs n in 16-byte chunks)
+        fits = expect_fused and (mode == 1 or n % 4 == 0)
+        want_fused = fits and rule_allows_fusing(mt.OP_NT if mode == 1 else mt.OP_NN, m, n, k, True)
+        assert (mt.mtnn_gemm_fused_epilogue_launches() == before + 1) == want_fused
+    else:
+        assert mt.mtnn_gemm_fused_epilogue_launches() == before
+    Y, intact = out.host()
+    assert intact, "wrote outside Y"
+    assert np.array_equal(Y.view(np.uint32), want_bits.cpu().numpy().view(np.uint32)), "differs from the separate calls"
+    if k > 0:
+        C_ref, S_ref = og.nt_ref(A, B, with_bound=True)
+        z = C_ref + b.astype(np.float64)
+        want = np.maximum(z, 0.0) if relu else z
+        # the clamp is 1-Lipschitz, so the product's componentwise bound carries over (plus one rounding of the sum)
+        err = np.abs(Y.astype(np.float64) - want)
+        bound = tol(k) * S_ref + 2.0 ** -23 * np.abs(z)
+        assert (err <= bound).all(), f"max excess {(err - bound).max():.3g}"
+
+
+def test_layer_forward_auto_mode_reports_the_selected_path():
+    import torch
+    m, n, k = 256, 512, 256
+    A = torch.from_numpy(I.uniform_pm1(71, 0, m, k)).cuda()
+    B = torch.from_numpy(I.uniform_pm1(71, 1, n, k)).cuda()
+    b = torch.from_numpy(I.uniform_pm1(71, 2, 1, n)[0]).cuda()
+    Y = torch.empty((m, n), device="cuda")
+    ws = torch.empty(mt.mtnn_tnn_workspace_bytes(n, k), dtype=torch.uint8, device="cuda")
+    assert mt.mtnn_fc_layer_forward(A, B, b, Y, True, 0, ws) == mt.mtnn_select(m, n, k)
+    assert mt.mtnn_fc_layer_forward(A, B, b, Y, True, 0, None) == 1       # no room for B^T: NT (Section II)
+
+
+# (m, n, k, lda pad, ldb pad, lddw pad, ldw pad, expect the fused path)
+UPDATE_CASES = [
+    (2048, 784, 128, 0, 0, 0, 0, True),     # dW of a Table IX layer at mini-batch 128
+    (1024, 2048, 4096, 0, 0, 0, 0, True),   # ... at mini-batch 4096
+    (200, 328, 260, 0, 0, 0, 0, True),      # ragged tiles
+    (256, 512, 64, 4, 4, 8, 4, True),       # padded leading dimensions
+    (10, 1024, 4096, 0, 0, 0, 0, True),     # small m n, long k: fused only if the rule does not split it
+    (100, 37, 51, 0, 0, 0, 0, False),       # unaligned: separate pass
+    (64, 128, 96, 0, 0, 0, 3, None),        # W rows not 16-byte aligned: fused kernel, word-wise update
+]
+
+
+@pytest.mark.parametrize("case", UPDATE_CASES, ids=lambda c: "x".join(map(str, c[:3])))
+def test_weight_grad_sgd_is_the_product_then_the_update(case):
+    """mtnn_fc_weight_grad_sgd against mtnn_nn followed by mtnn_fc_sgd, bit for bit, and against the fp64
+    oracle (dW to the product's tolerance; W to that times lr plus one rounding)."""
+    import torch
+    from oracle import gemm as og
+    from tests.gpu_util import Guarded, dev_matrix, tol
+    m, n, k, pa, pb, pg, pw, expect_fused = case
+    lr = np.float32(0.05)
+    seed = 900 + m + n + k
+    A = I.uniform_pm1(seed, 0, m, k)
+    B = I.uniform_pm1(seed, 1, k, n)
+    W0 = I.uniform_pm1(seed, 2, m, n)
+    dA, dB = dev_matrix(A, k + pa), dev_matrix(B, n + pb)
+    # reference: the separate calls (dense W, as mtnn_fc_sgd wants it)
+    g_ref = torch.empty((m, n), device="cuda")
+    w_ref = torch.from_numpy(W0.copy()).cuda()
+    mt.mtnn_nn(dA, dB, g_ref)
+    mt.mtnn_fc_sgd(w_ref, g_ref, float(lr))
+    g = Guarded(m, n, n + pg)
+    w = Guarded(m, n, n + pw)
+    w.view.copy_(torch.from_numpy(W0).cuda())
+    before = mt.mtnn_gemm_fused_epilogue_launches()
+    mt.mtnn_fc_weight_grad_sgd(dA, dB, g.view, w.view, float(lr))
+    torch.cuda.synchronize()
+    if expect_fused is not None:
+        want_fused = expect_fused and rule_allows_fusing(mt.OP_NN, m, n, k, False)
+        assert (mt.mtnn_gemm_fused_epilogue_launches() == before + 1) == want_fused
+    G, ok_g = g.host()
+    Wn, ok_w = w.host()
+    assert ok_g and ok_w, "wrote outside dW or W"
+    assert np.array_equal(G.view(np.uint32), g_ref.cpu().numpy().view(np.uint32)), "dW differs from mtnn_nn"
+    assert np.array_equal(Wn.view(np.uint32), w_ref.cpu().numpy().view(np.uint32)), "W differs from the separate update"
+    C_ref, S_ref = og.nn_ref(A, B, with_bound=True)
+    assert (np.abs(G.astype(np.float64) - C_ref) <= tol(k) * S_ref).all()
+    want_w = W0.astype(np.float64) - float(lr) * C_ref
+    bound = float(lr) * tol(k) * S_ref + 2.0 ** -23 * np.abs(want_w) + 1e-30
+    assert (np.abs(Wn.astype(np.float64) - want_w) <= bound).all()
+
+
+def test_step_uses_the_fused_epilogues():
+    """A step of an aligned net runs every forward product and every weight gradient with its epilogue fused."""
+    dims, batch = [784, 2048, 1024, 10], 128
+    X, labels, W, b = make_net(dims, batch, 31)
+    before = mt.mtnn_gemm_fused_epilogue_launches()
+    run_step(dims, batch, X, labels, W, b, 0.01, 1)
+    # 3 forward products; of the 3 weight gradients the 10 x 1024 one may be split over k (then it updates separately)
+    assert mt.mtnn_gemm_fused_epilogue_launches() - before >= 5
