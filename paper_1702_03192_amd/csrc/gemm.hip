@@ -1123,9 +1123,10 @@ constexpr void (*epilogue_kernel())(GemmParams)
 static const Config kConfigs[] = {
     //           tile         waves stages    per CU   NN: eff, round      NT: eff, round       guarded kernel: NN, NT
     MTNN_CFG_DMA(256, 256, 32, 4, 2, 2, 16,   1,   0.949f, 13.8e-6f,   0.943f, 13.3e-6f,   0.871f, 12.7e-6f, 0.842f, 11.5e-6f),  // 0: 8 waves of 64 x 128, 128 KB of LDS
-    // (1: the NN fit puts it level with configuration 0 inside the grid; beyond it the narrower tile
-    //  re-reads more of A and falls behind -- 135 against 148 TFLOP/s at 65536^3 -- so it is rated just below)
-    MTNN_CFG_DMA(256, 128, 16, 2, 2, 3, 16,   2,   0.943f, 11.9e-6f,   0.944f, 12.8e-6f,   0.840f, 9.8e-6f, 0.848f, 10.6e-6f),  // 1: 4 waves of 128 x 64, 72 KB
+    // (1: the fits put it level with configuration 0 inside the grid; beyond it the narrower tile
+    //  re-reads more of A and falls behind -- NN 135 against 148 TFLOP/s at 65536^3, NT 139 against 148 at
+    //  65536 x 256 x 32768 and 146 against 149 at 16384^3 -- so both operations rate it just below)
+    MTNN_CFG_DMA(256, 128, 16, 2, 2, 3, 16,   2,   0.943f, 11.9e-6f,   0.937f, 12.8e-6f,   0.840f, 9.8e-6f, 0.848f, 10.6e-6f),  // 1: 4 waves of 128 x 64, 72 KB
     MTNN_CFG_DMA(128, 128, 64, 4, 2, 2, 16,   1,   0.884f, 4.0e-6f,   0.886f, 3.7e-6f,   0.802f, 2.1e-6f, 0.776f, 2.0e-6f),   // 2: 8 waves of 32 x 64, 128 KB
     MTNN_CFG_DMA(64, 64, 64, 2, 2, 2, 16,     2,   0.886f, 2.9e-6f,   0.865f, 2.2e-6f,   0.688f, 1.1e-6f, 0.680f, 1.1e-6f),   // 3: 4 waves of 32 x 32, 64 KB
     MTNN_CFG_DMA(32, 256, 32, 1, 4, 2, 16,    2,   0.903f, 2.9e-6f,   0.892f, 3.0e-6f,   0.698f, 1.7e-6f, 0.621f, 2.0e-6f),   // 4: 4 waves of 32 x 64 (small m), 72 KB

@@ -1,6 +1,7 @@
 """The paper's fully connected networks as a shape workload (Section V-C, Tables IX and X).  Needs the GPU.
 
   python -m paper_1702_03192_amd.fcnet --out <dir>/fcnet_report.json [--md <dir>/fcnet_report.md]
+  python -m paper_1702_03192_amd.fcnet --profile-steps 20        (config 5's step N times, for a kernel profiler)
 
 Table IX: two families -- "MNIST" (784 inputs, 10 outputs, hidden 2048-1024 / 2048-2048-1024 /
 2048-2048-2048-1024) and "synthetic" (26752 inputs and outputs, hidden 4096 x 2 / 3 / 4) -- each
@@ -28,10 +29,47 @@ BATCHES = [128, 256, 512, 1024, 2048, 4096]
 MODES = ((1, "nt"), (0, "mtnn"), (-1, "tnn"))
 
 
+def profile_config5(steps):
+    """Config 5's training step (784-4096-4096-4096-10, mini-batch 1024, selector-chosen forward path),
+    `steps` times back to back: the workload of the per-kernel profile of the FC step."""
+    import torch
+    from . import binding as mt
+    from . import inputs
+    cfg = inputs.CONFIG5
+    dims, batch = cfg["dims"], cfg["batch"]
+    L = len(dims) - 1
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(cfg["seed"])
+    X = torch.randn((batch, dims[0]), generator=gen, device="cuda")
+    labels = torch.randint(0, dims[-1], (batch,), generator=gen, device="cuda", dtype=torch.int32)
+    W = [torch.from_numpy(inputs.xavier_uniform(cfg["seed"] + 1 + l, 2, dims[l + 1], dims[l])).cuda() for l in range(L)]
+    b = [torch.zeros(dims[l + 1], device="cuda") for l in range(L)]
+    gW = [torch.empty_like(w) for w in W]
+    gb = [torch.empty_like(v) for v in b]
+    loss = torch.empty(1, device="cuda")
+    ws = torch.empty(mt.mtnn_fc_workspace_bytes(dims, batch), dtype=torch.uint8, device="cuda")
+    desc, keep = mt.make_fc_desc(dims, batch, X, labels, W, b, gW, gb, loss, ws, 0.0, 0)
+    for _ in range(3):
+        mt.mtnn_fc_train_step(desc)
+    torch.cuda.synchronize()
+    a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        mt.mtnn_fc_train_step(desc)
+    e.record()
+    torch.cuda.synchronize()
+    flops = sum(2.0 * batch * dims[l] * dims[l + 1] * (3 if l > 0 else 2) for l in range(L))
+    ms = a.elapsed_time(e) / steps
+    print(f"[fcnet] config 5 step x {steps}: {ms:.3f} ms per step, {flops / ms / 1e9:.1f} TFLOP/s of GEMM work", flush=True)
+    return 0
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("--out", required=True)
+    ap.add_argument("--out", default=None)
     ap.add_argument("--md", default=None)
+    ap.add_argument("--profile-steps", type=int, default=0,
+                    help="run only this many training steps of the config-5 net (after 3 warm-ups) and exit")
     ap.add_argument("--samples", type=int, default=10)
     ap.add_argument("--batches", type=int, nargs="*", default=BATCHES)
     args = ap.parse_args(argv)
@@ -43,6 +81,10 @@ def main(argv=None):
 
     torch.cuda.set_device(0)
     mt.lib()
+    if args.profile_steps > 0:
+        return profile_config5(args.profile_steps)
+    if not args.out:
+        ap.error("--out is required")
     stream = torch.cuda.current_stream()
     side = torch.cuda.Stream()                                 # capture stream of the graph timings
     gen = torch.Generator(device="cuda")
