@@ -183,6 +183,10 @@ MTNN_API long long mtnn_gemm_even_cut_launches(void);
 /* How many products of this process ran with a fused epilogue (mtnn_fc_layer_forward,
  * mtnn_fc_weight_grad_sgd) rather than with the separate pass (diagnostics, tests). */
 MTNN_API long long mtnn_gemm_fused_epilogue_launches(void);
+/* enable = 0: mtnn_fc_layer_forward / mtnn_fc_weight_grad_sgd (and the training step built on them)
+ * run the plain product followed by the separate pass everywhere, for before / after measurements in
+ * one process; 1 (the default): fuse where possible.  Returns the previous setting.  Process-wide. */
+MTNN_API int mtnn_set_fused_epilogues(int enable);
 
 /* ---- one training step of a fully connected net (Section V-C, Table IX sizes) ---------------- */
 

@@ -90,6 +90,7 @@ SIGNATURES = {
     "mtnn_version": (_c_int, []),
     "mtnn_gemm_even_cut_launches": (ctypes.c_longlong, []),
     "mtnn_gemm_fused_epilogue_launches": (ctypes.c_longlong, []),
+    "mtnn_set_fused_epilogues": (_c_int, [_c_int]),
     "mtnn_device_attribute": (_c_int, [_c_int]),
 }
 
@@ -440,6 +441,11 @@ def mtnn_gemm_even_cut_launches() -> int:
 
 def mtnn_gemm_fused_epilogue_launches() -> int:
     return int(lib().mtnn_gemm_fused_epilogue_launches())
+
+
+def mtnn_set_fused_epilogues(enable: bool) -> bool:
+    """Process-wide switch for measurements: False = separate bias / ReLU / SGD passes.  Returns the old setting."""
+    return bool(lib().mtnn_set_fused_epilogues(1 if enable else 0))
 
 
 def mtnn_device_attribute(what: int) -> int:

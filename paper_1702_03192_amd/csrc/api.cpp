@@ -13,6 +13,7 @@
 namespace {
 
 std::atomic<int> g_last_hip_error{0};   // last non-zero HIP error a launcher reported (diagnostics only)
+std::atomic<int> g_fuse_epilogues{1};   // mtnn_set_fused_epilogues: 0 = always the separate pass (measurements)
 
 int launch_status(int err)
 {
@@ -69,7 +70,8 @@ int run_gemm(void* stream, int op, int cfg, int splits, int m, int n, int k, con
     int err;
     bool fused = false;
     if (k == 0) err = mtnn::launch_fill_zero(s, m, n, C, ldc);
-    else err = mtnn::launch_gemm(s, op, cfg, splits, m, n, k, A, lda, B, ldb, C, ldc, epi, &fused);
+    else err = mtnn::launch_gemm(s, op, cfg, splits, m, n, k, A, lda, B, ldb, C, ldc,
+                                 g_fuse_epilogues.load() ? epi : nullptr, &fused);
     if (err == 0 && epi && !fused) {
         if (epi->kind == 1) err = mtnn::launch_bias_act(s, m, n, C, ldc, epi->bias, epi->relu);
         else err = mtnn::launch_sgd_2d(s, m, n, epi->W, epi->ldw, C, ldc, epi->lr);
@@ -284,6 +286,7 @@ int mtnn_version(void) { return 100; }
 
 long long mtnn_gemm_even_cut_launches(void) { return mtnn::gemm_streamk_launches(); }
 long long mtnn_gemm_fused_epilogue_launches(void) { return mtnn::gemm_fused_launches(); }
+int mtnn_set_fused_epilogues(int enable) { return g_fuse_epilogues.exchange(enable ? 1 : 0); }
 
 int mtnn_device_attribute(int what)
 {

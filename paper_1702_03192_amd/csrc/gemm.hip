@@ -1246,11 +1246,16 @@ static double predicted_seconds_even_cut(const Config& c, int op, int m, int n, 
 
 // pipelined: the operands allow the pipelined kernel; otherwise the guarded kernel's own rates are
 // used (and the even cut, which exists only in the pipelined kernel, is not considered)
-static Choice choose(int op, int m, int n, int k, bool allow_split, bool pipelined = true)
+// epi_kind: the launch wants that epilogue fused.  A candidate that cannot fuse it (a configuration
+// without the fused instance, the even cut, a split weight gradient) is charged the separate pass over
+// C it would need: one more launch and two (bias, clamp) or three (update) trips of m x n words.
+static Choice choose(int op, int m, int n, int k, bool allow_split, bool pipelined = true, int epi_kind = kEpiNone)
 {
     Choice best = {0, 1};
     double best_t = 1e30;
     const int o = (op == OP_NT) ? 1 : 0;
+    const bool epi = pipelined && epi_kind != kEpiNone;
+    const double pass_s = epi ? 4.5e-6 + (epi_kind == kEpiBiasAct ? 2.0 : 3.0) * (double)m * (double)n * 4.0 / 4.0e12 : 0.0;
     for (int c = 0; c < kNumConfigs; ++c) {
         for (int splits = 1; splits <= kMaxSplits; splits *= 2) {
             if (splits > 1) {
@@ -1258,7 +1263,12 @@ static Choice choose(int op, int m, int n, int k, bool allow_split, bool pipelin
                 if ((size_t)m * n * splits * sizeof(float) > kScratchBytes) break;
                 if (k / splits < 2 * kSplitQuantum) break;
             }
-            const double t = predicted_seconds(kConfigs[c], o, m, n, k, splits, pipelined);
+            double t = predicted_seconds(kConfigs[c], o, m, n, k, splits, pipelined);
+            if (epi) {
+                const bool fuses = (epi_kind == kEpiBiasAct) ? (splits > 1 || kConfigs[c].dma_bias[o] != nullptr)
+                                                             : (splits == 1 && o == 0 && kConfigs[c].dma_sgd != nullptr);
+                if (!fuses) t += pass_s;
+            }
             if (t < best_t * 0.999) { best_t = t; best = Choice{c, splits}; }
         }
     }
@@ -1269,7 +1279,7 @@ static Choice choose(int op, int m, int n, int k, bool allow_split, bool pipelin
         // rule took it on 13, once wrongly (5 % slower)
         double sk_t = best_t * 0.95;
         for (int c = 9; c <= 10; ++c) {
-            const double t = predicted_seconds_even_cut(kConfigs[c], o, m, n, k);
+            const double t = predicted_seconds_even_cut(kConfigs[c], o, m, n, k) + pass_s;
             if (t < sk_t) { sk_t = t; best = Choice{c, kStreamK}; }
         }
     }
@@ -1292,7 +1302,7 @@ int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
     const bool chunks16 = (lda % 4 == 0) && (ldb % 4 == 0) && (k % 4 == 0) && (op == OP_NT || n % 4 == 0) &&
                           ((reinterpret_cast<uintptr_t>(A) & 15) == 0) && ((reinterpret_cast<uintptr_t>(B) & 15) == 0);
     if (cfg < 0) {
-        const Choice ch = choose(op, m, n, k, free_splits, chunks16);
+        const Choice ch = choose(op, m, n, k, free_splits, chunks16, kind);
         cfg = ch.cfg;
         if (free_splits) splits = ch.splits;
     } else if (free_splits) {

@@ -120,6 +120,13 @@ def main(argv=None):
                                  "forward_tflops": fwd_flop / t_f / 1e12,
                                  "total_tflops": (fwd_flop + bwd_flop) / t_s / 1e12}
                     if name == "mtnn":
+                        # the same step with the bias / ReLU / SGD passes as kernels of their own
+                        mt.mtnn_set_fused_epilogues(False)
+                        try:
+                            t_u, _ = _time_batches(lambda: mt.mtnn_fc_train_step(desc), stream, args.samples, 2000.0)
+                        finally:
+                            mt.mtnn_set_fused_epilogues(True)
+                        rec[name]["total_separate_passes_ms"] = t_u * 1e3
                         # the same step captured once into a HIP graph and replayed: what the launch path costs
                         # (lr is 0 here, so replays leave the weights alone)
                         with torch.cuda.stream(side):          # one-time set-up of this stream (split-k scratch)
@@ -159,12 +166,12 @@ def main(argv=None):
                     s = summary[family][phase]
                     f.write(f"| {family} | {phase[:-3]} | {s['nt']:.3f} | {s['mtnn']:.3f} | {s['tnn']:.3f} | "
                             f"{s['speedup_mtnn_over_nt']:.2f} |\n")
-            f.write("\n| family | hidden | batch | fwd NT ms | fwd MTNN ms | fwd TNN ms | step MTNN ms | step from a HIP graph ms | step TFLOP/s | labels |\n")
-            f.write("|---|---|---|---|---|---|---|---|---|---|\n")
+            f.write("\n| family | hidden | batch | fwd NT ms | fwd MTNN ms | fwd TNN ms | step MTNN ms | step from a HIP graph ms | step with separate passes ms | step TFLOP/s | labels |\n")
+            f.write("|---|---|---|---|---|---|---|---|---|---|---|\n")
             for r in rows:
                 f.write(f"| {r['family']} | {'-'.join(map(str, r['hidden']))} | {r['batch']} | {r['nt']['forward_ms']:.3f} | "
                         f"{r['mtnn']['forward_ms']:.3f} | {r['tnn']['forward_ms']:.3f} | {r['mtnn']['total_ms']:.3f} | "
-                        f"{r['mtnn']['total_graph_ms']:.3f} | "
+                        f"{r['mtnn']['total_graph_ms']:.3f} | {r['mtnn']['total_separate_passes_ms']:.3f} | "
                         f"{r['mtnn']['total_tflops']:.1f} | {r['labels']} |\n")
     return 0
 

@@ -60,6 +60,16 @@ def main(argv=None):
         A, B = operands(m, n, k, seed, dist)
         C = torch.empty((m, n), device="cuda")
         ws = torch.empty(mt.mtnn_tnn_workspace_bytes(n, k), dtype=torch.uint8, device="cuda")
+        # about 50 ms of this shape first: after a tiny shape the clocks are low, and the first path timed
+        # would pay for that (NT read 4 % low on the first big shape of the list)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        mt.mtnn_nt(A, B, C)
+        b.record(stream)
+        b.synchronize()
+        for _ in range(min(2000, int(50.0 / max(a.elapsed_time(b), 1e-3)))):
+            mt.mtnn_nt(A, B, C)
+        torch.cuda.synchronize()
         t_nt, _ = _time_batches(lambda: mt.mtnn_nt(A, B, C), stream, samples, 2000.0)
         t_tnn, _ = _time_batches(lambda: mt.mtnn_tnn(A, B, C, ws), stream, samples, 2000.0)
         t_auto, _ = _time_batches(lambda: mt.mtnn_auto(A, B, C, ws), stream, samples, 2000.0)

@@ -115,6 +115,7 @@ def test_fused_layer_calls_validation(L):
     assert upd(None, 4, 6, 8, A, 8, B, 6, C, 6, A, 6, 0.1) == 4           # W is A
     assert upd(None, 0, 6, 8, None, 8, None, 6, None, 6, None, 6, 0.1) == 0
     assert L.mtnn_gemm_fused_epilogue_launches() >= 0
+    assert L.mtnn_set_fused_epilogues(0) == 1 and L.mtnn_set_fused_epilogues(1) == 0 and L.mtnn_set_fused_epilogues(1) == 1
 
 
 def test_transpose_validation_codes(L):

@@ -230,14 +230,6 @@ def test_forward_only_entry_matches_the_step_and_leaves_the_weights():
 
 # ---- the two products with their elementwise step in the epilogue ---------------------------------
 
-def rule_allows_fusing(op, m, n, k, split_ok):
-    """Whether the launch the cost model picks for an aligned (op, m, n, k) has a fused epilogue: not the
-    16-wide-slab configuration (no fused instances), not the even cut, and for the update no split-k."""
-    name = mt.gemm_configs()[mt.mtnn_gemm_default_config(op, m, n, k)]
-    splits = mt.mtnn_gemm_default_splits(op, m, n, k)
-    return "x16_" not in name and splits != mt.EVEN_CUT and (split_ok or splits == 1)
-
-
 # (m, n, k, ldx pad, ldw pad, ldy pad, operands fit the pipelined kernel)
 FORWARD_CASES = [
     (128, 2048, 784, 0, 0, 0, True),       # a Table IX layer at mini-batch 128: pipelined kernel
@@ -281,9 +273,11 @@ def test_layer_forward_is_the_product_then_bias_then_clamp(case, relu, mode):
     assert chosen == mode
     if k > 0:
         # (the NN product of TNN also needs n in 16-byte chunks)
-        fits = expect_fused and (mode == 1 or n % 4 == 0)
-        want_fused = fits and rule_allows_fusing(mt.OP_NT if mode == 1 else mt.OP_NN, m, n, k, True)
-        assert (mt.mtnn_gemm_fused_epilogue_launches() == before + 1) == want_fused
+        # operands in 16-byte chunks fuse (in the kernel, or in the reduction kernel of a split-k launch),
+        # unless the rule finds the even cut worth a separate pass
+        want_fused = expect_fused and (mode == 1 or n % 4 == 0)
+        if mt.mtnn_gemm_default_splits(mt.OP_NT if mode == 1 else mt.OP_NN, m, n, k) != mt.EVEN_CUT:
+            assert (mt.mtnn_gemm_fused_epilogue_launches() == before + 1) == want_fused
     else:
         assert mt.mtnn_gemm_fused_epilogue_launches() == before
     Y, intact = out.host()
@@ -318,6 +312,7 @@ UPDATE_CASES = [
     (200, 328, 260, 0, 0, 0, 0, True),      # ragged tiles
     (256, 512, 64, 4, 4, 8, 4, True),       # padded leading dimensions
     (10, 1024, 4096, 0, 0, 0, 0, True),     # small m n, long k: fused only if the rule does not split it
+    (4096, 4096, 1024, 0, 0, 0, 0, True),   # config 5's weight gradients (the plain product would take the 16-wide-slab configuration)
     (100, 37, 51, 0, 0, 0, 0, False),       # unaligned: separate pass
     (64, 128, 96, 0, 0, 0, 3, None),        # W rows not 16-byte aligned: fused kernel, word-wise update
 ]
@@ -348,9 +343,9 @@ def test_weight_grad_sgd_is_the_product_then_the_update(case):
     before = mt.mtnn_gemm_fused_epilogue_launches()
     mt.mtnn_fc_weight_grad_sgd(dA, dB, g.view, w.view, float(lr))
     torch.cuda.synchronize()
-    if expect_fused is not None:
-        want_fused = expect_fused and rule_allows_fusing(mt.OP_NN, m, n, k, False)
-        assert (mt.mtnn_gemm_fused_epilogue_launches() == before + 1) == want_fused
+    if expect_fused is not None and mt.mtnn_gemm_default_splits(mt.OP_NN, m, n, k) == 1:
+        # (a weight gradient the rule splits over k updates in a separate pass)
+        assert (mt.mtnn_gemm_fused_epilogue_launches() == before + 1) == expect_fused
     G, ok_g = g.host()
     Wn, ok_w = w.host()
     assert ok_g and ok_w, "wrote outside dW or W"
@@ -371,3 +366,24 @@ def test_step_uses_the_fused_epilogues():
     run_step(dims, batch, X, labels, W, b, 0.01, 1)
     # 3 forward products; of the 3 weight gradients the 10 x 1024 one may be split over k (then it updates separately)
     assert mt.mtnn_gemm_fused_epilogue_launches() - before >= 5
+
+
+def test_step_is_bit_identical_with_and_without_fused_epilogues():
+    """The process-wide switch turns every fused epilogue into the plain product plus its separate pass;
+    logits, loss, gradients and updated parameters of a step must not change by a bit."""
+    dims, batch = [784, 2048, 1024, 10], 256
+    X, labels, W, b = make_net(dims, batch, 77)
+    b[0] = (I.uniform_pm1(77, 7, 1, dims[1])[0] * 0.1).astype(np.float32)
+    fused = run_step(dims, batch, X, labels, W, b, 0.05, 1)
+    assert mt.mtnn_set_fused_epilogues(False) is True
+    try:
+        before = mt.mtnn_gemm_fused_epilogue_launches()
+        plain = run_step(dims, batch, X, labels, W, b, 0.05, 1)
+        assert mt.mtnn_gemm_fused_epilogue_launches() == before
+    finally:
+        assert mt.mtnn_set_fused_epilogues(True) is False
+    assert fused["loss"] == plain["loss"]
+    assert np.array_equal(fused["logits"].view(np.uint32), plain["logits"].view(np.uint32))
+    for key in ("dW", "db", "W_new", "b_new"):
+        for l, (x, y) in enumerate(zip(fused[key], plain[key])):
+            assert np.array_equal(x.view(np.uint32), y.view(np.uint32)), f"{key}[{l}] differs"
