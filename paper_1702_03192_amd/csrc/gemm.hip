@@ -1236,10 +1236,15 @@ static double predicted_seconds(const Config& c, int op, int m, int n, int k, in
     kloc = ((kloc + kSplitQuantum - 1) / kSplitQuantum) * kSplitQuantum;
     if (splits == 1) kloc = k;
     const int occ = c.wg_per_cu();
-    // a CU that holds a single 4-wave workgroup keeps only one wave per SIMD busy
-    const double solo = (c.threads < 512 && per_cu < occ) ? 0.85 : 1.0;
+    // A CU works through its share `occ` workgroups at a time; when one is left over at the end it runs
+    // alone, and a single 4-wave workgroup keeps only one wave per SIMD busy (measured on one tile column,
+    // 64 x 128 tiles, k = 640: 19.7 us per tile two or three at a time, 23.6 us alone; two left over of
+    // three run at the full rate).
+    const double solo_tiles = (c.threads < 512 && per_cu % occ == 1) ? 1.0 : 0.0;
+    const double solo_rate = (occ >= 3 && per_cu > 1) ? 0.92 : 0.85;      // (21.6 us alone after rounds of three)
     const double wg_flops = 2.0 * c.bm * c.bn * (double)kloc;
-    double t = (double)per_cu * wg_flops / (peak_cu * (pipelined ? c.eff[op] : c.eff_guarded[op]) * solo);
+    double t = ((double)per_cu - solo_tiles + solo_tiles / solo_rate) * wg_flops /
+               (peak_cu * (pipelined ? c.eff[op] : c.eff_guarded[op]));
     t += (double)(pipelined ? c.round_s[op] : c.round_guarded_s[op]) * (double)((per_cu + occ - 1) / occ);  // first copies + result store per round
     // HBM floor: operands once, result once
     const double bytes = 4.0 * ((double)m * k + (double)n * k + (double)m * n);
