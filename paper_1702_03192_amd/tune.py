@@ -12,7 +12,8 @@ every leading dimension by one element, which forces the guarded kernel (its num
 that table).
 
 fit: per configuration and operation, a least-squares fit (in relative error) of
-    time = tiles_per_CU x 2 bm bn k / (eff x peak_per_CU) + rounds x round_s + 3 us
+    time = tile_units x 2 bm bn k / (eff x peak_per_CU) + rounds x round_s + 3 us
+(tile_units = tiles per CU, with a workgroup left alone at the end of a CU's share counted at its slower rate)
 over the shapes whose tiles fill all 256 CUs at the configuration's occupancy with no partial tiles
 and no split; prints the fitted (eff, round_s) in the order of the table in gemm.hip, and how far the
 library's compiled-in choice (mtnn_gemm_default_config / _splits) is from the best measured
@@ -79,6 +80,21 @@ def collect(out_path, samples, min_batch_us, odd_ld):
             print(f"[tune] m = {m} done", flush=True)
 
 
+def tile_units(per_cu, occ, waves):
+    """A CU's share in tile times, as gemm.hip's cost model counts it: `per_cu` tiles worked through `occ`
+    at a time; one 4-wave workgroup left over at the end runs alone, at 0.85 of the rate (0.92 after rounds
+    of three)."""
+    if waves >= 8 or per_cu % occ != 1:
+        return float(per_cu)
+    rate = 0.92 if (occ >= 3 and per_cu > 1) else 0.85
+    return per_cu - 1 + 1.0 / rate
+
+
+def _config_waves(name):
+    g = re.match(r"\d+x\d+x\d+_w(\d+)x(\d+)_", name)
+    return int(g.group(1)) * int(g.group(2))
+
+
 def _config_geometry(name):
     """(bm, bn, workgroups per CU the launch allows, LDS bytes of the pipelined kernel) from a configuration name."""
     g = re.match(r"(\d+)x(\d+)x(\d+)_w(\d+)x(\d+)_dma(\d+)_x(\d+)", name)
@@ -114,7 +130,7 @@ def fit_table(table, names):
                 if tiles < 256 * occ:
                     continue
                 per_cu = -(-tiles // 256)
-                X.append([per_cu * 2.0 * bm * bn * k / PEAK_PER_CU, -(-per_cu // occ)])
+                X.append([tile_units(per_cu, occ, _config_waves(nm)) * 2.0 * bm * bn * k / PEAK_PER_CU, -(-per_cu // occ)])
                 y.append(tab[(c, 1)] - 3e-6)
             if len(y) < 4:
                 out[(c, op)] = None

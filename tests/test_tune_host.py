@@ -12,6 +12,15 @@ def test_every_configuration_name_parses():
         assert name.startswith(f"{bm}x{bn}x")
 
 
+def test_tile_units_charge_the_workgroup_left_alone():
+    assert tune.tile_units(4, 2, 4) == 4.0                       # whole rounds
+    assert tune.tile_units(3, 2, 4) == 2 + 1 / 0.85              # two together, one alone
+    assert tune.tile_units(1, 2, 4) == 1 / 0.85
+    assert tune.tile_units(4, 3, 4) == 3 + 1 / 0.92              # alone after a round of three
+    assert tune.tile_units(5, 3, 4) == 5.0                       # two left over run at the full rate
+    assert tune.tile_units(3, 1, 8) == 3.0                       # 8-wave workgroups fill the SIMDs alone
+
+
 def test_fit_recovers_planted_parameters():
     names = mt.gemm_configs()
     planted = {}
@@ -26,7 +35,8 @@ def test_fit_recovers_planted_parameters():
                     for k in (64, 512, 4096):
                         tiles = -(-m // bm) * -(-n // bn)
                         per_cu = -(-tiles // 256)
-                        t = per_cu * 2.0 * bm * bn * k / (tune.PEAK_PER_CU * eff) + -(-per_cu // occ) * round_s + 3e-6
+                        units = tune.tile_units(per_cu, occ, tune._config_waves(name))
+                        t = units * 2.0 * bm * bn * k / (tune.PEAK_PER_CU * eff) + -(-per_cu // occ) * round_s + 3e-6
                         table.setdefault((op, m, n, k), {})[(c, 1)] = t
     fitted = tune.fit_table(table, names)
     for key, (eff, round_s) in planted.items():
