@@ -670,6 +670,13 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
     // place), so every issuing wave issues exactly LPS copies per slab.
     const int grp = wave / NI;
     const int wi = wave % NI;
+    // NT with four blocks per wave across n and a 16-byte aligned C: the rows of the B tile are placed
+    // in LDS so that block j of lane l works on column TN * l + j, as in the NN kernel (LDS row
+    // j * 32 + l of a wave's WN rows holds B row TN * l + j).  The fragment reads do not change, and the
+    // epilogue stores TN consecutive words per lane straight from registers instead of going through
+    // the LDS patches (256 x 256 tiles: 2-3 us per tile, 1.3 % at k = 1024, 3.4 % at k = 256).
+    const bool c_vec = ((reinterpret_cast<uintptr_t>(w.C) & 15) == 0) && ((w.ldc & 3) == 0);
+    const bool interleave = NT && TN == 4 && c_vec;
     const float* a_tile = uniform_ptr(w.A + (size_t)m0 * p.lda);
     const float* b_tile = uniform_ptr(NT ? w.B + (size_t)n0 * p.ldb : w.B);
     unsigned a_off[A_LOADS], a_dst[A_LOADS];
@@ -697,7 +704,12 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
             const int slot = u % CPR;
             const int c = slot ^ ((row / RPL) % CPR);
             b_k[i] = c * 4;
-            b_off[i] = (unsigned)(((size_t)(min(n0 + row, N - 1) - n0) * p.ldb + b_k[i]) * 4);
+            int brow = row;                                    // which row of B lands in LDS row `row`
+            if (interleave) {
+                const int local = row % WN;
+                brow = row - local + TN * (local % 32) + local / 32;
+            }
+            b_off[i] = (unsigned)(((size_t)(min(n0 + brow, N - 1) - n0) * p.ldb + b_k[i]) * 4);
         } else {
             const int krow = u / NCH;
             const int slot = u % NCH;
@@ -866,7 +878,6 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
 
     // epilogue: interior tiles of a 16-byte-aligned C go through wave-private LDS patches (the slab
     // buffers are free once every wave has passed this barrier)
-    const bool c_vec = ((reinterpret_cast<uintptr_t>(w.C) & 15) == 0) && ((w.ldc & 3) == 0);
     const bool stream = whole_lines(w.C, w.ldc);
     // kEpiBiasAct: the bias of the lane's column of each block (the block -> column mapping of the stores),
     // added, and the clamp applied, as each value is stored: the same two operations on the same fp32
@@ -877,7 +888,7 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
     for (int j = 0; j < TN; ++j) {
         bv[j] = 0.f;
         if (BIAS) {
-            const int col = NT ? n0 + wn0 + j * 32 + lr : n0 + wn0 + TN * lr + j;
+            const int col = (NT && !interleave) ? n0 + wn0 + j * 32 + lr : n0 + wn0 + TN * lr + j;
             if (col < N) bv[j] = p.bias[col];
         }
     }
@@ -886,7 +897,7 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
         static_assert(!NT, "the fused update exists for the NN kernel only");
         const bool w_vec = c_vec && ((reinterpret_cast<uintptr_t>(p.W) & 15) == 0) && ((p.ldw & 3) == 0);
         store_tile_interleaved_sgd<TM, TN>(acc, w.C, w.ldc, p.W, p.ldw, p.lr, M, N, m0 + wm0, n0 + wn0, lr, lh, w_vec);
-    } else if (!NT) {
+    } else if (!NT || interleave) {
         if (stream)
             store_tile_interleaved<TM, TN, BIAS, true>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh, c_vec, bv, relu);
         else
@@ -1153,7 +1164,10 @@ constexpr void (*epilogue_kernel())(GemmParams)
 
 static const Config kConfigs[] = {
     //           tile         waves stages    per CU   NN: eff, round      NT: eff, round       guarded kernel: NN, NT
-    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2, 16,   1,   0.949f, 13.8e-6f,   0.943f, 13.3e-6f,   0.871f, 12.7e-6f, 0.842f, 11.5e-6f),  // 0: 8 waves of 64 x 128, 128 KB of LDS
+    // (0: NT carries NN's pair: since its epilogue stores straight from registers like NN's, the two measure
+    //  the same -- 143.4 TFLOP/s both at 8192 x 8192 x 1024, 122.2 / 122.3 at k = 256; its own fit, 0.943 and
+    //  13.3 us, dates from the staged epilogue)
+    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2, 16,   1,   0.949f, 13.8e-6f,   0.949f, 13.8e-6f,   0.871f, 12.7e-6f, 0.842f, 11.5e-6f),  // 0: 8 waves of 64 x 128, 128 KB of LDS
     // (1: the fits put it level with configuration 0 inside the grid; beyond it the narrower tile
     //  re-reads more of A and falls behind -- NN 135 against 148 TFLOP/s at 65536^3, NT 139 against 148 at
     //  65536 x 256 x 32768 and 146 against 149 at 16384^3 -- so both operations rate it just below)
