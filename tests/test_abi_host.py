@@ -175,3 +175,24 @@ def test_inplace_transpose_validation(L):
     assert L.mtnn_transpose_inplace(None, 0, None, 0) == 0
     assert L.mtnn_tnn_inplace(None, 4, 6, 8, A, 8, B, 8, C, 6) == 8      # B not square
     assert L.mtnn_tnn_inplace(None, 4, 8, 8, A, 7, B, 8, C, 8) == 3
+
+
+def test_cost_model_choice_is_valid_and_repeatable_over_many_shapes():
+    """The configuration / split rule on 3000 seeded shapes from 1 to 2^17 per dimension (pure host code):
+    always a configuration of the table and a split count the launcher accepts, the same on every call,
+    and split-k only where every split keeps at least 128 of k."""
+    import numpy as np
+    rng = np.random.default_rng(1702)
+    n_cfg = len(mt.gemm_configs())
+    dims = np.exp(rng.uniform(0.0, np.log(2.0 ** 17), size=(3000, 3))).astype(np.int64)
+    dims[:8] = [[1, 1, 1], [1, 131072, 1], [131072, 1, 131072], [65536, 65536, 65536], [1, 1, 131072],
+                [131072, 131072, 1], [7, 5, 3], [255, 257, 129]]
+    for m, n, k in dims:
+        m, n, k = int(m), int(n), int(k)
+        for op in (0, 1):
+            c, s = mt.mtnn_gemm_default_config(op, m, n, k), mt.mtnn_gemm_default_splits(op, m, n, k)
+            assert 0 <= c < n_cfg
+            assert s == mt.EVEN_CUT or s in (1, 2, 4, 8, 16, 32)
+            if s > 1:
+                assert k // s >= 128 and m * n * s * 4 <= (64 << 20)
+            assert (c, s) == (mt.mtnn_gemm_default_config(op, m, n, k), mt.mtnn_gemm_default_splits(op, m, n, k))
