@@ -234,6 +234,8 @@ def test_forward_only_entry_matches_the_step_and_leaves_the_weights():
 FORWARD_CASES = [
     (128, 2048, 784, 0, 0, 0, True),       # a Table IX layer at mini-batch 128: pipelined kernel
     (1024, 4096, 4096, 0, 0, 0, True),     # a config-2 shape
+    (4096, 4096, 1024, 0, 0, 0, True),     # the other one: 256 x 256 tiles, whose NT columns are interleaved per lane
+    (4000, 4000, 1000, 0, 0, 0, True),     # ... with ragged edge tiles
     (200, 328, 1000, 0, 0, 0, True),       # ragged tiles, operands still in 16-byte chunks
     (256, 512, 260, 4, 8, 4, True),        # padded leading dimensions (multiples of 4)
     (64, 128, 8192, 0, 0, 0, True),        # split-k: the reduction kernel carries the epilogue
