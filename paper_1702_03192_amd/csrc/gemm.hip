@@ -36,6 +36,7 @@
 #include "mtnn_internal.h"
 
 #include <atomic>
+#include <cmath>
 #include <cstdlib>
 #include <mutex>
 
@@ -1259,7 +1260,14 @@ static double predicted_seconds(const Config& c, int op, int m, int n, int k, in
     const double wg_flops = 2.0 * c.bm * c.bn * (double)kloc;
     double t = ((double)per_cu - solo_tiles + solo_tiles / solo_rate) * wg_flops /
                (peak_cu * (pipelined ? c.eff[op] : c.eff_guarded[op]));
-    t += (double)(pipelined ? c.round_s[op] : c.round_guarded_s[op]) * (double)((per_cu + occ - 1) / occ);  // first copies + result store per round
+    // first copies + result store per round.  The 256 x 256 tile's figure was fitted on grids of at most
+    // four rounds, where all 256 workgroups store at the same moment; over more rounds they drift apart
+    // and the stores stop colliding (NN, k = 512, per round beyond the k loop: 11.7 us at 4 rounds, 7.5
+    // at 16, 4.8 at 64, 4.3 at 256).
+    const long long rounds = (per_cu + occ - 1) / occ;
+    double round_cost = pipelined ? c.round_s[op] : c.round_guarded_s[op];
+    if (pipelined && c.bm * c.bn >= 256 * 256 && rounds > 4) round_cost *= 0.36 + 0.64 * pow(4.0 / (double)rounds, 0.75);
+    t += round_cost * (double)rounds;
     // HBM floor: operands once, result once
     const double bytes = 4.0 * ((double)m * k + (double)n * k + (double)m * n);
     if (t < bytes / 5.0e12) t = bytes / 5.0e12;
