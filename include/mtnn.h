@@ -12,15 +12,19 @@
  * Conventions for every call
  *   - matrices are row-major fp32; leading dimensions are in ELEMENTS;
  *   - A, B, C, in, out and workspace are DEVICE pointers owned by the caller; the library keeps no
- *     reference to them after the enqueued work has run.  The only device memory the library ever
- *     allocates is the split-k scratch described at mtnn_gemm_ex (once per device and stream,
- *     on the first launch that needs it);
+ *     reference to them after the enqueued work has run.  The library allocates and frees no device
+ *     memory: the one buffer it uses beyond a call's arguments is the scratch the caller lends it
+ *     per stream with mtnn_set_scratch;
+ *   - the kernels exist for gfx950 only: a call that would launch one while the current device is
+ *     missing or of another architecture returns MTNN_ERR_NO_DEVICE and launches nothing;
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); work is enqueued
  *     on it and the call returns without synchronising;
  *   - alpha = 1 and there is no beta*C term (Section II): C is overwritten;
  *   - padding elements (columns at or beyond the logical width when ld > width) are never
  *     written in outputs and never influence results when present in inputs;
- *   - the same inputs and shape give bit-identical outputs on every call (no atomics);
+ *   - the same inputs, shape and scratch capacity of the stream give bit-identical outputs on every
+ *     call, inside or outside a stream capture (no atomics; how a product is divided over workgroups
+ *     depends on (operation, m, n, k, alignment, scratch bytes registered) and nothing else);
  *   - the return value is MTNN_OK (0) or one of the MTNN_ERR_* codes below.  Arguments are
  *     validated on the host before any device call, so a call that fails validation has
  *     touched neither the device nor the outputs.
@@ -49,7 +53,7 @@ enum {
     MTNN_ERR_NULL = 2,       /* a NULL pointer with a non-empty problem                   */
     MTNN_ERR_LD = 3,         /* a leading dimension smaller than the logical row length   */
     MTNN_ERR_ALIAS = 4,      /* an output range overlaps an input range                   */
-    MTNN_ERR_WORKSPACE = 5,  /* workspace missing or too small (mtnn_tnn only)            */
+    MTNN_ERR_WORKSPACE = 5,  /* workspace (mtnn_tnn) or scratch (an explicit split) missing or too small */
     MTNN_ERR_LAUNCH = 6,     /* the HIP runtime refused a launch                          */
     MTNN_ERR_MODEL = 7,      /* model file missing, malformed or of the wrong arity       */
     MTNN_ERR_ARG = 8,        /* any other invalid argument (bad config id, bad label ...) */
@@ -161,16 +165,25 @@ MTNN_API int mtnn_model_margin(const double *x, int nfeat, double *margin);
  * mtnn_nt / mtnn_nn choose both per shape with a fixed cost model.  These calls run a given
  * configuration (cfg in [0, count), or -1 for the model's choice) and split count (1..32, or 0 for
  * the model's choice when cfg is -1 and no split when cfg is given).  op: 0 = NN, 1 = NT.
- * Split-k keeps its partial products in a 64 MiB scratch buffer that the library allocates once per
- * (device, stream) the first time it is needed and never frees; a launch whose partials do not fit
- * runs unsplit, and so does one issued while its stream is being captured into a HIP graph before the
- * buffer exists (the library never allocates under capture; run the call once on that stream first).
+ *
+ * Scratch.  A split launch keeps its partial products (m x n x splits floats) in scratch memory that
+ * the CALLER owns and registers per stream: mtnn_set_scratch(stream, ptr, bytes) lends the library
+ * `bytes` of device memory at `ptr` (256-byte aligned) for every later launch on that stream of the
+ * current device, until it is replaced or withdrawn (ptr = NULL, bytes = 0); the memory must stay
+ * valid while such launches are in flight, and launches on other streams must get other memory.  The
+ * cost model only considers divisions whose partials fit what is registered (nothing registered:
+ * unsplit launches only), so a call's result depends on the registered capacity and not on when or
+ * where it is issued; an EXPLICIT split count (or even cut) that does not fit returns
+ * MTNN_ERR_WORKSPACE.  mtnn_scratch_bytes_default() is the capacity the cost model was tuned with
+ * (64 MiB) and the one mtnn_gemm_default_config / _splits assume; mtnn_gemm_scratch_bytes is what a
+ * given (cfg, splits) launch needs (0 for an unsplit one or invalid arguments).
+ *
  * splits = MTNN_GEMM_EVEN_CUT asks for the third way of dividing the work: the k ranges of all C
- * tiles, in units of 64, are laid in one line and cut into 256 x (workgroups per CU) equal pieces,
+ * tiles, in units of 64, are laid in one line and cut into (CUs x workgroups per CU) equal pieces,
  * one per workgroup; tiles that a cut goes through are finished by a fix-up kernel that adds their
- * pieces in k order (same scratch buffer, same reproducibility).  It runs only where the pipelined
- * kernel can (16-byte aligned operands, k % 4 = 0, ...), there are at least as many units as pieces
- * and the scratch fits; otherwise the call runs unsplit.  mtnn_gemm_default_splits may return it. */
+ * pieces in k order (same scratch, same reproducibility).  It runs only where the pipelined
+ * kernel can (16-byte aligned operands, k % 4 = 0, ...) and there are at least as many units as
+ * pieces; otherwise the call runs unsplit.  mtnn_gemm_default_splits may return it. */
 #define MTNN_GEMM_EVEN_CUT (-2)
 MTNN_API int mtnn_gemm_config_count(void);
 MTNN_API const char *mtnn_gemm_config_name(int cfg);
@@ -178,6 +191,13 @@ MTNN_API int mtnn_gemm_default_config(int op, int m, int n, int k);
 MTNN_API int mtnn_gemm_default_splits(int op, int m, int n, int k);
 MTNN_API int mtnn_gemm_ex(void *stream, int op, int cfg, int splits, int m, int n, int k,
                  const float *A, int lda, const float *B, int ldb, float *C, int ldc);
+MTNN_API int mtnn_set_scratch(void *stream, void *scratch, size_t bytes);
+MTNN_API size_t mtnn_get_scratch_bytes(void *stream);      /* registered for (current device, stream); 0 if none */
+MTNN_API size_t mtnn_scratch_bytes_default(void);
+MTNN_API size_t mtnn_gemm_scratch_bytes(int cfg, int splits, int m, int n, int k);
+/* What mtnn_nt (op 1) / mtnn_nn (op 0) choose for 16-byte aligned operands of this shape on a stream
+ * with `scratch_bytes` registered: *cfg the configuration, *splits 1..32 or MTNN_GEMM_EVEN_CUT. */
+MTNN_API int mtnn_gemm_choice(int op, int m, int n, int k, size_t scratch_bytes, int *cfg, int *splits);
 /* How many launches of this process took the even-cut path (diagnostics, tests). */
 MTNN_API long long mtnn_gemm_even_cut_launches(void);
 /* How many products of this process ran with a fused epilogue (mtnn_fc_layer_forward,
@@ -283,6 +303,10 @@ MTNN_API const char *mtnn_status_string(int status);
 /* The hipError_t behind the most recent MTNN_ERR_LAUNCH in this process (0 if none); diagnostics. */
 MTNN_API int mtnn_last_hip_error(void);
 MTNN_API int mtnn_version(void);
+/* 1 if `arch` (the architecture name the HIP runtime reports for a device, e.g.
+ * "gfx950:sramecc+:xnack-") is the one the kernels are built for, else 0.  Every call that launches
+ * a kernel applies this test to the current device and returns MTNN_ERR_NO_DEVICE when it fails. */
+MTNN_API int mtnn_arch_supported(const char *arch);
 /* A property of the current device, for reports: what = 0 compute units, 1 peak shader clock in kHz,
  * 2 peak memory clock in kHz, 3 memory bus width in bits.  Returns -1 if it cannot be read (no device,
  * unknown `what`). */

@@ -70,6 +70,12 @@ SIGNATURES = {
     "mtnn_gemm_default_config": (_c_int, [_c_int, _c_int, _c_int, _c_int]),
     "mtnn_gemm_default_splits": (_c_int, [_c_int, _c_int, _c_int, _c_int]),
     "mtnn_gemm_ex": (_c_int, [_c_vp, _c_int, _c_int, _c_int] + _GEMM[1:]),
+    "mtnn_set_scratch": (_c_int, [_c_vp, _c_vp, _c_sz]),
+    "mtnn_get_scratch_bytes": (_c_sz, [_c_vp]),
+    "mtnn_scratch_bytes_default": (_c_sz, []),
+    "mtnn_gemm_scratch_bytes": (_c_sz, [_c_int, _c_int, _c_int, _c_int, _c_int]),
+    "mtnn_gemm_choice": (_c_int, [_c_int, _c_int, _c_int, _c_int, _c_sz, _p_int, _p_int]),
+    "mtnn_arch_supported": (_c_int, [ctypes.c_char_p]),
     "mtnn_fc_workspace_bytes": (_c_sz, [_c_int, _p_int, _c_int]),
     "mtnn_fc_train_step": (_c_int, [_c_vp, ctypes.POINTER(FcStepDesc)]),
     "mtnn_fc_forward": (_c_int, [_c_vp, ctypes.POINTER(FcStepDesc)]),
@@ -131,13 +137,49 @@ def _check(status: int, where: str) -> None:
         raise MtnnError(status, where)
 
 
-def _stream(stream) -> Optional[int]:
+# The library allocates nothing: launches that divide a product over several workgroups per C tile
+# keep their partial products in scratch memory lent per (device, stream).  This binding lends a torch
+# tensor of the default capacity the first time it sees a stream, so that every call on that stream
+# -- eager or under capture -- is divided the same way.
+_scratch = {}     # (device index, stream handle) -> the tensor lent to the library
+
+
+def lend_scratch(stream=None, nbytes: Optional[int] = None):
+    """Lend the library `nbytes` (default: mtnn_scratch_bytes_default()) of scratch for `stream` of the current
+    device, replacing what was lent before.  nbytes = 0 withdraws it (split launches then do not run)."""
+    import torch
+    h = _handle(stream)
+    key = (torch.cuda.current_device(), h)
+    if nbytes is None:
+        nbytes = int(lib().mtnn_scratch_bytes_default())
+    if nbytes == 0:
+        _check(lib().mtnn_set_scratch(h or None, None, 0), "mtnn_set_scratch")
+        _scratch[key] = None
+        return None
+    if torch.cuda.is_current_stream_capturing():
+        raise RuntimeError("scratch cannot be allocated while a stream is being captured: call lend_scratch(stream) "
+                           "(or run one call on the stream) before the capture begins")
+    buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    _check(lib().mtnn_set_scratch(h or None, buf.data_ptr(), nbytes), "mtnn_set_scratch")
+    _scratch[key] = buf      # (the previous tensor, if any, is released only now that the library no longer points at it)
+    return buf
+
+
+def _handle(stream) -> int:
     if stream is None:
         import torch
-        return torch.cuda.current_stream().cuda_stream or None
+        return int(torch.cuda.current_stream().cuda_stream)
     if isinstance(stream, int):
-        return stream or None
-    return stream.cuda_stream or None
+        return stream
+    return int(stream.cuda_stream)
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    h = _handle(stream)
+    if (torch.cuda.current_device(), h) not in _scratch:
+        lend_scratch(h)
+    return h or None
 
 
 def _dev(t, name):
@@ -426,6 +468,24 @@ def mtnn_copy_bytes(src, dst, stream=None):
 
 def mtnn_gemm_default_splits(op: int, m: int, n: int, k: int) -> int:
     return int(lib().mtnn_gemm_default_splits(op, m, n, k))
+
+
+def mtnn_gemm_scratch_bytes(cfg: int, splits: int, m: int, n: int, k: int) -> int:
+    """Scratch a (cfg, splits) launch needs for its partial products; 0 for an unsplit launch."""
+    return int(lib().mtnn_gemm_scratch_bytes(cfg, splits, m, n, k))
+
+
+def mtnn_gemm_choice(op: int, m: int, n: int, k: int, scratch_bytes: Optional[int] = None):
+    """(cfg, splits) the cost model picks for aligned operands with that much scratch (default: the default capacity)."""
+    if scratch_bytes is None:
+        scratch_bytes = int(lib().mtnn_scratch_bytes_default())
+    c, s = ctypes.c_int(), ctypes.c_int()
+    _check(lib().mtnn_gemm_choice(op, m, n, k, scratch_bytes, ctypes.byref(c), ctypes.byref(s)), "mtnn_gemm_choice")
+    return c.value, s.value
+
+
+def mtnn_get_scratch_bytes(stream=None) -> int:
+    return int(lib().mtnn_get_scratch_bytes(_handle(stream) or None))
 
 
 def mtnn_status_string(status: int) -> str:

@@ -4,6 +4,7 @@
 #include "../../include/mtnn.h"
 #include "mtnn_internal.h"
 #include "selector.h"
+#include "gemm_config.h"
 
 #include <atomic>
 #include <stdint.h>
@@ -18,9 +19,13 @@ std::atomic<int> g_fuse_epilogues{1};   // mtnn_set_fused_epilogues: 0 = always 
 int launch_status(int err)
 {
     if (err == 0) return MTNN_OK;
+    if (err == mtnn::kErrScratch) return MTNN_ERR_WORKSPACE;
     g_last_hip_error = err;
     return MTNN_ERR_LAUNCH;
 }
+
+// what split launches on a stream may use when the caller has registered nothing smaller or larger
+constexpr size_t kDefaultScratchBytes = 64u << 20;
 
 struct Range {
     uintptr_t lo, hi;   // [lo, hi)
@@ -60,18 +65,22 @@ int check_gemm(int op, int m, int n, int k, const float* A, int lda, const float
 }
 
 // epi: work to fuse into the product where the launch can, done as a separate pass over C where it cannot
+// scratch: where a split launch keeps its partial products; null = what the caller registered for the stream
 int run_gemm(void* stream, int op, int cfg, int splits, int m, int n, int k, const float* A, int lda,
-             const float* B, int ldb, float* C, int ldc, const mtnn::Epilogue* epi = nullptr)
+             const float* B, int ldb, float* C, int ldc, const mtnn::Epilogue* epi = nullptr,
+             const mtnn::Scratch* scratch = nullptr)
 {
     const int st = check_gemm(op, m, n, k, A, lda, B, ldb, C, ldc);
     if (st != MTNN_OK) return st;
     if (m == 0 || n == 0) return MTNN_OK;
+    mtnn::Geometry geo;
+    if (!mtnn::current_geometry(&geo)) return MTNN_ERR_NO_DEVICE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     int err;
     bool fused = false;
     if (k == 0) err = mtnn::launch_fill_zero(s, m, n, C, ldc);
-    else err = mtnn::launch_gemm(s, op, cfg, splits, m, n, k, A, lda, B, ldb, C, ldc,
-                                 g_fuse_epilogues.load() ? epi : nullptr, &fused);
+    else err = mtnn::launch_gemm(s, geo, scratch ? *scratch : mtnn::scratch_lookup(s), op, cfg, splits, m, n, k,
+                                 A, lda, B, ldb, C, ldc, g_fuse_epilogues.load() ? epi : nullptr, &fused);
     if (err == 0 && epi && !fused) {
         if (epi->kind == 1) err = mtnn::launch_bias_act(s, m, n, C, ldc, epi->bias, epi->relu);
         else err = mtnn::launch_sgd_2d(s, m, n, epi->W, epi->ldw, C, ldc, epi->lr);
@@ -114,6 +123,12 @@ int pick_label(int m, int n, int k, const void* workspace, size_t workspace_byte
     return label;
 }
 
+bool device_ok()
+{
+    mtnn::Geometry geo;
+    return mtnn::current_geometry(&geo);
+}
+
 int check_transpose(int rows, int cols, const float* in, int ldin, const float* out, int ldout)
 {
     if (rows < 0 || cols < 0) return MTNN_ERR_DIM;
@@ -152,7 +167,37 @@ int mtnn_gemm_ex(void* stream, int op, int cfg, int splits, int m, int n, int k,
 int mtnn_gemm_default_splits(int op, int m, int n, int k)
 {
     if ((op != mtnn::OP_NN && op != mtnn::OP_NT) || m <= 0 || n <= 0 || k <= 0) return -1;
-    return mtnn::gemm_default_splits(op, m, n, k);
+    return mtnn::gemm_default_splits(op, m, n, k, kDefaultScratchBytes);
+}
+
+size_t mtnn_scratch_bytes_default(void) { return kDefaultScratchBytes; }
+
+int mtnn_gemm_choice(int op, int m, int n, int k, size_t scratch_bytes, int* cfg, int* splits)
+{
+    if (op != mtnn::OP_NN && op != mtnn::OP_NT) return MTNN_ERR_ARG;
+    if (m <= 0 || n <= 0 || k <= 0) return MTNN_ERR_DIM;
+    const mtnn::Choice ch = mtnn::choose(mtnn::geometry_or_nominal(), op, m, n, k, true, true, mtnn::kEpiNone, scratch_bytes);
+    if (cfg) *cfg = ch.cfg;
+    if (splits) *splits = ch.splits;
+    return MTNN_OK;
+}
+
+int mtnn_set_scratch(void* stream, void* scratch, size_t bytes)
+{
+    return mtnn::scratch_register(static_cast<hipStream_t>(stream), scratch, bytes);
+}
+
+size_t mtnn_get_scratch_bytes(void* stream)
+{
+    const mtnn::Scratch s = mtnn::scratch_lookup(static_cast<hipStream_t>(stream));
+    return s.ptr ? s.bytes : 0;
+}
+
+size_t mtnn_gemm_scratch_bytes(int cfg, int splits, int m, int n, int k)
+{
+    if (cfg < 0 || cfg >= mtnn::gemm_config_count() || m <= 0 || n <= 0 || k <= 0) return 0;
+    if (splits != MTNN_GEMM_EVEN_CUT && (splits < 2 || splits > 32)) return 0;
+    return mtnn::scratch_needed(mtnn::geometry_or_nominal(), cfg, splits, m, n, k);
 }
 
 int mtnn_gemm_config_count(void) { return mtnn::gemm_config_count(); }
@@ -160,7 +205,7 @@ const char* mtnn_gemm_config_name(int cfg) { return mtnn::gemm_config_name(cfg);
 int mtnn_gemm_default_config(int op, int m, int n, int k)
 {
     if ((op != mtnn::OP_NN && op != mtnn::OP_NT) || m <= 0 || n <= 0 || k <= 0) return -1;
-    return mtnn::gemm_default_config(op, m, n, k);
+    return mtnn::gemm_default_config(op, m, n, k, kDefaultScratchBytes);
 }
 
 int mtnn_transpose(void* stream, int rows, int cols, const float* in, int ldin, float* out, int ldout)
@@ -168,6 +213,7 @@ int mtnn_transpose(void* stream, int rows, int cols, const float* in, int ldin, 
     const int st = check_transpose(rows, cols, in, ldin, out, ldout);
     if (st != MTNN_OK) return st;
     if (rows == 0 || cols == 0) return MTNN_OK;
+    if (!device_ok()) return MTNN_ERR_NO_DEVICE;
     const int err = mtnn::launch_transpose(static_cast<hipStream_t>(stream), rows, cols, in, ldin, out, ldout);
     return launch_status(err);
 }
@@ -178,6 +224,7 @@ int mtnn_transpose_inplace(void* stream, int n, float* X, int ld)
     if (n == 0) return MTNN_OK;
     if (!X) return MTNN_ERR_NULL;
     if (ld < n) return MTNN_ERR_LD;
+    if (!device_ok()) return MTNN_ERR_NO_DEVICE;
     return launch_status(mtnn::launch_transpose_inplace(static_cast<hipStream_t>(stream), n, X, ld));
 }
 
@@ -188,6 +235,9 @@ int mtnn_tnn_inplace(void* stream, int m, int n, int k, const float* A, int lda,
     const int st0 = check_gemm(mtnn::OP_NT, m, n, k, A, lda, B, ldb, C, ldc);
     if (st0 != MTNN_OK) return st0;
     if (m == 0 || n == 0) return MTNN_OK;
+    // B is written on the way (transposed, then transposed back): as an output it must not overlap A
+    // (the Gram product A x A^T with A == B would otherwise have its left operand transposed under it)
+    if (overlap(span(B, n, k, ldb), span(A, m, k, lda))) return MTNN_ERR_ALIAS;
     int st = mtnn_transpose_inplace(stream, n, B, ldb);
     if (st != MTNN_OK) return st;
     st = run_gemm(stream, mtnn::OP_NN, -1, 0, m, n, k, A, lda, B, ldb, C, ldc);
@@ -203,6 +253,7 @@ int mtnn_copy_bytes(void* stream, size_t bytes, const void* in, void* out)
         return MTNN_ERR_ARG;
     const uintptr_t a = reinterpret_cast<uintptr_t>(in), b = reinterpret_cast<uintptr_t>(out);
     if (a < b + bytes && b < a + bytes) return MTNN_ERR_ALIAS;
+    if (!device_ok()) return MTNN_ERR_NO_DEVICE;
     return launch_status(mtnn::launch_copy(static_cast<hipStream_t>(stream), bytes / 16, in, out));
 }
 
@@ -287,6 +338,8 @@ int mtnn_version(void) { return 100; }
 long long mtnn_gemm_even_cut_launches(void) { return mtnn::gemm_streamk_launches(); }
 long long mtnn_gemm_fused_epilogue_launches(void) { return mtnn::gemm_fused_launches(); }
 int mtnn_set_fused_epilogues(int enable) { return g_fuse_epilogues.exchange(enable ? 1 : 0); }
+
+int mtnn_arch_supported(const char* arch) { return mtnn::arch_is_gfx950(arch) ? 1 : 0; }
 
 int mtnn_device_attribute(int what)
 {

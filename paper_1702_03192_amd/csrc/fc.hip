@@ -293,7 +293,16 @@ int launch_sgd_2d(hipStream_t s, int rows, int width, float* P, long ldp, const 
 }  // namespace mtnn
 
 namespace {
-int status_of(hipError_t e) { return e == hipSuccess ? MTNN_OK : MTNN_ERR_LAUNCH; }
+// (the elementwise kernels ask nothing of the device's geometry, so these entry points do not look it
+// up; a launch refused for want of a device, or of code for it, reports that instead of a launch error)
+int status_of(hipError_t e)
+{
+    if (e == hipSuccess) return MTNN_OK;
+    if (e == hipErrorNoDevice || e == hipErrorInvalidDevice || e == hipErrorNoBinaryForGpu ||
+        e == hipErrorInvalidDeviceFunction || e == hipErrorSharedObjectInitFailed)
+        return MTNN_ERR_NO_DEVICE;
+    return MTNN_ERR_LAUNCH;
+}
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 }  // namespace
 

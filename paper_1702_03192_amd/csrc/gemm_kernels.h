@@ -33,12 +33,8 @@
 //
 // The summation order of every C element is fixed by (configuration, k), never by timing:
 // results are bit-reproducible.
-#include "mtnn_internal.h"
-
-#include <atomic>
-#include <cmath>
-#include <cstdlib>
-#include <mutex>
+#pragma once
+#include "gemm_config.h"
 
 namespace mtnn {
 
@@ -48,36 +44,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // global load where the target allows unaligned vector access
 typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 
-struct GemmParams {
-    const float* A;
-    const float* B;
-    float* C;
-    int M, N, K;
-    long lda, ldb, ldc;
-    int tiles_m, tiles_n;
-    int group_m;      // C-tile rows per band (L2 locality)
-    int num_xcd;      // 8 on MI355X
-    // split-k: workgroup w handles C tile w % tiles and k range [split * k_per_split, ...) with
-    // split = w / tiles; partial products go to `part` (splits dense M x N matrices), summed by
-    // reduce_splits_kernel in split order.  splits == 1: results go straight to C.
-    int splits;
-    int k_per_split;  // a multiple of every configuration's k slab
-    float* part;
-    int sk_units_per_tile;   // gemm_streamk_kernel: k units (of kSplitQuantum) per tile
-    // fused epilogues (read only by the kernel instances built for them)
-    const float* bias;       // kEpiBiasAct: C = act(A x B + bias[column])
-    int relu;
-    float* W;                // kEpiSgd: C = A x B and W -= lr * C (W: M x N, leading dimension ldw)
-    long ldw;
-    float lr;
-};
 
-// what a kernel instance does with its accumulators besides storing them
-constexpr int kEpiNone = 0;
-constexpr int kEpiBiasAct = 1;   // every launch shape; with split-k the reduction kernel applies it
-constexpr int kEpiSgd = 2;       // pipelined NN kernel, unsplit launches only
 
-constexpr int kSplitQuantumDev = 64;   // k ranges of split work are multiples of this (every slab size divides it)
 
 // what one workgroup works on: its k range of A and B, and where its tile of results goes
 struct WorkView {
@@ -970,8 +938,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_streamk_kernel(Gem
         const int s1 = (left < cut.units_per_tile - s0) ? s0 + left : cut.units_per_tile;
         int tm, tn;
         tile_of_block(q, tile, tm, tn);
-        const int k0 = s0 * kSplitQuantumDev;
-        const int k1 = min(p.K, s1 * kSplitQuantumDev);
+        const int k0 = s0 * kSplitQuantum;
+        const int k1 = min(p.K, s1 * kSplitQuantum);
         WorkView w;
         w.pid = tile;
         w.K = k1 - k0;
@@ -995,7 +963,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_streamk_kernel(Gem
 
 // C tile = sum of its pieces in k order, for every tile that was cut.  kFixChunks workgroups of 256
 // threads per tile, each taking a band of BM / kFixChunks rows.
-constexpr int kFixChunks = 4;
 constexpr int kFixMaxPieces = 8;      // pieces of one tile summed per pass (more: further passes)
 
 template <int BM, int BN>
@@ -1090,417 +1057,4 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restr
         C[(size_t)i * ldc + j] = acc;
     }
 }
-
-// ---- configurations ---------------------------------------------------------------------------
-
-struct Config {
-    const char* name;
-    int bm, bn, bk;
-    void (*kern[2][2])(GemmParams);   // guarded kernel, [op][vec]
-    void (*dma[2])(GemmParams);       // pipelined kernel, [op]; null if the configuration has none
-    void (*dma_bias[2])(GemmParams);  // pipelined kernel with the bias + activation epilogue, [op]
-    void (*dma_sgd)(GemmParams);      // pipelined NN kernel with the fused SGD step
-    void (*sk[2])(GemmParams);        // the same with the work cut evenly over a fixed grid, [op]
-    void (*fix)(GemmParams, int);     // ... and its fix-up kernel
-    int nstage;
-    int threads;
-    int waves_n;
-    // Fitted to measured times of the {64..8192}^3 grid with every CU busy (tune.py collect / fit):
-    // time of one CU = tiles x (2 bm bn k / (eff x peak per CU)) + rounds x round_s
-    // (separately for NN and NT: index = GemmOp)
-    float eff[2];                     // rate of the k loop as a fraction of the fp32 MFMA peak
-    float round_s[2];                 // seconds per round outside the k loop: first copies, result store
-    float eff_guarded[2];             // the same two for the guarded kernel (fitted with odd leading dimensions)
-    float round_guarded_s[2];
-    int max_wg;                       // workgroups per CU the launch allows (it sizes its LDS request to that)
-    // LDS bytes of the guarded kernel: two buffers of an A slab and a B slab (layouts as in the kernel)
-    size_t lds_bytes(int op) const
-    {
-        const size_t a = (size_t)bm * (bk + 4);
-        const size_t b = (op == OP_NT) ? (size_t)bn * (bk + 4) : (size_t)bk * (bn + 8);
-        return 2 * (a + b) * sizeof(float);
-    }
-    size_t lds_bytes_dma() const
-    {
-        const size_t ring = (size_t)nstage * (bm + bn) * bk * sizeof(float);
-        // epilogue patches: 16 rows x (wave tile width + 8) words per wave
-        const size_t waves = (size_t)threads / 64;
-        const size_t wn = (size_t)bn / (size_t)waves_n;
-        const size_t patches = waves * 16 * (wn + 8) * sizeof(float);
-        return ring > patches ? ring : patches;
-    }
-    // workgroups of the pipelined kernel that fit one CU (160 KB of LDS, 2048 threads, 512 VGPRs per lane slot)
-    int wg_per_cu() const
-    {
-        const int by_lds = (int)((160 * 1024) / lds_bytes_dma());
-        const int r = by_lds < max_wg ? by_lds : max_wg;
-        return r < 1 ? 1 : r;
-    }
-};
-
-// The pipelined kernel with a fused epilogue, or null for the 16-wide-slab configuration: there the
-// epilogue's arithmetic makes the compiler move all 128 accumulators from AGPRs to VGPRs in one block
-// at the loop exit, and the registers that takes no longer allow the two workgroups per CU the
-// configuration is rated for (its launches run the plain kernel and the separate pass instead).
-template <int BM, int BN, int BK, int WMV, int WNV, bool NT, int NS, int EPI>
-constexpr void (*epilogue_kernel())(GemmParams)
-{
-    if constexpr (BK == 16) return nullptr;
-    else return &gemm_dma_kernel<BM, BN, BK, WMV, WNV, NT, NS, EPI>;
-}
-
-#define MTNN_GUARDED(BM, BN, BK, WMV, WNV)                                                    \
-    {{gemm_kernel<BM, BN, BK, WMV, WNV, false, false>, gemm_kernel<BM, BN, BK, WMV, WNV, false, true>},   \
-     {gemm_kernel<BM, BN, BK, WMV, WNV, true, false>, gemm_kernel<BM, BN, BK, WMV, WNV, true, true>}}
-
-// pipelined kernel with NS slab buffers, and the guarded kernel (slab GBK) that serves what it cannot
-#define MTNN_CFG_DMA(BM, BN, BK, WMV, WNV, NS, GBK, MAXWG, EFF_NN, RND_NN, EFF_NT, RND_NT, GEFF_NN, GRND_NN, GEFF_NT, GRND_NT)                                    \
-    { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV "_dma" #NS "_x" #MAXWG, BM, BN, BK, MTNN_GUARDED(BM, BN, GBK, WMV, WNV), \
-      {gemm_dma_kernel<BM, BN, BK, WMV, WNV, false, NS>, gemm_dma_kernel<BM, BN, BK, WMV, WNV, true, NS>}, \
-      {epilogue_kernel<BM, BN, BK, WMV, WNV, false, NS, kEpiBiasAct>(), epilogue_kernel<BM, BN, BK, WMV, WNV, true, NS, kEpiBiasAct>()}, \
-      epilogue_kernel<BM, BN, BK, WMV, WNV, false, NS, kEpiSgd>(), \
-      {gemm_streamk_kernel<BM, BN, BK, WMV, WNV, false, NS>, gemm_streamk_kernel<BM, BN, BK, WMV, WNV, true, NS>}, \
-      streamk_fixup_kernel<BM, BN>, \
-      NS, WMV * WNV * 64, WNV, {EFF_NN, EFF_NT}, {RND_NN, RND_NT}, {GEFF_NN, GEFF_NT}, {GRND_NN, GRND_NT}, MAXWG }
-
-static const Config kConfigs[] = {
-    //           tile         waves stages    per CU   NN: eff, round      NT: eff, round       guarded kernel: NN, NT
-    // (0: NT carries NN's pair: since its epilogue stores straight from registers like NN's, the two measure
-    //  the same -- 143.4 TFLOP/s both at 8192 x 8192 x 1024, 122.2 / 122.3 at k = 256; its own fit, 0.943 and
-    //  13.3 us, dates from the staged epilogue)
-    MTNN_CFG_DMA(256, 256, 32, 4, 2, 2, 16,   1,   0.949f, 13.8e-6f,   0.949f, 13.8e-6f,   0.871f, 12.7e-6f, 0.842f, 11.5e-6f),  // 0: 8 waves of 64 x 128, 128 KB of LDS
-    // (1: the fits put it level with configuration 0 inside the grid; beyond it the narrower tile
-    //  re-reads more of A and falls behind -- NN 135 against 148 TFLOP/s at 65536^3, NT 139 against 148 at
-    //  65536 x 256 x 32768 and 146 against 149 at 16384^3 -- so both operations rate it just below)
-    MTNN_CFG_DMA(256, 128, 16, 2, 2, 3, 16,   2,   0.943f, 11.9e-6f,   0.937f, 12.8e-6f,   0.840f, 9.8e-6f, 0.848f, 10.6e-6f),  // 1: 4 waves of 128 x 64, 72 KB
-    MTNN_CFG_DMA(128, 128, 64, 4, 2, 2, 16,   1,   0.884f, 4.0e-6f,   0.886f, 3.7e-6f,   0.802f, 2.1e-6f, 0.776f, 2.0e-6f),   // 2: 8 waves of 32 x 64, 128 KB
-    MTNN_CFG_DMA(64, 64, 64, 2, 2, 2, 16,     2,   0.886f, 2.9e-6f,   0.865f, 2.2e-6f,   0.688f, 1.1e-6f, 0.680f, 1.1e-6f),   // 3: 4 waves of 32 x 32, 64 KB
-    MTNN_CFG_DMA(32, 256, 32, 1, 4, 2, 16,    2,   0.903f, 2.9e-6f,   0.892f, 3.0e-6f,   0.698f, 1.7e-6f, 0.621f, 2.0e-6f),   // 4: 4 waves of 32 x 64 (small m), 72 KB
-    MTNN_CFG_DMA(256, 32, 32, 4, 1, 2, 16,    2,   0.869f, 3.9e-6f,   0.885f, 3.0e-6f,   0.567f, 1.9e-6f, 0.535f, 1.4e-6f),   // 5: 4 waves of 64 x 32 (small n), 72 KB
-    MTNN_CFG_DMA(128, 256, 32, 2, 4, 2, 16,   1,   0.927f, 6.9e-6f,   0.926f, 6.8e-6f,   0.822f, 5.9e-6f, 0.795f, 4.0e-6f),   // 6: 8 waves of 64 x 64, 96 KB
-    MTNN_CFG_DMA(256, 128, 32, 4, 2, 2, 16,   1,   0.920f, 7.1e-6f,   0.925f, 7.2e-6f,   0.837f, 4.8e-6f, 0.805f, 4.5e-6f),   // 7: 8 waves of 64 x 64, 96 KB
-    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16,    2,   0.885f, 3.6e-6f,   0.910f, 2.7e-6f,   0.740f, 1.9e-6f, 0.728f, 2.0e-6f),   // 8: 4 waves of 64 x 32, 48 KB
-    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16,    2,   0.904f, 2.9e-6f,   0.913f, 2.7e-6f,   0.783f, 2.0e-6f, 0.743f, 1.8e-6f),   // 9: 4 waves of 32 x 64, 48 KB
-    MTNN_CFG_DMA(128, 128, 32, 2, 2, 2, 16,   2,   0.906f, 5.0e-6f,   0.933f, 5.3e-6f,   0.820f, 4.2e-6f, 0.789f, 4.3e-6f),   // 10: 4 waves of 64 x 64, 64 KB
-    MTNN_CFG_DMA(128, 64, 32, 2, 2, 2, 16,    3,   0.839f, 3.4e-6f,   0.897f, 2.1e-6f,   0.753f, 2.1e-6f, 0.734f, 2.3e-6f),   // 11: as 8, three per CU (small k)
-    MTNN_CFG_DMA(64, 128, 32, 2, 2, 2, 16,    3,   0.907f, 3.0e-6f,   0.898f, 2.4e-6f,   0.807f, 2.2e-6f, 0.745f, 1.9e-6f),   // 12: as 9, three per CU (small k)
-};
-constexpr int kNumConfigs = (int)(sizeof(kConfigs) / sizeof(kConfigs[0]));
-constexpr int kMaxSplits = 32;
-constexpr int kStreamK = -2;          // in place of a split count: cut the work evenly over a fixed grid
-constexpr int kSplitQuantum = kSplitQuantumDev;
-
-static std::atomic<long long> g_streamk_launches{0};
-long long gemm_streamk_launches() { return g_streamk_launches.load(); }
-static std::atomic<long long> g_fused_launches{0};
-long long gemm_fused_launches() { return g_fused_launches.load(); }
-
-int gemm_config_count() { return kNumConfigs; }
-const char* gemm_config_name(int cfg) { return (cfg >= 0 && cfg < kNumConfigs) ? kConfigs[cfg].name : nullptr; }
-
-// ---- scratch for split-k partial products -------------------------------------------------------
-//
-// One fixed-size buffer per (device, stream), allocated the first time a split-k launch needs it and
-// kept until the process ends; launches on one stream are ordered, so they can share it.  A launch
-// whose partials do not fit, or a ninth stream, simply runs without split-k.
-namespace {
-constexpr size_t kScratchBytes = 64u << 20;
-struct ScratchSlot { int dev; hipStream_t stream; float* ptr; };
-ScratchSlot g_scratch[8];
-int g_scratch_used = 0;
-std::mutex g_scratch_mutex;
-
-float* scratch_for(hipStream_t s)
-{
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
-    std::lock_guard<std::mutex> lock(g_scratch_mutex);
-    for (int i = 0; i < g_scratch_used; ++i)
-        if (g_scratch[i].dev == dev && g_scratch[i].stream == s) return g_scratch[i].ptr;
-    if (g_scratch_used == 8) return nullptr;
-    // never allocate under stream capture (it would invalidate the capture): the launch then runs
-    // without scratch, i.e. unsplit; a caller who wants the split paths in a graph warms the stream up first
-    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(s, &capturing) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
-    if (capturing != hipStreamCaptureStatusNone) return nullptr;
-    float* ptr = nullptr;
-    if (hipMalloc(&ptr, kScratchBytes) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
-    g_scratch[g_scratch_used++] = ScratchSlot{dev, s, ptr};
-    return ptr;
-}
-}  // namespace
-
-// ---- choice of configuration and split count ----------------------------------------------------
-//
-// A small cost model, evaluated for every configuration and split count; the cheapest wins, ties go
-// to the earlier (larger) configuration.  For a candidate: workgroups = tiles x splits are dealt
-// evenly to the 256 CUs; a CU works through its share at the configuration's fitted k-loop rate, less if
-// it holds fewer workgroups than it could overlap; every round of resident workgroups pays the
-// configuration's fitted time outside the k loop (first copies, result store);
-// split-k adds the traffic of writing and re-reading the partial products.  The choice depends only
-// on (op, m, n, k), never on timing, so results stay reproducible.
-struct Choice { int cfg; int splits; };
-
-static double predicted_seconds(const Config& c, int op, int m, int n, int k, int splits, bool pipelined)
-{
-    const double peak_cu = 157.3e12 / 256.0;
-    const long long tiles = (long long)((m + c.bm - 1) / c.bm) * ((n + c.bn - 1) / c.bn);
-    const long long wgs = tiles * splits;
-    const long long per_cu = (wgs + 255) / 256;
-    int kloc = (k + splits - 1) / splits;
-    kloc = ((kloc + kSplitQuantum - 1) / kSplitQuantum) * kSplitQuantum;
-    if (splits == 1) kloc = k;
-    const int occ = c.wg_per_cu();
-    // A CU works through its share `occ` workgroups at a time; when one is left over at the end it runs
-    // alone, and a single 4-wave workgroup keeps only one wave per SIMD busy (measured on one tile column,
-    // 64 x 128 tiles, k = 640: 19.7 us per tile two or three at a time, 23.6 us alone; two left over of
-    // three run at the full rate).
-    const double solo_tiles = (c.threads < 512 && per_cu % occ == 1) ? 1.0 : 0.0;
-    const double solo_rate = (occ >= 3 && per_cu > 1) ? 0.92 : 0.85;      // (21.6 us alone after rounds of three)
-    const double wg_flops = 2.0 * c.bm * c.bn * (double)kloc;
-    double t = ((double)per_cu - solo_tiles + solo_tiles / solo_rate) * wg_flops /
-               (peak_cu * (pipelined ? c.eff[op] : c.eff_guarded[op]));
-    // first copies + result store per round.  The 256 x 256 tile's figure was fitted on grids of at most
-    // four rounds, where all 256 workgroups store at the same moment; over more rounds they drift apart
-    // and the stores stop colliding (NN, k = 512, per round beyond the k loop: 11.7 us at 4 rounds, 7.5
-    // at 16, 4.8 at 64, 4.3 at 256).
-    const long long rounds = (per_cu + occ - 1) / occ;
-    double round_cost = pipelined ? c.round_s[op] : c.round_guarded_s[op];
-    if (pipelined && c.bm * c.bn >= 256 * 256 && rounds > 4) round_cost *= 0.36 + 0.64 * pow(4.0 / (double)rounds, 0.75);
-    t += round_cost * (double)rounds;
-    // HBM floor: operands once, result once
-    const double bytes = 4.0 * ((double)m * k + (double)n * k + (double)m * n);
-    if (t < bytes / 5.0e12) t = bytes / 5.0e12;
-    if (splits > 1) t += 2.0e-6 + 0.3e-6 * splits + 4.0 * (double)m * n * (splits + 2) / 4.0e12;
-    return t + 3.0e-6;
-}
-
-// Predicted time of the even cut (gemm_streamk_kernel + fix-up) for configuration c, or a huge value
-// where it cannot run.  Every workgroup gets the same number of k units, so the k-loop time is the
-// padded work spread over all CUs; a workgroup pays the time outside the k loop once per tile it
-// touches, and the fix-up kernel moves every cut tile's pieces once more.  The four weights are a
-// least-squares fit to 130 measured (shape, configuration) pairs (tune.py even-cut; mean error 5 %).
-static double predicted_seconds_even_cut(const Config& c, int op, int m, int n, int k)
-{
-    const double peak_cu = 157.3e12 / 256.0;
-    const long long tiles = (long long)((m + c.bm - 1) / c.bm) * ((n + c.bn - 1) / c.bn);
-    const int units_per_tile = (k + kSplitQuantum - 1) / kSplitQuantum;
-    const long long units = tiles * units_per_tile;
-    const int occ = c.wg_per_cu();
-    const int groups = 256 * occ;
-    if (units < groups || units >= 0x7fffffffLL) return 1e30;
-    if ((size_t)2 * groups * c.bm * c.bn * sizeof(float) > kScratchBytes) return 1e30;
-    // with fewer tiles than an eighth of the pieces, every tile is cut many times and the fix-up
-    // kernel (a few workgroups adding dozens of pieces each) dominates: measured 3x slower than split-k
-    if (tiles * 8 < groups) return 1e30;
-    const double units_per_wg = (double)units / groups;
-    const double main_s = units_per_wg * occ * 2.0 * c.bm * c.bn * kSplitQuantum / (peak_cu * c.eff[op]);
-    const double segments = units_per_wg / units_per_tile + 1.0;
-    const double cut_tiles = tiles < groups ? (double)tiles : (double)groups;
-    const double pieces = tiles < groups ? ((double)groups / tiles + 1.0 < 2.0 ? 2.0 : (double)groups / tiles + 1.0) : 2.0;
-    const double fix_bytes = cut_tiles * (pieces + 1.0) * c.bm * c.bn * 4.0;
-    return 1.04 * main_s + 1.01 * segments * c.round_s[op] + 0.41 * fix_bytes / 4.0e12 + 11.0e-6;
-}
-
-// pipelined: the operands allow the pipelined kernel; otherwise the guarded kernel's own rates are
-// used (and the even cut, which exists only in the pipelined kernel, is not considered)
-// epi_kind: the launch wants that epilogue fused.  A candidate that cannot fuse it (a configuration
-// without the fused instance, the even cut, a split weight gradient) is charged the separate pass over
-// C it would need: one more launch and two (bias, clamp) or three (update) trips of m x n words.
-static Choice choose(int op, int m, int n, int k, bool allow_split, bool pipelined = true, int epi_kind = kEpiNone)
-{
-    Choice best = {0, 1};
-    double best_t = 1e30;
-    const int o = (op == OP_NT) ? 1 : 0;
-    const bool epi = pipelined && epi_kind != kEpiNone;
-    const double pass_s = epi ? 4.5e-6 + (epi_kind == kEpiBiasAct ? 2.0 : 3.0) * (double)m * (double)n * 4.0 / 4.0e12 : 0.0;
-    for (int c = 0; c < kNumConfigs; ++c) {
-        for (int splits = 1; splits <= kMaxSplits; splits *= 2) {
-            if (splits > 1) {
-                if (!allow_split) break;
-                if ((size_t)m * n * splits * sizeof(float) > kScratchBytes) break;
-                if (k / splits < 2 * kSplitQuantum) break;
-            }
-            double t = predicted_seconds(kConfigs[c], o, m, n, k, splits, pipelined);
-            if (epi) {
-                const bool fuses = (epi_kind == kEpiBiasAct) ? (splits > 1 || kConfigs[c].dma_bias[o] != nullptr)
-                                                             : (splits == 1 && o == 0 && kConfigs[c].dma_sgd != nullptr);
-                if (!fuses) t += pass_s;
-            }
-            if (t < best_t * 0.999) { best_t = t; best = Choice{c, splits}; }
-        }
-    }
-    if (allow_split && pipelined) {
-        // the even cut, for the two configurations it was measured with (64 x 128 and 128 x 128 tiles,
-        // two per CU), and only where it promises 5 % or more: on 65 measured shapes (tune.py even-cut)
-        // it beat the best ordinary launch of all configurations and split counts on 19, by 2-10 %; this
-        // rule took it on 13, once wrongly (5 % slower)
-        double sk_t = best_t * 0.95;
-        for (int c = 9; c <= 10; ++c) {
-            const double t = predicted_seconds_even_cut(kConfigs[c], o, m, n, k) + pass_s;
-            if (t < sk_t) { sk_t = t; best = Choice{c, kStreamK}; }
-        }
-    }
-    return best;
-}
-
-int gemm_default_config(int op, int m, int n, int k) { return choose(op, m, n, k, true).cfg; }
-int gemm_default_splits(int op, int m, int n, int k) { return choose(op, m, n, k, true).splits; }
-
-int launch_gemm(hipStream_t s, int op, int cfg, int splits, int m, int n, int k,
-                const float* A, long lda, const float* B, long ldb, float* C, long ldc,
-                const Epilogue* epi, bool* fused)
-{
-    if (fused) *fused = false;
-    if (op != OP_NN && op != OP_NT) return (int)hipErrorInvalidValue;
-    const int kind = epi ? epi->kind : kEpiNone;
-    if (kind != kEpiNone && kind != kEpiBiasAct && kind != kEpiSgd) return (int)hipErrorInvalidValue;
-    // splits: >= 1 as given; kStreamK the even cut; any other value <= 0 leaves the choice to the rule
-    const bool free_splits = (splits <= 0 && splits != kStreamK);
-    const bool chunks16 = (lda % 4 == 0) && (ldb % 4 == 0) && (k % 4 == 0) && (op == OP_NT || n % 4 == 0) &&
-                          ((reinterpret_cast<uintptr_t>(A) & 15) == 0) && ((reinterpret_cast<uintptr_t>(B) & 15) == 0);
-    if (cfg < 0) {
-        const Choice ch = choose(op, m, n, k, free_splits, chunks16, kind);
-        cfg = ch.cfg;
-        if (free_splits) splits = ch.splits;
-    } else if (free_splits) {
-        splits = 1;
-    }
-    if (cfg >= kNumConfigs || splits > kMaxSplits) return (int)hipErrorInvalidValue;
-    const bool want_streamk = (splits == kStreamK);
-    if (splits < 1) splits = 1;
-    const Config& c = kConfigs[cfg];
-    GemmParams p;
-    p.A = A; p.B = B; p.C = C;
-    p.M = m; p.N = n; p.K = k;
-    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
-    p.tiles_m = (m + c.bm - 1) / c.bm;
-    p.tiles_n = (n + c.bn - 1) / c.bn;
-    p.group_m = p.tiles_m < 8 ? p.tiles_m : 8;
-    p.num_xcd = 8;
-    // split-k: equal k ranges, multiples of the quantum; drop splits that would be empty
-    p.splits = 1;
-    p.k_per_split = k;
-    p.part = nullptr;
-    p.sk_units_per_tile = 0;
-    p.bias = (kind == kEpiBiasAct) ? epi->bias : nullptr;
-    p.relu = (kind == kEpiBiasAct) ? epi->relu : 0;
-    p.W = (kind == kEpiSgd) ? epi->W : nullptr;
-    p.ldw = (kind == kEpiSgd) ? epi->ldw : 0;
-    p.lr = (kind == kEpiSgd) ? epi->lr : 0.f;
-    if (splits > 1) {
-        int kps = (k + splits - 1) / splits;
-        kps = ((kps + kSplitQuantum - 1) / kSplitQuantum) * kSplitQuantum;
-        const int eff_splits = (k + kps - 1) / kps;
-        if (eff_splits > 1 && (size_t)m * n * eff_splits * sizeof(float) <= kScratchBytes) {
-            float* part = scratch_for(s);
-            if (part) {
-                p.splits = eff_splits;
-                p.k_per_split = kps;
-                p.part = part;
-            }
-        }
-    }
-    const long long total = (long long)p.tiles_m * p.tiles_n * p.splits;
-    if (total > 0x7fffffffLL) return (int)hipErrorInvalidValue;
-    const bool vec = (lda % 4 == 0) && (ldb % 4 == 0) &&
-                     ((reinterpret_cast<uintptr_t>(A) & 15) == 0) &&
-                     ((reinterpret_cast<uintptr_t>(B) & 15) == 0);
-    // the pipelined kernel needs whole 16-byte chunks everywhere (see its preconditions) ...
-    // ... and per-lane byte offsets inside a tile that fit 32 bits
-    const unsigned long long lim = 1ull << 32;
-    const bool off_ok = (unsigned long long)c.bm * (unsigned long long)lda * 4ull < lim &&
-                        (op == OP_NT ? (unsigned long long)c.bn * (unsigned long long)ldb * 4ull < lim
-                                     : (unsigned long long)(c.bk + 1) * (unsigned long long)ldb * 4ull < lim);
-    const bool dma_ok = vec && c.dma[op] && (k % 4 == 0) && (op == OP_NT || n % 4 == 0) && off_ok;
-    if (want_streamk && dma_ok) {
-        // the even cut: 256 x (workgroups per CU) pieces, if there is at least one unit for each and
-        // the 2 x pieces scratch slots fit; otherwise the plain launch below
-        const int groups = 256 * c.wg_per_cu();
-        const int units_per_tile = (k + kSplitQuantum - 1) / kSplitQuantum;
-        const long long units = (long long)p.tiles_m * p.tiles_n * units_per_tile;
-        const size_t need = (size_t)2 * groups * c.bm * c.bn * sizeof(float);
-        float* part = (units >= groups && units < 0x7fffffffLL && need <= kScratchBytes) ? scratch_for(s) : nullptr;
-        if (part) {
-            p.part = part;
-            p.sk_units_per_tile = units_per_tile;
-            size_t lds_sk = c.lds_bytes_dma();
-            const size_t share = ((160 * 1024) / (size_t)c.wg_per_cu()) & ~(size_t)1023;
-            if (lds_sk < share - 1024) lds_sk = share - 1024;
-            static std::atomic<bool> raised_sk[kNumConfigs][2][16] = {};
-            int dev = 0;
-            if (hipGetDevice(&dev) != hipSuccess) return (int)hipGetLastError();
-            if (lds_sk > 64 * 1024 && (dev < 0 || dev >= 16 || !raised_sk[cfg][op][dev])) {
-                const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(c.sk[op]),
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-                if (e != hipSuccess) return (int)e;
-                if (dev >= 0 && dev < 16) raised_sk[cfg][op][dev] = true;
-            }
-            hipLaunchKernelGGL(c.sk[op], dim3((unsigned)groups), dim3(c.threads), lds_sk, s, p);
-            hipError_t err = hipGetLastError();
-            if (err != hipSuccess) return (int)err;
-            hipLaunchKernelGGL(c.fix, dim3((unsigned)(p.tiles_m * p.tiles_n * kFixChunks)), dim3(256), 0, s, p, groups);
-            ++g_streamk_launches;
-            return (int)hipGetLastError();
-        }
-    }
-    // A fused epilogue runs in the pipelined kernel's instance built for it (unsplit launches), or, for
-    // the bias + activation, in the reduction kernel of a split launch; anything else is left to the caller.
-    const bool fuse_reduce = (kind == kEpiBiasAct) && p.splits > 1;
-    const bool fuse_main = p.splits == 1 && dma_ok &&
-                           ((kind == kEpiBiasAct && c.dma_bias[op]) || (kind == kEpiSgd && op == OP_NN && c.dma_sgd));
-    auto kern = fuse_main ? (kind == kEpiBiasAct ? c.dma_bias[op] : c.dma_sgd)
-                          : dma_ok ? c.dma[op] : c.kern[op][vec ? 1 : 0];
-    Config guarded = c;
-    guarded.bk = 16;
-    size_t lds = dma_ok ? c.lds_bytes_dma() : guarded.lds_bytes(op);
-    if (dma_ok) {
-        // Ask for at least 1/want of the CU's LDS, want = the workgroups a CU should hold at a time (the
-        // configuration's limit, or fewer if the grid has fewer per CU): no CU can then take more than
-        // the cost model assumed, so a grid of exactly 256 x want workgroups spreads evenly instead of
-        // piling three on some CUs and one on others.
-        long long per_cu_wgs = (total + 255) / 256;
-        int want = c.wg_per_cu();
-        if (per_cu_wgs < want) want = (int)per_cu_wgs;
-        if (want < 1) want = 1;
-        const size_t share = ((160 * 1024) / (size_t)want) & ~(size_t)1023;
-        const size_t floor_bytes = share > 1024 ? share - 1024 : share;
-        if (lds < floor_bytes) lds = floor_bytes;
-    }
-    if (lds > 64 * 1024) {
-        // opt in to the large LDS carve-out once per kernel and device
-        static std::atomic<bool> raised[kNumConfigs][2][5][16] = {};   // (racing callers at worst set the attribute twice)
-        const int which = fuse_main ? 2 + kind : dma_ok ? 2 : (vec ? 1 : 0);
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return (int)hipGetLastError();
-        if (dev < 0 || dev >= 16 || !raised[cfg][op][which][dev]) {
-            // (to the whole 160 KB: the request below varies with the grid)
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            if (e != hipSuccess) return (int)e;
-            if (dev >= 0 && dev < 16) raised[cfg][op][which][dev] = true;
-        }
-    }
-    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(c.threads), lds, s, p);
-    hipError_t err = hipGetLastError();
-    if (err != hipSuccess) return (int)err;
-    if (p.splits > 1) {
-        const long long elems = (long long)m * n;
-        long long blocks = (elems + 255) / 256;
-        if (blocks > 2048) blocks = 2048;
-        if (fuse_reduce)
-            hipLaunchKernelGGL(reduce_splits_kernel<kEpiBiasAct>, dim3((unsigned)blocks), dim3(256), 0, s,
-                               p.part, p.splits, m, n, C, ldc, p.bias, p.relu);
-        else
-            hipLaunchKernelGGL(reduce_splits_kernel<kEpiNone>, dim3((unsigned)blocks), dim3(256), 0, s,
-                               p.part, p.splits, m, n, C, ldc, nullptr, 0);
-        err = hipGetLastError();
-    }
-    if (err == hipSuccess && (fuse_main || fuse_reduce)) {
-        ++g_fused_launches;
-        if (fused) *fused = true;
-    }
-    return (int)err;
-}
-
 }  // namespace mtnn

@@ -16,6 +16,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <memory>
+#include <atomic>
 #include <mutex>
 #include <string>
 
@@ -223,6 +224,9 @@ bool load_model(const char* path, Model& out)
 namespace {
 std::mutex g_model_mutex;
 std::shared_ptr<const Model> g_model;   // null = no model: always NT
+// Counts every change of the current predictor.  Memoised answers carry the count they were made
+// under: an address would not do, since a new model can be allocated where a freed one was.
+std::atomic<unsigned long long> g_model_generation{1};
 
 // first use: a model named by the environment variable MTNN_MODEL is loaded if nothing else has
 // been installed; a missing or malformed file leaves "always NT" in place
@@ -235,7 +239,10 @@ void load_from_env()
     if (!load_model(path, m)) return;
     auto p = std::make_shared<const Model>(std::move(m));
     std::lock_guard<std::mutex> lock(g_model_mutex);
-    if (!g_model) g_model = std::move(p);
+    if (!g_model) {
+        g_model = std::move(p);
+        g_model_generation.fetch_add(1, std::memory_order_release);
+    }
 }
 
 std::shared_ptr<const Model> current()
@@ -249,6 +256,7 @@ void install(Model&& m)
     auto p = std::make_shared<const Model>(std::move(m));
     std::lock_guard<std::mutex> lock(g_model_mutex);
     g_model = std::move(p);
+    g_model_generation.fetch_add(1, std::memory_order_release);
 }
 }  // namespace
 
@@ -269,16 +277,20 @@ int mtnn_features(int m, int n, int k, double* x)
 int mtnn_select(int m, int n, int k)
 {
     if (m <= 0 || n <= 0 || k <= 0) return 0;
-    // a one-entry memo: training loops repeat the same few shapes, and the hit path is three compares
-    struct Memo { int m, n, k, label; const void* model; };
-    static thread_local Memo memo = {0, 0, 0, 0, nullptr};
+    // a one-entry memo: training loops repeat the same few shapes, and the hit path is four compares.
+    // The generation is read before the model: an answer stored under an older count than the model
+    // it was computed from is at worst recomputed, never served for a newer model.
+    struct Memo { int m, n, k, label; unsigned long long generation; };
+    static thread_local Memo memo = {0, 0, 0, 0, 0};
+    std::call_once(mtnn::g_env_once, mtnn::load_from_env);
+    const unsigned long long gen = mtnn::g_model_generation.load(std::memory_order_acquire);
+    if (memo.generation == gen && memo.m == m && memo.n == n && memo.k == k) return memo.label;
     auto model = mtnn::current();
     if (!model || model->num_features != mtnn::kSelectorFeatures) return 1;
-    if (memo.model == model.get() && memo.m == m && memo.n == n && memo.k == k) return memo.label;
     double x[mtnn::kSelectorFeatures];
     mtnn::selector_features(m, n, k, x);
     const int label = mtnn::model_margin(*model, x) >= 0.0 ? 1 : -1;
-    memo = Memo{m, n, k, label, model.get()};
+    memo = Memo{m, n, k, label, gen};
     return label;
 }
 
@@ -321,6 +333,7 @@ void mtnn_unload_model(void)
 {
     std::lock_guard<std::mutex> lock(mtnn::g_model_mutex);
     mtnn::g_model.reset();
+    mtnn::g_model_generation.fetch_add(1, std::memory_order_release);
 }
 
 int mtnn_gbdt_train(int nrows, int nfeat, const double* X, const int* labels, int num_trees, int max_depth,

@@ -196,3 +196,72 @@ def test_cost_model_choice_is_valid_and_repeatable_over_many_shapes():
             if s > 1:
                 assert k // s >= 128 and m * n * s * 4 <= (64 << 20)
             assert (c, s) == (mt.mtnn_gemm_default_config(op, m, n, k), mt.mtnn_gemm_default_splits(op, m, n, k))
+
+
+def test_no_device_is_reported_not_a_launch_error(L):
+    """Without a usable gfx950 (this test runs where there is no GPU at all) a call with valid arguments
+    launches nothing and says so; validation errors still come first."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    assert L.mtnn_nt(None, 4, 6, 8, A, 8, B, 8, C, 6) == 9
+    assert L.mtnn_nn(None, 4, 6, 8, A, 8, B, 6, C, 6) == 9
+    assert L.mtnn_nt(None, 4, 6, 0, None, 1, None, 1, C, 6) == 9          # k = 0 still has to write zeros
+    assert L.mtnn_transpose(None, 4, 6, A, 6, B, 4) == 9
+    assert L.mtnn_transpose_inplace(None, 4, A, 4) == 9
+    assert L.mtnn_copy_bytes(None, 64, A, B) == 9
+    assert L.mtnn_tnn(None, 4, 6, 8, A, 8, B, 8, C, 6, W, 256) == 9
+    assert L.mtnn_nt(None, 4, 6, 8, A, 7, B, 8, C, 6) == 3                # a bad argument is still a bad argument
+    assert L.mtnn_set_scratch(None, 0x700000, 1 << 20) == 9               # scratch belongs to a device's stream
+    assert L.mtnn_get_scratch_bytes(None) == 0
+    assert "gfx950" in mt.mtnn_status_string(9)
+
+
+def test_architecture_test_on_names(L):
+    ok = [b"gfx950", b"gfx950:sramecc+:xnack-", b"gfx950:xnack-"]
+    bad = [b"gfx942", b"gfx942:sramecc+:xnack-", b"gfx90a", b"gfx9500", b"gfx95", b"", b"sm_90", b"gfx1100"]
+    assert all(L.mtnn_arch_supported(a) == 1 for a in ok)
+    assert all(L.mtnn_arch_supported(a) == 0 for a in bad)
+    assert L.mtnn_arch_supported(None) == 0
+
+
+def test_scratch_arguments_and_needs(L):
+    assert L.mtnn_set_scratch(None, None, 64) == 8                         # bytes without memory
+    assert L.mtnn_set_scratch(None, 0x700000, 0) == 8                      # memory without bytes
+    assert L.mtnn_set_scratch(None, 0x700010, 1 << 20) == 8                # not 256-byte aligned
+    assert L.mtnn_scratch_bytes_default() == 64 << 20
+    assert mt.mtnn_gemm_scratch_bytes(3, 4, 100, 200, 4096) == 100 * 200 * 4 * 4
+    assert mt.mtnn_gemm_scratch_bytes(3, 32, 100, 200, 130) == 100 * 200 * 4 * 3   # empty splits are dropped: 3 ranges of 64
+    assert mt.mtnn_gemm_scratch_bytes(3, 1, 100, 200, 4096) == 0
+    assert mt.mtnn_gemm_scratch_bytes(99, 4, 100, 200, 4096) == 0
+    # the even cut: two tile-sized slots per workgroup of the fixed grid (nominal device: 256 CUs x 2 per CU)
+    assert mt.mtnn_gemm_scratch_bytes(10, mt.EVEN_CUT, 1000, 900, 1100) == 2 * 512 * 128 * 128 * 4
+
+
+def test_choice_respects_the_scratch_capacity():
+    """The cost model only considers divisions whose partial products fit the scratch it is told about."""
+    import numpy as np
+    rng = np.random.default_rng(3192)
+    dims = np.exp(rng.uniform(np.log(16.0), np.log(2.0 ** 14), size=(400, 3))).astype(np.int64)
+    n_cfg = len(mt.gemm_configs())
+    saw_split = False
+    for m, n, k in dims:
+        m, n, k = int(m), int(n), int(k)
+        for op in (0, 1):
+            assert mt.mtnn_gemm_choice(op, m, n, k, 0)[1] == 1             # no scratch: unsplit launches only
+            for cap in (1 << 16, 1 << 22, 64 << 20):
+                c, s = mt.mtnn_gemm_choice(op, m, n, k, cap)
+                assert 0 <= c < n_cfg
+                if s != 1:
+                    saw_split = True
+                    assert 0 < mt.mtnn_gemm_scratch_bytes(c, s, m, n, k) <= cap
+            assert mt.mtnn_gemm_choice(op, m, n, k) == (mt.mtnn_gemm_default_config(op, m, n, k),
+                                                        mt.mtnn_gemm_default_splits(op, m, n, k))
+    assert saw_split
+
+
+def test_tnn_inplace_rejects_b_overlapping_a(L):
+    """B is written by the in-place path, so the Gram product A x A^T (A == B) must be refused."""
+    assert L.mtnn_tnn_inplace(None, 8, 8, 8, A, 8, A, 8, C, 8) == 4
+    assert L.mtnn_tnn_inplace(None, 4, 8, 8, A + 32 * 4, 8, A, 8, C, 8) == 4      # A inside B
+    assert L.mtnn_tnn_inplace(None, 8, 8, 8, A, 8, B, 8, C, 8) in (0, 6, 9)       # disjoint: passes validation

@@ -260,3 +260,28 @@ def test_classifier_study_runs_on_a_synthetic_table(tmp_path):
     g = rep["classifiers"]["GBDT (8 trees, depth 8)"]
     assert g["cv5_accuracy"] >= rep["classifiers"]["majority rule"]["cv5_accuracy"] - 0.02
     assert rep["training_size_curve"][-1]["accuracy_on_all"] >= rep["training_size_curve"][0]["accuracy_on_all"] - 0.01
+
+
+def test_memo_follows_the_model_through_retraining():
+    """mtnn_select memoises its last answer; the memo must die with the model it came from, also when a
+    later model happens to be allocated where an earlier one was (train A, train B, train C, querying
+    one shape under A and C only)."""
+    shapes = np.array([[m, n, k] for m in (64, 256, 1024, 4096) for n in (64, 256, 1024, 4096) for k in (64, 256, 1024, 4096)],
+                      dtype=np.int32)
+    probe = (1024, 1024, 1024)
+    all_nt = np.ones(len(shapes), dtype=np.int32)
+    all_tnn = -all_nt
+    try:
+        for round_ in range(6):
+            mt.mtnn_train_selector(shapes, all_nt)
+            assert mt.mtnn_select(*probe) == 1
+            mt.mtnn_train_selector(shapes, all_tnn)          # not queried with the probe shape
+            mt.mtnn_train_selector(shapes, all_tnn if round_ % 2 else all_nt)
+            mt.mtnn_train_selector(shapes, all_tnn)
+            assert mt.mtnn_select(*probe) == -1
+            mt.mtnn_unload_model()
+            assert mt.mtnn_select(*probe) == 1               # no model: NT
+    finally:
+        mt.mtnn_unload_model()
+        if os.path.exists(mt.DEFAULT_MODEL):
+            mt.mtnn_load_model(mt.DEFAULT_MODEL)
