@@ -191,6 +191,20 @@ MTNN_API int mtnn_gemm_default_config(int op, int m, int n, int k);
 MTNN_API int mtnn_gemm_default_splits(int op, int m, int n, int k);
 MTNN_API int mtnn_gemm_ex(void *stream, int op, int cfg, int splits, int m, int n, int k,
                  const float *A, int lda, const float *B, int ldb, float *C, int ldc);
+/* mtnn_gemm_ex for callers that cannot allocate device memory and have none to lend: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Arguments, validation,
+ * kernels and results are those of mtnn_gemm_ex on a stream with MTNN_STATIC_SCRATCH_BYTES lent, but
+ * the partial products of a divided launch live in an array inside the library's code object (one
+ * copy per GPU, held until the process ends) and whatever mtnn_set_scratch registered is ignored.
+ * The call allocates and frees nothing.  An explicit split count or even cut whose partials need
+ * more than MTNN_STATIC_SCRATCH_BYTES returns MTNN_ERR_WORKSPACE and launches nothing (ask
+ * mtnn_gemm_scratch_bytes beforehand); with cfg = -1 and splits = 0 the rule only considers what
+ * fits.  All calls on one GPU share that GPU's array -- on every stream -- so two such calls that
+ * overlap in time race on it: issue them on one stream, or order them yourself.  The first call on
+ * a device asks the runtime for the array's address there (no stream operation, no allocation). */
+#define MTNN_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+MTNN_API int mtnn_gemm_ex_static(void *stream, int op, int cfg, int splits, int m, int n, int k,
+                        const float *A, int lda, const float *B, int ldb, float *C, int ldc);
 MTNN_API int mtnn_set_scratch(void *stream, void *scratch, size_t bytes);
 MTNN_API size_t mtnn_get_scratch_bytes(void *stream);      /* registered for (current device, stream); 0 if none */
 MTNN_API size_t mtnn_scratch_bytes_default(void);

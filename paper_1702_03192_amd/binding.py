@@ -70,6 +70,7 @@ SIGNATURES = {
     "mtnn_gemm_default_config": (_c_int, [_c_int, _c_int, _c_int, _c_int]),
     "mtnn_gemm_default_splits": (_c_int, [_c_int, _c_int, _c_int, _c_int]),
     "mtnn_gemm_ex": (_c_int, [_c_vp, _c_int, _c_int, _c_int] + _GEMM[1:]),
+    "mtnn_gemm_ex_static": (_c_int, [_c_vp, _c_int, _c_int, _c_int] + _GEMM[1:]),
     "mtnn_set_scratch": (_c_int, [_c_vp, _c_vp, _c_sz]),
     "mtnn_get_scratch_bytes": (_c_sz, [_c_vp]),
     "mtnn_scratch_bytes_default": (_c_sz, []),
@@ -232,6 +233,16 @@ def mtnn_gemm_ex(op, cfg, A, B, C, stream=None, splits=0):
     m, k = A.shape
     n = B.shape[0] if op == OP_NT else B.shape[1]
     _check(lib().mtnn_gemm_ex(_stream(stream), op, cfg, splits, m, n, k, pa, lda, pb, ldb, pc, ldc), "mtnn_gemm_ex")
+    return C
+
+
+def mtnn_gemm_ex_static(op, cfg, A, B, C, stream=None, splits=0):
+    """mtnn_gemm_ex with the library's own static scratch (32 MiB per GPU): allocates nothing."""
+    (pa, lda), (pb, ldb), (pc, ldc) = _dev(A, "A"), _dev(B, "B"), _dev(C, "C")
+    m, k = A.shape
+    n = B.shape[0] if op == OP_NT else B.shape[1]
+    _check(lib().mtnn_gemm_ex_static(_handle(stream) or None, op, cfg, splits, m, n, k, pa, lda, pb, ldb, pc, ldc),
+           "mtnn_gemm_ex_static")
     return C
 
 

@@ -65,10 +65,10 @@ int check_gemm(int op, int m, int n, int k, const float* A, int lda, const float
 }
 
 // epi: work to fuse into the product where the launch can, done as a separate pass over C where it cannot
-// scratch: where a split launch keeps its partial products; null = what the caller registered for the stream
+// provider: where a divided launch keeps its partial products; null = what the caller registered for the stream
 int run_gemm(void* stream, int op, int cfg, int splits, int m, int n, int k, const float* A, int lda,
              const float* B, int ldb, float* C, int ldc, const mtnn::Epilogue* epi = nullptr,
-             const mtnn::Scratch* scratch = nullptr)
+             mtnn::ScratchProvider provider = nullptr)
 {
     const int st = check_gemm(op, m, n, k, A, lda, B, ldb, C, ldc);
     if (st != MTNN_OK) return st;
@@ -78,9 +78,19 @@ int run_gemm(void* stream, int op, int cfg, int splits, int m, int n, int k, con
     hipStream_t s = static_cast<hipStream_t>(stream);
     int err;
     bool fused = false;
-    if (k == 0) err = mtnn::launch_fill_zero(s, m, n, C, ldc);
-    else err = mtnn::launch_gemm(s, geo, scratch ? *scratch : mtnn::scratch_lookup(s), op, cfg, splits, m, n, k,
-                                 A, lda, B, ldb, C, ldc, g_fuse_epilogues.load() ? epi : nullptr, &fused);
+    if (k == 0) {
+        err = mtnn::launch_fill_zero(s, m, n, C, ldc);
+    } else {
+        mtnn::Scratch scratch;
+        if (provider) {
+            const int ps = provider(&scratch);
+            if (ps != MTNN_OK) return ps;
+        } else {
+            scratch = mtnn::scratch_lookup(s);
+        }
+        err = mtnn::launch_gemm(s, geo, scratch, op, cfg, splits, m, n, k, A, lda, B, ldb, C, ldc,
+                                g_fuse_epilogues.load() ? epi : nullptr, &fused);
+    }
     if (err == 0 && epi && !fused) {
         if (epi->kind == 1) err = mtnn::launch_bias_act(s, m, n, C, ldc, epi->bias, epi->relu);
         else err = mtnn::launch_sgd_2d(s, m, n, epi->W, epi->ldw, C, ldc, epi->lr);
@@ -141,6 +151,17 @@ int check_transpose(int rows, int cols, const float* in, int ldin, const float* 
 
 }  // namespace
 
+namespace mtnn {
+int gemm_ex_entry(void* stream, int op, int cfg, int splits, int m, int n, int k, const float* A, int lda,
+                  const float* B, int ldb, float* C, int ldc, ScratchProvider provider)
+{
+    if ((op != OP_NN && op != OP_NT) || cfg < -1 || cfg >= gemm_config_count() ||
+        (splits < 0 && splits != MTNN_GEMM_EVEN_CUT) || splits > 32)
+        return MTNN_ERR_ARG;
+    return run_gemm(stream, op, cfg, splits, m, n, k, A, lda, B, ldb, C, ldc, nullptr, provider);
+}
+}  // namespace mtnn
+
 extern "C" {
 
 int mtnn_nt(void* stream, int m, int n, int k, const float* A, int lda, const float* B, int ldb,
@@ -158,10 +179,7 @@ int mtnn_nn(void* stream, int m, int n, int k, const float* A, int lda, const fl
 int mtnn_gemm_ex(void* stream, int op, int cfg, int splits, int m, int n, int k, const float* A, int lda,
                  const float* B, int ldb, float* C, int ldc)
 {
-    if ((op != mtnn::OP_NN && op != mtnn::OP_NT) || cfg < -1 || cfg >= mtnn::gemm_config_count() ||
-        (splits < 0 && splits != MTNN_GEMM_EVEN_CUT) || splits > 32)
-        return MTNN_ERR_ARG;
-    return run_gemm(stream, op, cfg, splits, m, n, k, A, lda, B, ldb, C, ldc);
+    return mtnn::gemm_ex_entry(stream, op, cfg, splits, m, n, k, A, lda, B, ldb, C, ldc, nullptr);
 }
 
 int mtnn_gemm_default_splits(int op, int m, int n, int k)

@@ -61,6 +61,12 @@ constexpr int kErrScratch = -1000;     // not a hipError_t: the launch needs mor
 int launch_gemm(hipStream_t s, const Geometry& geo, const Scratch& scratch, int op, int cfg, int splits, int m, int n, int k,
                 const float* A, long lda, const float* B, long ldb, float* C, long ldc,
                 const Epilogue* epi = nullptr, bool* fused = nullptr);
+// Argument validation and dispatch of mtnn_gemm_ex (api.cpp).  provider: called after validation,
+// with the device known to be usable, for the scratch a divided launch may use (it returns an MTNN
+// status); null = the scratch registered for the stream.
+typedef int (*ScratchProvider)(Scratch* out);
+int gemm_ex_entry(void* stream, int op, int cfg, int splits, int m, int n, int k, const float* A, int lda,
+                  const float* B, int ldb, float* C, int ldc, ScratchProvider provider);
 int gemm_config_count();
 long long gemm_streamk_launches();
 long long gemm_fused_launches();
