@@ -6,4 +6,4 @@ imports nothing from the product package.  The arithmetic lives in
 ``mtnn_oracle.c`` (dense operations), ``selection.py`` (label rule, metrics,
 boosted trees) and ``fc.py`` (one training step of a fully connected net).
 """
-from .gemm import nt_ref, nn_ref, transpose_ref, tnn_ref, num_threads  # noqa: F401
+from .gemm import nt_ref, nn_ref, transpose_ref, tnn_ref, num_threads, nt_f64, nn_f64, tn_f64  # noqa: F401

@@ -30,6 +30,10 @@ def _load():
                                              ctypes.c_void_p, ctypes.c_long]
         lib.oracle_transpose_ref.restype = None
         lib.oracle_num_threads.restype = ctypes.c_int
+        for name in ("oracle_f64_nt", "oracle_f64_nn", "oracle_f64_tn"):
+            fn = getattr(lib, name)
+            fn.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 3
+            fn.restype = None
         _lib = lib
     return _lib
 
@@ -110,3 +114,43 @@ def transpose_ref(X, ldout=None, fill=np.nan):
 def tnn_ref(A, B, rows=None, with_bound=False):
     """Algorithm 1 on the CPU: transpose B, then the NN product.  Used to test the oracle against itself."""
     return nn_ref(A, np.ascontiguousarray(transpose_ref(B)), rows=rows, with_bound=with_bound)
+
+
+def _f64(x, name):
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    if x.ndim != 2:
+        raise ValueError(f"{name} must be 2-D")
+    return x
+
+
+def nt_f64(A, B):
+    """A x B^T (Eq. 2) on float64 operands: A m x k, B n x k."""
+    A, B = _f64(A, "A"), _f64(B, "B")
+    if A.shape[1] != B.shape[1]:
+        raise ValueError("A and B must have the same number of columns (k)")
+    C = np.zeros((A.shape[0], B.shape[0]), dtype=np.float64)
+    if C.size:
+        _load().oracle_f64_nt(A.shape[0], B.shape[0], A.shape[1], A.ctypes.data, B.ctypes.data, C.ctypes.data)
+    return C
+
+
+def nn_f64(A, B):
+    """A x B (Eq. 1) on float64 operands: A m x k, B k x n."""
+    A, B = _f64(A, "A"), _f64(B, "B")
+    if A.shape[1] != B.shape[0]:
+        raise ValueError("A columns must equal B rows (k)")
+    C = np.zeros((A.shape[0], B.shape[1]), dtype=np.float64)
+    if C.size:
+        _load().oracle_f64_nn(A.shape[0], B.shape[1], A.shape[1], A.ctypes.data, B.ctypes.data, C.ctypes.data)
+    return C
+
+
+def tn_f64(A, B):
+    """A^T x B on float64 operands: A k x m, B k x n, the sum running over the shared row index."""
+    A, B = _f64(A, "A"), _f64(B, "B")
+    if A.shape[0] != B.shape[0]:
+        raise ValueError("A and B must have the same number of rows (k)")
+    C = np.zeros((A.shape[1], B.shape[1]), dtype=np.float64)
+    if C.size:
+        _load().oracle_f64_tn(A.shape[1], B.shape[1], A.shape[0], A.ctypes.data, B.ctypes.data, C.ctypes.data)
+    return C

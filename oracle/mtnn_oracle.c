@@ -105,3 +105,47 @@ void oracle_transpose_ref(int nrows, int ncols,
         for (long c = 0; c < ncols; ++c)
             out[c * ldout + r] = in[r * ldin + c];
 }
+
+/* The same two definitions on DOUBLE operands, for the training-step oracle (whose activations and
+ * gradients are doubles, not floats): every C[i][j] is the definition's sum taken in increasing
+ * order of the summation index, one term at a time.  All matrices dense row-major.
+ *   nt:  C[i][j] = sum_l A[i][l] * B[j][l]     A m x k, B n x k   (Eq. 2: a layer's forward product)
+ *   nn:  C[i][j] = sum_l A[i][l] * B[l][j]     A m x k, B k x n   (Eq. 1: the gradient w.r.t. a layer's input)
+ *   tn:  C[i][j] = sum_r A[r][i] * B[r][j]     A k x m, B k x n   (Eq. 1 applied to A^T: the weight gradient,
+ *                                                                  summed over the mini-batch index r) */
+void oracle_f64_nt(int m, int n, int k, const double *A, const double *B, double *C)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int i = 0; i < m; ++i)
+        for (long j = 0; j < n; ++j) {
+            double acc = 0.0;
+            for (long l = 0; l < k; ++l) acc += A[(size_t)i * k + l] * B[(size_t)j * k + l];
+            C[(size_t)i * n + j] = acc;
+        }
+}
+
+void oracle_f64_nn(int m, int n, int k, const double *A, const double *B, double *C)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int i = 0; i < m; ++i) {
+        double *row = C + (size_t)i * n;
+        for (long j = 0; j < n; ++j) row[j] = 0.0;
+        for (long l = 0; l < k; ++l) {            /* element j of the row still gets its terms in increasing l */
+            double a = A[(size_t)i * k + l];
+            for (long j = 0; j < n; ++j) row[j] += a * B[(size_t)l * n + j];
+        }
+    }
+}
+
+void oracle_f64_tn(int m, int n, int k, const double *A, const double *B, double *C)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int i = 0; i < m; ++i) {
+        double *row = C + (size_t)i * n;
+        for (long j = 0; j < n; ++j) row[j] = 0.0;
+        for (long r = 0; r < k; ++r) {            /* ... in increasing r */
+            double a = A[(size_t)r * m + i];
+            for (long j = 0; j < n; ++j) row[j] += a * B[(size_t)r * n + j];
+        }
+    }
+}

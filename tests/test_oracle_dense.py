@@ -163,3 +163,34 @@ def test_transpose_vectors_and_padding():
     base = T.base if T.base is not None else T
     assert np.all(np.asarray(base)[:, 4:] == -7.0)                      # output padding untouched
     assert oracle.transpose_ref(np.zeros((0, 3), np.float32)).shape == (3, 0)
+
+
+def test_float64_products_against_hand_expansion_and_an_independent_routine():
+    """The double-operand products the training-step oracle uses (Eq. 2 forward, Eq. 1 backward, and
+    Eq. 1 on a transposed left operand): a hand-expanded 2 x 3 x 2 case each, exact integer inputs,
+    and numpy's matmul as an independent routine within fp64 rounding."""
+    A = np.array([[1.0, 2.0], [3.0, 4.0]])                      # 2 x 2
+    B = np.array([[5.0, 6.0], [7.0, 8.0], [9.0, 10.0]])         # 3 x 2
+    assert oracle.nt_f64(A, B).tolist() == [[1 * 5 + 2 * 6, 1 * 7 + 2 * 8, 1 * 9 + 2 * 10],
+                                            [3 * 5 + 4 * 6, 3 * 7 + 4 * 8, 3 * 9 + 4 * 10]]
+    Bn = np.array([[5.0, 6.0, 7.0], [8.0, 9.0, 10.0]])          # 2 x 3
+    assert oracle.nn_f64(A, Bn).tolist() == [[1 * 5 + 2 * 8, 1 * 6 + 2 * 9, 1 * 7 + 2 * 10],
+                                             [3 * 5 + 4 * 8, 3 * 6 + 4 * 9, 3 * 7 + 4 * 10]]
+    # tn: A is k x m = 2 x 2 (rows are the summed index), B is k x n = 2 x 3: C[i][j] = sum_r A[r][i] B[r][j]
+    assert oracle.tn_f64(A, Bn).tolist() == [[1 * 5 + 3 * 8, 1 * 6 + 3 * 9, 1 * 7 + 3 * 10],
+                                             [2 * 5 + 4 * 8, 2 * 6 + 4 * 9, 2 * 7 + 4 * 10]]
+    rng = np.random.RandomState(5)
+    Ai = rng.randint(-9, 10, size=(17, 23)).astype(np.float64)
+    Bi = rng.randint(-9, 10, size=(11, 23)).astype(np.float64)
+    assert np.array_equal(oracle.nt_f64(Ai, Bi), (Ai.astype(np.int64) @ Bi.astype(np.int64).T).astype(np.float64))
+    assert np.array_equal(oracle.nn_f64(Ai, Bi.T), oracle.nt_f64(Ai, Bi))          # same terms, same order
+    assert np.array_equal(oracle.tn_f64(Ai.T, Bi.T), oracle.nt_f64(Ai, Bi))
+    Ar, Br = rng.normal(size=(33, 70)), rng.normal(size=(45, 70))
+    bound = 70 * 2.0 ** -52 * (np.abs(Ar) @ np.abs(Br).T)
+    assert (np.abs(oracle.nt_f64(Ar, Br) - Ar @ Br.T) <= bound).all()
+    assert (np.abs(oracle.nn_f64(Ar, Br.T) - Ar @ Br.T) <= bound).all()
+    assert (np.abs(oracle.tn_f64(Ar.T, Br.T) - Ar @ Br.T) <= bound).all()
+    # the float32-operand routines are the same sums: widening the operands first changes nothing
+    A32, B32 = Ar.astype(np.float32), Br.astype(np.float32)
+    assert np.array_equal(oracle.nt_f64(A32, B32), oracle.nt_ref(A32, B32))
+    assert oracle.nt_f64(np.zeros((0, 4)), np.zeros((3, 4))).shape == (0, 3)
