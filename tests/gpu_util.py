@@ -62,3 +62,22 @@ def check_gemm(C_gpu, C_ref, S_ref, k, what=""):
     assert comp <= tol(k), f"{what}: componentwise error {comp:.3e} > {tol(k):.3e}"
     assert norm <= tol(k), f"{what}: normwise error {norm:.3e} > {tol(k):.3e}"
     return comp, norm
+
+
+def check_gemm_on_device(C_dev, C_ref, S_ref, k, what=""):
+    """check_gemm for large results: the same two readings of the tolerance, with the elementwise
+    comparison arithmetic (subtract, divide, max -- nothing of the method) done by torch in float64 on
+    the device instead of numpy on the host.  C_dev: fp32 device tensor; C_ref, S_ref: the oracle's
+    float64 host arrays."""
+    import torch
+    assert tuple(C_dev.shape) == C_ref.shape, what
+    got = C_dev.double()
+    assert bool(torch.isfinite(got).all()), f"{what}: non-finite output"
+    ref = torch.from_numpy(np.ascontiguousarray(C_ref)).cuda()
+    s = torch.from_numpy(np.ascontiguousarray(S_ref)).cuda()
+    diff = (got - ref).abs_()
+    norm = float(diff.max() / ref.abs().max().clamp_min(1e-300)) if diff.numel() else 0.0
+    comp = float((diff / torch.where(s > 0, s, torch.ones_like(s))).max()) if diff.numel() else 0.0
+    assert comp <= tol(k), f"{what}: componentwise error {comp:.3e} > {tol(k):.3e}"
+    assert norm <= tol(k), f"{what}: normwise error {norm:.3e} > {tol(k):.3e}"
+    return comp, norm

@@ -193,6 +193,42 @@ def test_config4_skinny_and_irregular(shape, seed):
     check_all_paths(*shape, seed, "normal")
 
 
+@pytest.mark.parametrize("shape,seed", zip(I.CONFIG4["shapes"], I.CONFIG4["seeds"]))
+def test_config4_full_size_with_leading_dimensions_padded_by_three(shape, seed):
+    """The skinny and irregular shapes once more with every leading dimension = width + 3 (rows no longer
+    16-byte aligned: the guarded kernels), NaN in the operands' padding and canaries around and inside C."""
+    import torch
+    m, n, k = shape
+    A, B = I.nt_operands(m, n, k, seed, "normal")
+    C, S = oracle.nt_ref(A, B, with_bound=True)
+    dA, dB = dev_matrix(A, k + 3), dev_matrix(B, k + 3)
+    ws = torch.empty(mt.mtnn_tnn_workspace_bytes(n, k), dtype=torch.uint8, device="cuda")
+    results = {}
+    for name in ("nt", "tnn", "auto"):
+        out = Guarded(m, n, n + 3)
+        if name == "nt":
+            mt.mtnn_nt(dA, dB, out.view)
+        elif name == "tnn":
+            mt.mtnn_tnn(dA, dB, out.view, ws)
+        else:
+            assert mt.mtnn_auto(dA, dB, out.view, ws) == mt.mtnn_select(m, n, k)
+        sync()
+        got, intact = out.host()
+        assert intact, f"{name}: wrote into the padding of C or outside it"
+        check_gemm(got, C, S, k, f"{name} ld+3 {m}x{n}x{k}")
+        results[name] = got
+    bt = ws[: n * k * 4].view(torch.float32).view(k, n).cpu().numpy()
+    assert bt.tobytes() == np.ascontiguousarray(B.T).tobytes()
+    # NN alone on a padded B^T as well (ldb = n + 3)
+    Bt = np.ascontiguousarray(B.T)
+    out = Guarded(m, n, n + 3)
+    mt.mtnn_nn(dA, dev_matrix(Bt, n + 3), out.view)
+    sync()
+    got, intact = out.host()
+    assert intact
+    check_gemm(got, C, S, k, f"nn ld+3 {m}x{n}x{k}")
+
+
 def test_auto_without_workspace_runs_nt():
     A, B = I.nt_operands(128, 128, 128, 9)
     dA, dB = dev_matrix(A), dev_matrix(B)
