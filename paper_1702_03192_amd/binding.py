@@ -302,6 +302,69 @@ def mtnn_auto(A, B, C, workspace=None, stream=None) -> int:
     return chosen.value
 
 
+# ---- prepared calls ------------------------------------------------------------------------
+
+class Prepared:
+    """One library call with every argument resolved beforehand: pointers, leading dimensions, sizes and
+    the stream are taken from the tensors once, so that calling the object is a single ctypes call.
+    For loops that issue the same call many times (training steps, timing batches): the wrappers above
+    spend several microseconds per call on tensor checks and the stream lookup, which is more than a
+    small product takes on the GPU.  The object keeps its tensors alive; it must not outlive the
+    stream it was prepared for."""
+    __slots__ = ("_fn", "_args", "_name", "_keep", "_chosen")
+
+    def __init__(self, name, args, keep, chosen=None):
+        self._fn = getattr(lib(), name)
+        self._args = args
+        self._name = name
+        self._keep = keep
+        self._chosen = chosen
+
+    def __call__(self):
+        status = self._fn(*self._args)
+        if status:
+            _check(status, self._name)
+        return self._chosen.value if self._chosen is not None else None
+
+
+def _gemm_args(op, A, B, C, stream):
+    (pa, lda), (pb, ldb), (pc, ldc) = _dev(A, "A"), _dev(B, "B"), _dev(C, "C")
+    m, k = A.shape
+    n = B.shape[0] if op == OP_NT else B.shape[1]
+    if (B.shape[1] if op == OP_NT else B.shape[0]) != k or tuple(C.shape) != (m, n):
+        raise ValueError("shape mismatch")
+    return (_stream(stream), m, n, k, pa, lda, pb, ldb, pc, ldc)
+
+
+def prepare_nt(A, B, C, stream=None) -> Prepared:
+    return Prepared("mtnn_nt", _gemm_args(OP_NT, A, B, C, stream), (A, B, C))
+
+
+def prepare_nn(A, B, C, stream=None) -> Prepared:
+    return Prepared("mtnn_nn", _gemm_args(OP_NN, A, B, C, stream), (A, B, C))
+
+
+def prepare_tnn(A, B, C, workspace, stream=None) -> Prepared:
+    pw, wb = _ws(workspace)
+    return Prepared("mtnn_tnn", _gemm_args(OP_NT, A, B, C, stream) + (pw, wb), (A, B, C, workspace))
+
+
+def prepare_auto(A, B, C, workspace=None, stream=None) -> Prepared:
+    """Calling the result runs Algorithm 2 and returns the label of the path taken."""
+    pw, wb = _ws(workspace)
+    chosen = ctypes.c_int(0)
+    return Prepared("mtnn_auto", _gemm_args(OP_NT, A, B, C, stream) + (pw, wb, ctypes.byref(chosen)),
+                    (A, B, C, workspace), chosen)
+
+
+def prepare_transpose(X, out, stream=None) -> Prepared:
+    (pi, ldi), (po, ldo) = _dev(X, "in"), _dev(out, "out")
+    rows, cols = X.shape
+    if tuple(out.shape) != (cols, rows):
+        raise ValueError("shape mismatch")
+    return Prepared("mtnn_transpose", (_stream(stream), rows, cols, pi, ldi, po, ldo), (X, out))
+
+
 # ---- selection ----------------------------------------------------------------------------
 
 def mtnn_select(m: int, n: int, k: int) -> int:

@@ -70,9 +70,10 @@ def main(argv=None):
         for _ in range(min(2000, int(50.0 / max(a.elapsed_time(b), 1e-3)))):
             mt.mtnn_nt(A, B, C)
         torch.cuda.synchronize()
-        t_nt, _ = _time_batches(lambda: mt.mtnn_nt(A, B, C), stream, samples, 2000.0)
-        t_tnn, _ = _time_batches(lambda: mt.mtnn_tnn(A, B, C, ws), stream, samples, 2000.0)
-        t_auto, _ = _time_batches(lambda: mt.mtnn_auto(A, B, C, ws), stream, samples, 2000.0)
+        # prepared calls (arguments resolved once, one ctypes call per launch): what a training loop would hold
+        t_nt, _ = _time_batches(mt.prepare_nt(A, B, C), stream, samples, 2000.0)
+        t_tnn, _ = _time_batches(mt.prepare_tnn(A, B, C, ws), stream, samples, 2000.0)
+        t_auto, _ = _time_batches(mt.prepare_auto(A, B, C, ws), stream, samples, 2000.0)
         label = mt.mtnn_select(m, n, k)
         fl = 2.0 * m * n * k
         roof = roofline_seconds(m, n, k)
@@ -116,13 +117,14 @@ def main(argv=None):
         nsets = int(max(1, min(64, -(-(1 << 30) // int(pair_bytes)))))
         Xs = [torch.rand((rows, cols), device="cuda") for _ in range(nsets)]
         Ys = [torch.empty((cols, rows), device="cuda") for _ in range(nsets)]
-        t, tmin = _time_batches(lambda: mt.mtnn_transpose(Xs[0], Ys[0]), stream, args.samples, 2000.0)
+        calls = [mt.prepare_transpose(x, y) for x, y in zip(Xs, Ys)]
+        t, tmin = _time_batches(calls[0], stream, args.samples, 2000.0)
         turn = [0]
 
         def rotating():
             i = turn[0]
             turn[0] = (i + 1) % nsets
-            mt.mtnn_transpose(Xs[i], Ys[i])
+            calls[i]()
 
         t_rot, _ = _time_batches(rotating, stream, args.samples, 2000.0)
         report["transposes"].append({"rows": rows, "cols": cols, "t_us": t * 1e6, "gbs": pair_bytes / t / 1e9,
@@ -133,7 +135,7 @@ def main(argv=None):
                                      "frac_of_peak_rotating": pair_bytes / t_rot / 1e9 / PEAK_GBS})
         print(f"[report] transpose {rows}x{cols}: {pair_bytes / t / 1e9:.0f} GB/s on one buffer pair, "
               f"{pair_bytes / t_rot / 1e9:.0f} GB/s rotating over {nsets}", flush=True)
-        del Xs, Ys
+        del Xs, Ys, calls
     src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     dst = torch.empty_like(src)
     t, _ = _time_batches(lambda: mt.mtnn_copy_bytes(src, dst), stream, args.samples, 2000.0)
@@ -164,25 +166,27 @@ def main(argv=None):
 
     if args.grid_verify:
         rows = []
-        worse = 0
+        worse = worse_1pct = worse_strict = 0
         for (m, n, k, seed) in inputs.sweep_shapes():
             r = time_shape(m, n, k, seed, "uniform", max(8, args.samples // 2))
             rows.append(r)
-            if r["t_auto_us"] > max(r["t_nt_us"], r["t_tnn_us"]) * 1.03:
-                worse += 1
+            slowest = max(r["t_nt_us"], r["t_tnn_us"])
+            worse += r["t_auto_us"] > slowest * 1.03
+            worse_1pct += r["t_auto_us"] > slowest * 1.01
+            worse_strict += r["t_auto_us"] > slowest
         p_nt = [r["nt_gflops"] for r in rows]
         p_tnn = [r["tnn_gflops"] for r in rows]
         p_m = [r["mtnn_gflops"] for r in rows]
         gow = [(pm - min(a, b)) / min(a, b) for pm, a, b in zip(p_m, p_nt, p_tnn)]
         lub = [(pm - max(a, b)) / max(a, b) for pm, a, b in zip(p_m, p_nt, p_tnn)]
         report["grid_verify"] = {
-            "shapes": len(rows), "auto_slower_than_worse_by_3pct": worse,
+            "shapes": len(rows), "auto_slower_than_worse_strict": worse_strict,
+            "auto_slower_than_worse_by_1pct": worse_1pct, "auto_slower_than_worse_by_3pct": worse,
             "measured_gow_avg": statistics.mean(gow), "measured_gow_max": max(gow),
             "measured_lub_avg": statistics.mean(lub), "measured_lub_min": min(lub),
             "mtnn_vs_nt_avg": statistics.mean((pm - a) / a for pm, a in zip(p_m, p_nt)),
             "mtnn_vs_tnn_avg": statistics.mean((pm - b) / b for pm, b in zip(p_m, p_tnn)),
-            # calls shorter than ~20 us are bound by the launch path, where mtnn_auto's Python wrapper
-            # (two more arguments, the returned label) costs a few tenths of a microsecond more than mtnn_nt's
+            # (calls shorter than ~20 us are bound by the launch path)
             "mtnn_vs_nt_avg_calls_over_20us": statistics.mean((r["mtnn_gflops"] - r["nt_gflops"]) / r["nt_gflops"]
                                                               for r in rows if r["t_nt_us"] >= 20.0),
             "labels_nt": sum(1 for r in rows if r["label"] == 1), "labels_tnn": sum(1 for r in rows if r["label"] == -1),

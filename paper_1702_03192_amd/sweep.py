@@ -147,14 +147,15 @@ def collect(out_path, samples, min_batch_us, limit=None, grid="bench", budget_s=
                 mt.mtnn_tnn(A, B, C, w)
                 del w
 
-            t_nt, t_nt_min = _time_batches(lambda: mt.mtnn_nt(A, B, C), stream, samples, min_batch_us, budget_s)
-            t_tnn, t_tnn_min = _time_batches(lambda: mt.mtnn_tnn(A, B, C, ws), stream, samples, min_batch_us, budget_s)
-            t_tr, _ = _time_batches(lambda: mt.mtnn_transpose(B, Bt), stream, samples, min_batch_us, budget_s)
+            # (prepared calls: arguments resolved once, one ctypes call per launch)
+            t_nt, t_nt_min = _time_batches(mt.prepare_nt(A, B, C), stream, samples, min_batch_us, budget_s)
+            t_tnn, t_tnn_min = _time_batches(mt.prepare_tnn(A, B, C, ws), stream, samples, min_batch_us, budget_s)
+            t_tr, _ = _time_batches(mt.prepare_transpose(B, Bt), stream, samples, min_batch_us, budget_s)
             if budget_s is not None and t_nt > budget_s / 8:
                 t_nn = t_tnn - t_tr                           # long shapes: the difference stands in
                 t_al = float("nan")
             else:
-                t_nn, _ = _time_batches(lambda: mt.mtnn_nn(A, Bt, C), stream, samples, min_batch_us, budget_s)
+                t_nn, _ = _time_batches(mt.prepare_nn(A, Bt, C), stream, samples, min_batch_us, budget_s)
                 t_al, _ = _time_batches(tnn_alloc, stream, max(5, samples // 4), min_batch_us, budget_s)
             wr.writerow({"m": m, "n": n, "k": k, "seed": seed, "t_nt": "%.9g" % t_nt, "t_nt_min": "%.9g" % t_nt_min,
                          "t_tnn": "%.9g" % t_tnn, "t_tnn_min": "%.9g" % t_tnn_min, "t_transpose": "%.9g" % t_tr,
