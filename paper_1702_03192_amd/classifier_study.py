@@ -4,10 +4,11 @@ Table VI and the convergence figure).  Host only.
   python -m paper_1702_03192_amd.classifier_study --csv <table> --out <report.json>
 
 Compared: the boosted trees of the paper (8 trees, depth 8), a single decision tree (one tree, depth 8:
-the paper's "DT") and the majority rule.  The paper's SVM baselines come from an external library and
-are comparison systems, not rebuilt here.  Accuracy is 5-fold cross-validated; train time is the
-library call on all rows; predict time is per prediction inside the library (mtnn_select_batch over
-10^6 shapes).  The training-size curve trains on x % of the rows (stratified, seeded) and tests on all
+the paper's "DT"), the two support vector machines of Table VI (radial basis function and polynomial
+kernels with the paper's C = 1000 and gamma = 0.01, features scaled to (0, 1) on the training rows;
+our own solver, svm.py) and the majority rule.  Accuracy is 5-fold cross-validated; train time is
+one fit on all rows; predict time is per prediction (trees: inside the library, mtnn_select_batch
+over 10^6 shapes; SVMs: the decision function over 20000 shapes).  The training-size curve trains on x % of the rows (stratified, seeded) and tests on all
 rows, x = 10, 15, ..., 100, as in the paper.
 """
 from __future__ import annotations
@@ -60,6 +61,39 @@ def main(argv=None):
         report["classifiers"][name] = {"cv5_accuracy": float(np.mean(accs)), "cv5_min": min(accs), "cv5_max": max(accs),
                                        "train_on_all_accuracy": train_acc, "train_ms": float(np.median(times) * 1e3),
                                        "predict_us": per_pred * 1e6, "nodes": sum(L.mtnn_model_tree_size(t) for t in range(L.mtnn_model_num_trees()))}
+    from . import svm
+    probe_x = np.array([mt.mtnn_features(*map(int, s)) for s in probe[:20000]])
+    for name, kind in (("SVM-RBF (C 1000, gamma 0.01)", "rbf"), ("SVM-Poly (C 1000, gamma 0.01, degree 3)", "poly")):
+        accs, acc_nt, acc_tnn = [], [], []
+        for tr, te in folds:
+            tr, te = np.array(tr), np.array(te)
+            if len(set(labels[tr])) < 2:
+                pred = np.full(len(te), labels[tr][0])
+            else:
+                xs, lo, hi = svm.scale01(X[tr])
+                model = svm.train(xs, labels[tr], kind)
+                pred = model.predict(svm.scale01(X[te], lo, hi)[0])
+            accs.append(float((pred == labels[te]).mean()))
+            if (labels[te] == 1).any():
+                acc_nt.append(float((pred[labels[te] == 1] == 1).mean()))
+            if (labels[te] == -1).any():
+                acc_tnn.append(float((pred[labels[te] == -1] == -1).mean()))
+        entry = {"cv5_accuracy": float(np.mean(accs)), "cv5_min": min(accs), "cv5_max": max(accs),
+                 "cv5_accuracy_nt_class": float(np.mean(acc_nt)) if acc_nt else None,
+                 "cv5_accuracy_tnn_class": float(np.mean(acc_tnn)) if acc_tnn else None}
+        if len(set(labels)) >= 2:
+            xs, lo, hi = svm.scale01(X)
+            t0 = time.perf_counter()
+            model = svm.train(xs, labels, kind)
+            entry["train_ms"] = (time.perf_counter() - t0) * 1e3
+            entry["train_on_all_accuracy"] = float((model.predict(xs) == labels).mean())
+            entry["support_vectors"] = int(model.sv.shape[0])
+            entry["solver_steps"], entry["solver_converged"] = int(model.steps), bool(model.converged)
+            ps = svm.scale01(probe_x, lo, hi)[0]
+            t0 = time.perf_counter()
+            model.predict(ps)
+            entry["predict_us"] = (time.perf_counter() - t0) / len(ps) * 1e6
+        report["classifiers"][name] = entry
     maj = 1 if (labels == 1).sum() >= (labels == -1).sum() else -1
     report["classifiers"]["majority rule"] = {"cv5_accuracy": float(np.mean([(labels[te] == maj).mean() for _, te in folds])),
                                               "train_ms": 0.0, "predict_us": 0.0}
