@@ -83,11 +83,23 @@ MTNN_API int mtnn_transpose(void *stream, int rows, int cols,
  * (Section III, Section VI); the square case decomposes into independent tile swaps. */
 MTNN_API int mtnn_transpose_inplace(void *stream, int n, float *X, int ld);
 
-/* TNN without a workspace, for a square B (n == k, else MTNN_ERR_ARG): B is transposed in place,
- * the NN product runs on it, and B is transposed back; B is unchanged once the enqueued work has
- * run, but it is WRITTEN in between, so nothing else may read it concurrently. */
+/* In-place transpose of a dense rectangular matrix: X holds rows x cols (leading dimension cols) on
+ * entry and cols x rows (leading dimension rows) on exit, bit-exact, with no second buffer -- the
+ * paper's way out when the memory for B^T is missing (Section III; future work in Section VI).  The
+ * index permutation is factored into two or three passes that each permute within rows or within
+ * columns (three when rows and cols share a factor), every pass a set of independent LDS-sized
+ * problems; see csrc/transpose_inplace_rect.hip.  rows == cols takes the square kernel; a vector
+ * (rows or cols == 1) is a no-op.  Limits: rows, cols <= 32768 (else MTNN_ERR_ARG). */
+MTNN_API int mtnn_transpose_inplace_rect(void *stream, int rows, int cols, float *X);
+
+/* TNN without a workspace: B is transposed in place, the NN product runs on it, and B is transposed
+ * back; B is unchanged once the enqueued work has run, but it is WRITTEN in between, so nothing else
+ * may read it concurrently and it must not overlap A (MTNN_ERR_ALIAS).  A square B (n == k) may have
+ * any leading dimension; a rectangular B must be dense (ldb == k) and within the limits of
+ * mtnn_transpose_inplace_rect, else MTNN_ERR_ARG (mtnn_tnn_inplace_supported tells beforehand). */
 MTNN_API int mtnn_tnn_inplace(void *stream, int m, int n, int k,
                      const float *A, int lda, float *B, int ldb, float *C, int ldc);
+MTNN_API int mtnn_tnn_inplace_supported(int n, int k, int ldb);
 
 /* Bytes of workspace TNN needs for B^T (n*k floats, rounded up to 256 B); 0 if n or k <= 0. */
 MTNN_API size_t mtnn_tnn_workspace_bytes(int n, int k);
@@ -108,6 +120,20 @@ MTNN_API int mtnn_tnn(void *stream, int m, int n, int k,
 MTNN_API int mtnn_auto(void *stream, int m, int n, int k,
               const float *A, int lda, const float *B, int ldb, float *C, int ldc,
               void *workspace, size_t workspace_bytes, int *chosen);
+
+/* The choice among three alternatives that Section VI leaves as future work: NT (+1), TNN with the
+ * caller's workspace (-1), or TNN through in-place transposes of B (-2) when there is no room for
+ * B^T.  mtnn_select3 is the rule: the predictor's label decides between NT and TNN as in Algorithm 2;
+ * where it answers TNN but have_workspace is 0, the in-place path is taken only if can_inplace is set
+ * and the kernels' cost model puts the NN product plus two in-place transposes below the NT product,
+ * otherwise NT (the memory rule of Section II).  Returns 0 for non-positive sizes.
+ * mtnn_auto3 runs the chosen path; mode 0 = the rule, +1 / -1 / -2 force a path (-1 needs the
+ * workspace: MTNN_ERR_WORKSPACE; -2 needs mtnn_tnn_inplace_supported: MTNN_ERR_ARG).  B is not const:
+ * the in-place path writes it on the way and restores it.  *chosen (may be NULL) receives the path. */
+MTNN_API int mtnn_select3(int m, int n, int k, int have_workspace, int can_inplace);
+MTNN_API int mtnn_auto3(void *stream, int mode, int m, int n, int k,
+               const float *A, int lda, float *B, int ldb, float *C, int ldc,
+               void *workspace, size_t workspace_bytes, int *chosen);
 
 /* ---- selection (Section IV) ----------------------------------------------------------- */
 

@@ -48,6 +48,10 @@ SIGNATURES = {
     "mtnn_transpose": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_int, _c_vp, _c_int]),
     "mtnn_transpose_inplace": (_c_int, [_c_vp, _c_int, _c_vp, _c_int]),
     "mtnn_tnn_inplace": (_c_int, _GEMM),
+    "mtnn_tnn_inplace_supported": (_c_int, [_c_int, _c_int, _c_int]),
+    "mtnn_transpose_inplace_rect": (_c_int, [_c_vp, _c_int, _c_int, _c_vp]),
+    "mtnn_select3": (_c_int, [_c_int, _c_int, _c_int, _c_int, _c_int]),
+    "mtnn_auto3": (_c_int, [_c_vp, _c_int] + _GEMM[1:] + [_c_vp, _c_sz, _p_int]),
     "mtnn_tnn_workspace_bytes": (_c_sz, [_c_int, _c_int]),
     "mtnn_tnn": (_c_int, _GEMM + [_c_vp, _c_sz]),
     "mtnn_auto": (_c_int, _GEMM + [_c_vp, _c_sz, _p_int]),
@@ -265,8 +269,32 @@ def mtnn_transpose_inplace(X, stream=None):
     return X
 
 
+def mtnn_transpose_inplace_rect(X, rows: int, cols: int, stream=None):
+    """The dense rows x cols matrix in the 1-D (or any contiguous) tensor X becomes cols x rows, in place."""
+    if not X.is_contiguous() or X.numel() != rows * cols:
+        raise ValueError("X must be a contiguous tensor of rows * cols elements")
+    _check(lib().mtnn_transpose_inplace_rect(_stream(stream), rows, cols, X.data_ptr()), "mtnn_transpose_inplace_rect")
+    return X
+
+
+def mtnn_select3(m: int, n: int, k: int, have_workspace: bool, can_inplace: bool) -> int:
+    return int(lib().mtnn_select3(m, n, k, int(have_workspace), int(can_inplace)))
+
+
+def mtnn_auto3(A, B, C, workspace=None, mode: int = 0, stream=None) -> int:
+    """NT (+1), TNN (-1) or TNN through in-place transposes of B (-2): the rule (mode 0) or a forced path."""
+    (pa, lda), (pb, ldb), (pc, ldc) = _dev(A, "A"), _dev(B, "B"), _dev(C, "C")
+    m, k = A.shape
+    n = B.shape[0]
+    pw, wb = _ws(workspace)
+    chosen = ctypes.c_int(0)
+    _check(lib().mtnn_auto3(_stream(stream), mode, m, n, k, pa, lda, pb, ldb, pc, ldc, pw, wb, ctypes.byref(chosen)),
+           "mtnn_auto3")
+    return chosen.value
+
+
 def mtnn_tnn_inplace(A, B, C, stream=None):
-    """C = A x B^T through an in-place transpose of the square B (restored afterwards)."""
+    """C = A x B^T through in-place transposes of B (restored afterwards)."""
     (pa, lda), (pb, ldb), (pc, ldc) = _dev(A, "A"), _dev(B, "B"), _dev(C, "C")
     m, k = A.shape
     n = B.shape[0]

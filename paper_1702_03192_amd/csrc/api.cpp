@@ -246,21 +246,94 @@ int mtnn_transpose_inplace(void* stream, int n, float* X, int ld)
     return launch_status(mtnn::launch_transpose_inplace(static_cast<hipStream_t>(stream), n, X, ld));
 }
 
+int mtnn_transpose_inplace_rect(void* stream, int rows, int cols, float* X)
+{
+    if (rows < 0 || cols < 0) return MTNN_ERR_DIM;
+    if (rows == 0 || cols == 0) return MTNN_OK;
+    if (!X) return MTNN_ERR_NULL;
+    if (rows == cols) return mtnn_transpose_inplace(stream, rows, X, rows);
+    if (rows == 1 || cols == 1) return MTNN_OK;                    // a vector keeps its words where they are
+    if (!mtnn::transpose_inplace_rect_supported(rows, cols)) return MTNN_ERR_ARG;
+    if (!device_ok()) return MTNN_ERR_NO_DEVICE;
+    return launch_status(mtnn::launch_transpose_inplace_rect(static_cast<hipStream_t>(stream), rows, cols, X));
+}
+
+int mtnn_tnn_inplace_supported(int n, int k, int ldb)
+{
+    if (n <= 0 || k <= 0 || ldb < k) return 0;
+    if (n == k) return 1;                                          // square: any leading dimension
+    return (ldb == k && mtnn::transpose_inplace_rect_supported(n, k)) ? 1 : 0;
+}
+
 int mtnn_tnn_inplace(void* stream, int m, int n, int k, const float* A, int lda, float* B, int ldb, float* C, int ldc)
 {
-    // TNN with no workspace, for a square B: transpose B in place, NN product, transpose back
-    if (n != k) return MTNN_ERR_ARG;
+    // TNN with no workspace: transpose B in place, NN product on it, transpose back
     const int st0 = check_gemm(mtnn::OP_NT, m, n, k, A, lda, B, ldb, C, ldc);
     if (st0 != MTNN_OK) return st0;
     if (m == 0 || n == 0) return MTNN_OK;
+    if (k == 0) return run_gemm(stream, mtnn::OP_NT, -1, 0, m, n, k, A, lda, B, ldb, C, ldc);
+    if (!mtnn_tnn_inplace_supported(n, k, ldb)) return MTNN_ERR_ARG;
     // B is written on the way (transposed, then transposed back): as an output it must not overlap A
     // (the Gram product A x A^T with A == B would otherwise have its left operand transposed under it)
     if (overlap(span(B, n, k, ldb), span(A, m, k, lda))) return MTNN_ERR_ALIAS;
-    int st = mtnn_transpose_inplace(stream, n, B, ldb);
+    const bool square = (n == k);
+    int st = square ? mtnn_transpose_inplace(stream, n, B, ldb) : mtnn_transpose_inplace_rect(stream, n, k, B);
     if (st != MTNN_OK) return st;
-    st = run_gemm(stream, mtnn::OP_NN, -1, 0, m, n, k, A, lda, B, ldb, C, ldc);
-    const int st2 = mtnn_transpose_inplace(stream, n, B, ldb);   // restore B even if the product failed to launch
+    // B now holds B^T: k x n, leading dimension ldb (square) or n (dense rectangular)
+    st = run_gemm(stream, mtnn::OP_NN, -1, 0, m, n, k, A, lda, B, square ? ldb : n, C, ldc);
+    // restore B even if the product failed to launch
+    const int st2 = square ? mtnn_transpose_inplace(stream, n, B, ldb) : mtnn_transpose_inplace_rect(stream, k, n, B);
     return st != MTNN_OK ? st : st2;
+}
+
+// Does TNN through in-place transposes promise to beat NT?  The cost model's estimates of the two
+// products, and two in-place transposes of B at their measured rates: the square kernel moves 8 bytes
+// per word in one pass at ~4.5 TB/s; the rectangular one makes two or three passes (three when the
+// dimensions share a factor) at ~2 TB/s each.
+static bool inplace_pays(int m, int n, int k)
+{
+    const mtnn::Geometry geo = mtnn::geometry_or_nominal();
+    const double t_nt = mtnn::gemm_predicted_seconds(geo, mtnn::OP_NT, m, n, k, kDefaultScratchBytes);
+    const double t_nn = mtnn::gemm_predicted_seconds(geo, mtnn::OP_NN, m, n, k, kDefaultScratchBytes);
+    const double words = (double)n * (double)k;
+    double t_ip;
+    if (n == k) {
+        t_ip = 8.0 * words / 4.5e12 + 3e-6;
+    } else {
+        int a = n, b = k;
+        while (b) { const int r = a % b; a = b; b = r; }
+        t_ip = (a > 1 ? 3.0 : 2.0) * (8.0 * words / 2.0e12 + 3e-6);
+    }
+    return t_nt - t_nn > 2.0 * t_ip;
+}
+
+int mtnn_select3(int m, int n, int k, int have_workspace, int can_inplace)
+{
+    if (m <= 0 || n <= 0 || k <= 0) return 0;
+    const int label = mtnn_select(m, n, k);
+    if (label != -1) return label;
+    if (have_workspace) return -1;
+    return (can_inplace && inplace_pays(m, n, k)) ? -2 : 1;
+}
+
+int mtnn_auto3(void* stream, int mode, int m, int n, int k, const float* A, int lda, float* B, int ldb,
+               float* C, int ldc, void* workspace, size_t workspace_bytes, int* chosen)
+{
+    if (mode != 0 && mode != 1 && mode != -1 && mode != -2) return MTNN_ERR_ARG;
+    const int st = check_gemm(mtnn::OP_NT, m, n, k, A, lda, B, ldb, C, ldc);
+    if (st != MTNN_OK) return st;
+    int path = mode;
+    if (mode == 0) {
+        const bool room = workspace && workspace_bytes >= mtnn_tnn_workspace_bytes(n, k);
+        const bool can_ip = m > 0 && n > 0 && k > 0 && mtnn_tnn_inplace_supported(n, k, ldb) &&
+                            !overlap(span(B, n, k, ldb), span(A, m, k, lda));
+        path = (m > 0 && n > 0 && k > 0) ? mtnn_select3(m, n, k, room ? 1 : 0, can_ip ? 1 : 0) : 1;
+        if (path == -1 && !room) path = 1;       // (MTNN_FORCE may name TNN where there is no room for it)
+    }
+    if (chosen) *chosen = path;
+    if (path == -2) return mtnn_tnn_inplace(stream, m, n, k, A, lda, B, ldb, C, ldc);
+    if (path == -1) return mtnn_tnn(stream, m, n, k, A, lda, B, ldb, C, ldc, workspace, workspace_bytes);
+    return mtnn_nt(stream, m, n, k, A, lda, B, ldb, C, ldc);
 }
 
 int mtnn_copy_bytes(void* stream, size_t bytes, const void* in, void* out)

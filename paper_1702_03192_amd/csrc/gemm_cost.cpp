@@ -176,6 +176,14 @@ Choice choose(const Geometry& geo, int op, int m, int n, int k, bool allow_split
     return best;
 }
 
+double gemm_predicted_seconds(const Geometry& geo, int op, int m, int n, int k, size_t scratch_bytes)
+{
+    const Choice ch = choose(geo, op, m, n, k, true, true, kEpiNone, scratch_bytes);
+    const int o = (op == OP_NT) ? 1 : 0;
+    if (ch.splits == kStreamK) return predicted_seconds_even_cut(geo, ch.cfg, o, m, n, k, scratch_bytes);
+    return predicted_seconds(geo, kTileConfigs[ch.cfg], o, m, n, k, ch.splits, true);
+}
+
 int gemm_config_count() { return kNumTileConfigs; }
 const char* gemm_config_name(int cfg) { return (cfg >= 0 && cfg < kNumTileConfigs) ? kTileConfigs[cfg].name : nullptr; }
 

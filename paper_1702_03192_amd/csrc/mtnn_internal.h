@@ -73,6 +73,8 @@ long long gemm_fused_launches();
 const char* gemm_config_name(int cfg);
 int gemm_default_config(int op, int m, int n, int k, size_t scratch_bytes);
 int gemm_default_splits(int op, int m, int n, int k, size_t scratch_bytes);
+// the cost model's estimate for the launch the rule would choose (aligned operands)
+double gemm_predicted_seconds(const Geometry& geo, int op, int m, int n, int k, size_t scratch_bytes);
 
 // the separate passes behind the fused epilogues, for matrices with any leading dimension (fc.hip)
 int launch_bias_act(hipStream_t s, int rows, int width, float* Z, long ld, const float* b, int relu);
@@ -80,6 +82,9 @@ int launch_sgd_2d(hipStream_t s, int rows, int width, float* P, long ldp, const 
 
 int launch_fill_zero(hipStream_t s, int m, int n, float* C, long ldc);
 int launch_transpose_inplace(hipStream_t s, int n, float* X, long ld);
+// dense rows x cols -> cols x rows in the same buffer (transpose_inplace_rect.hip)
+bool transpose_inplace_rect_supported(int rows, int cols);
+int launch_transpose_inplace_rect(hipStream_t s, int rows, int cols, float* X);
 int launch_copy(hipStream_t s, size_t nvec, const void* in, void* out);
 int launch_transpose(hipStream_t s, int rows, int cols, const float* in, long ldin, float* out, long ldout);
 

@@ -173,7 +173,17 @@ def test_inplace_transpose_validation(L):
     assert L.mtnn_transpose_inplace(None, 4, None, 4) == 2
     assert L.mtnn_transpose_inplace(None, 4, A, 3) == 3
     assert L.mtnn_transpose_inplace(None, 0, None, 0) == 0
-    assert L.mtnn_tnn_inplace(None, 4, 6, 8, A, 8, B, 8, C, 6) == 8      # B not square
+    assert L.mtnn_tnn_inplace(None, 4, 6, 8, A, 9, B, 9, C, 6) == 8      # B rectangular and not dense
+    assert L.mtnn_tnn_inplace(None, 4, 40000, 8, A, 8, B, 8, 0x40000000, 40000) == 8   # beyond the in-place kernel's limit
+    assert L.mtnn_tnn_inplace(None, 4, 6, 8, A, 8, B, 8, C, 6) in (0, 9)  # dense rectangular B: accepted
+    assert L.mtnn_tnn_inplace_supported(6, 8, 8) == 1 and L.mtnn_tnn_inplace_supported(6, 8, 9) == 0
+    assert L.mtnn_tnn_inplace_supported(8, 8, 11) == 1 and L.mtnn_tnn_inplace_supported(8, 8, 7) == 0
+    assert L.mtnn_tnn_inplace_supported(32768, 5, 5) == 1 and L.mtnn_tnn_inplace_supported(32769, 5, 5) == 0
+    assert L.mtnn_transpose_inplace_rect(None, -1, 4, A) == 1
+    assert L.mtnn_transpose_inplace_rect(None, 4, 6, None) == 2
+    assert L.mtnn_transpose_inplace_rect(None, 4, 40000, A) == 8
+    assert L.mtnn_transpose_inplace_rect(None, 0, 6, None) == 0
+    assert L.mtnn_transpose_inplace_rect(None, 1, 60000, A) == 0          # a vector: nothing to move
     assert L.mtnn_tnn_inplace(None, 4, 8, 8, A, 7, B, 8, C, 8) == 3
 
 
@@ -265,3 +275,34 @@ def test_tnn_inplace_rejects_b_overlapping_a(L):
     assert L.mtnn_tnn_inplace(None, 8, 8, 8, A, 8, A, 8, C, 8) == 4
     assert L.mtnn_tnn_inplace(None, 4, 8, 8, A + 32 * 4, 8, A, 8, C, 8) == 4      # A inside B
     assert L.mtnn_tnn_inplace(None, 8, 8, 8, A, 8, B, 8, C, 8) in (0, 6, 9)       # disjoint: passes validation
+
+
+def test_three_way_choice_validation_and_rule(L):
+    need = mt.mtnn_tnn_workspace_bytes(6, 8)
+    chosen = ctypes.c_int(9)
+    assert L.mtnn_auto3(None, 2, 4, 6, 8, A, 8, B, 8, C, 6, W, need, ctypes.byref(chosen)) == 8      # unknown mode
+    assert L.mtnn_auto3(None, 0, 4, 6, 8, A, 7, B, 8, C, 6, W, need, ctypes.byref(chosen)) == 3      # argument checks first
+    assert L.mtnn_auto3(None, -1, 4, 6, 8, A, 8, B, 8, C, 6, None, 0, ctypes.byref(chosen)) == 5     # forced TNN needs its workspace
+    assert chosen.value == -1
+    assert L.mtnn_auto3(None, -2, 4, 6, 8, A, 8, B, 9, C, 6, None, 0, ctypes.byref(chosen)) == 8     # forced in-place, B not dense
+    assert L.mtnn_auto3(None, -2, 8, 8, 8, A, 8, A, 8, C, 8, None, 0, ctypes.byref(chosen)) == 4     # ... and B must not be A
+    assert L.mtnn_auto3(None, 0, 0, 6, 8, None, 8, None, 8, None, 6, None, 0, ctypes.byref(chosen)) == 0
+    assert chosen.value == 1
+    # the rule: NT where the predictor says NT; TNN where it says TNN and there is room; without room, in place only if allowed and worth it
+    assert L.mtnn_select3(0, 4, 4, 1, 1) == 0
+    rows = [(m, n, k) for m in (64, 512, 4096) for n in (64, 512, 4096) for k in (64, 512, 4096)]
+    try:
+        mt.mtnn_train_selector(rows, [1] * len(rows))
+        assert all(L.mtnn_select3(m, n, k, w, ip) == 1 for m, n, k in rows for w in (0, 1) for ip in (0, 1))
+        mt.mtnn_train_selector(rows, [-1] * len(rows))
+        for m, n, k in rows:
+            assert L.mtnn_select(m, n, k) == -1
+            assert L.mtnn_select3(m, n, k, 1, 0) == -1 and L.mtnn_select3(m, n, k, 1, 1) == -1
+            assert L.mtnn_select3(m, n, k, 0, 0) == 1                      # the memory rule of Section II
+            assert L.mtnn_select3(m, n, k, 0, 1) in (1, -2)
+        # the two kernels are tuned alike here, so two more passes over B never pay on these shapes
+        assert all(L.mtnn_select3(m, n, k, 0, 1) == 1 for m, n, k in rows)
+    finally:
+        mt.mtnn_unload_model()
+        if os.path.exists(mt.DEFAULT_MODEL):
+            mt.mtnn_load_model(mt.DEFAULT_MODEL)

@@ -5,7 +5,7 @@ import pytest
 import oracle
 from paper_1702_03192_amd import binding as mt
 from paper_1702_03192_amd import inputs as I
-from gpu_util import CANARY_BITS, Guarded, dev_matrix
+from gpu_util import CANARY_BITS, Guarded, check_gemm, dev_matrix
 
 pytestmark = pytest.mark.gpu
 
@@ -129,6 +129,93 @@ def test_tnn_inplace_matches_oracle_and_restores_b():
     C, S = oracle.nt_ref(A, B, with_bound=True)
     check_gemm(got, C, S, n, "tnn_inplace")
     assert dB.cpu().numpy().tobytes() == B.tobytes()
-    with pytest.raises(mt.MtnnError) as e:
-        mt.mtnn_tnn_inplace(dA[:, :100].contiguous(), dev_matrix(B[:, :100].copy()), out.view)
+    with pytest.raises(mt.MtnnError) as e:          # a rectangular B must be dense
+        mt.mtnn_tnn_inplace(dA[:, :100].contiguous(), dev_matrix(B[:, :100].copy(), 104), out.view)
     assert e.value.status == 8
+
+
+# ---- rectangular in-place transposition -------------------------------------------------------------
+
+RECT_SHAPES = [(2, 3), (3, 2), (5, 7), (97, 3), (3, 97), (31, 17), (127, 251), (251, 127), (1009, 13),   # prime dimensions
+               (24, 36), (36, 24), (64, 48), (100, 1000), (1000, 100), (96, 4096), (4096, 96),            # a common factor: three passes
+               (1, 9), (9, 1), (1024, 2048), (2048, 1024), (1500, 4500), (4097, 1023), (33, 32768), (32768, 33),
+               (8192, 4096), (300, 301)]
+
+
+@pytest.mark.parametrize("rows,cols", RECT_SHAPES, ids=lambda v: str(v))
+def test_rectangular_inplace_transpose_is_bit_exact_and_its_own_inverse(rows, cols):
+    """rows x cols dense -> cols x rows dense in the same buffer, against the oracle's transpose word for
+    word (an index-coded matrix, so a misplaced word shows), canaries on both sides, and back again."""
+    import torch
+    guard = 64
+    if rows * cols < (1 << 24):        # every word distinct and exact in fp32: word e holds the value e
+        x = np.arange(rows * cols, dtype=np.float32).reshape(rows, cols)
+    else:
+        x = I.uniform_pm1(77, 0, rows, cols)
+    host = np.full(guard + rows * cols + guard, np.float32(np.nan), dtype=np.float32)
+    host[:guard].view(np.uint32)[:] = 0x7FC0DEAD
+    host[guard + rows * cols:].view(np.uint32)[:] = 0x7FC0DEAD
+    host[guard:guard + rows * cols] = x.reshape(-1)
+    buf = torch.from_numpy(host).cuda()
+    body = buf[guard:guard + rows * cols]
+    mt.mtnn_transpose_inplace_rect(body, rows, cols)
+    torch.cuda.synchronize()
+    got = buf.cpu().numpy()
+    want = np.ascontiguousarray(oracle.transpose_ref(x)).reshape(-1)
+    assert got[guard:guard + rows * cols].tobytes() == want.tobytes()
+    assert (got[:guard].view(np.uint32) == 0x7FC0DEAD).all() and (got[guard + rows * cols:].view(np.uint32) == 0x7FC0DEAD).all()
+    mt.mtnn_transpose_inplace_rect(body, cols, rows)
+    torch.cuda.synchronize()
+    assert buf.cpu().numpy()[guard:guard + rows * cols].tobytes() == x.reshape(-1).tobytes()
+
+
+def test_rectangular_inplace_transpose_keeps_nan_payloads_and_signed_zeros():
+    import torch
+    rows, cols = 37, 52
+    bits = I.uniform_ints(99, 0, rows * cols, 0, 2 ** 31 - 1).astype(np.uint32) * np.uint32(2) + np.uint32(1)
+    bits[:4] = [0x80000000, 0x7FC00001, 0xFFC12345, 0x00000001]
+    buf = torch.from_numpy(bits.view(np.float32).copy()).cuda()
+    mt.mtnn_transpose_inplace_rect(buf, rows, cols)
+    torch.cuda.synchronize()
+    assert buf.cpu().numpy().view(np.uint32).tobytes() == np.ascontiguousarray(bits.reshape(rows, cols).T).tobytes()
+
+
+@pytest.mark.parametrize("m,n,k", [(100, 96, 260), (257, 1000, 100), (64, 127, 251), (300, 2048, 1024)])
+def test_tnn_through_rectangular_inplace_transposes_matches_oracle_and_restores_b(m, n, k):
+    import torch
+    A, B = I.nt_operands(m, n, k, 4400 + n, "normal")
+    C, S = oracle.nt_ref(A, B, with_bound=True)
+    dA, dB = dev_matrix(A), dev_matrix(B)
+    out = Guarded(m, n, n + 4)
+    mt.mtnn_tnn_inplace(dA, dB, out.view)
+    torch.cuda.synchronize()
+    got, intact = out.host()
+    assert intact
+    check_gemm(got, C, S, k, f"in-place TNN {m}x{n}x{k}")
+    assert dB.cpu().numpy().tobytes() == B.tobytes(), "B was not restored"
+
+
+def test_three_way_choice_runs_each_forced_path_and_the_rule():
+    import torch
+    m, n, k = 200, 328, 124
+    A, B = I.nt_operands(m, n, k, 4500, "uniform")
+    C, S = oracle.nt_ref(A, B, with_bound=True)
+    dA, dB = dev_matrix(A), dev_matrix(B)
+    ws = torch.full((mt.mtnn_tnn_workspace_bytes(n, k) // 4,), float("nan"), device="cuda")
+    for mode, workspace in ((1, None), (-1, ws), (-2, None), (0, ws), (0, None)):
+        out = Guarded(m, n)
+        chosen = mt.mtnn_auto3(dA, dB, out.view, workspace, mode)
+        torch.cuda.synchronize()
+        got, intact = out.host()
+        assert intact
+        check_gemm(got, C, S, k, f"auto3 mode {mode} -> {chosen}")
+        if mode != 0:
+            assert chosen == mode
+        else:
+            assert chosen == mt.mtnn_select3(m, n, k, workspace is not None, True)
+        assert dB.cpu().numpy().tobytes() == B.tobytes()
+    bt = ws[: n * k].view(k, n).cpu().numpy()
+    assert bt.tobytes() == np.ascontiguousarray(B.T).tobytes()          # the forced TNN went through the workspace
+    with pytest.raises(mt.MtnnError) as e:
+        mt.mtnn_auto3(dA, dB, Guarded(m, n).view, None, -1)
+    assert e.value.status == 5
