@@ -287,23 +287,16 @@ int mtnn_tnn_inplace(void* stream, int m, int n, int k, const float* A, int lda,
 }
 
 // Does TNN through in-place transposes promise to beat NT?  The cost model's estimates of the two
-// products, and two in-place transposes of B at their measured rates: the square kernel moves 8 bytes
-// per word in one pass at ~4.5 TB/s; the rectangular one makes two or three passes (three when the
-// dimensions share a factor) at ~2 TB/s each.
+// products, and two in-place transposes of B at their measured rates (8 bytes per word moved): the
+// square kernel, one pass of tile swaps, ~4.1 TB/s; the rectangular one, two or three passes with
+// index arithmetic per word, 0.2-0.7 TB/s (0.35 taken).
 static bool inplace_pays(int m, int n, int k)
 {
     const mtnn::Geometry geo = mtnn::geometry_or_nominal();
     const double t_nt = mtnn::gemm_predicted_seconds(geo, mtnn::OP_NT, m, n, k, kDefaultScratchBytes);
     const double t_nn = mtnn::gemm_predicted_seconds(geo, mtnn::OP_NN, m, n, k, kDefaultScratchBytes);
-    const double words = (double)n * (double)k;
-    double t_ip;
-    if (n == k) {
-        t_ip = 8.0 * words / 4.5e12 + 3e-6;
-    } else {
-        int a = n, b = k;
-        while (b) { const int r = a % b; a = b; b = r; }
-        t_ip = (a > 1 ? 3.0 : 2.0) * (8.0 * words / 2.0e12 + 3e-6);
-    }
+    const double bytes = 8.0 * (double)n * (double)k;
+    const double t_ip = (n == k) ? bytes / 4.1e12 + 3e-6 : bytes / 0.35e12 + 10e-6;
     return t_nt - t_nn > 2.0 * t_ip;
 }
 
