@@ -372,6 +372,11 @@ def prepare_nn(A, B, C, stream=None) -> Prepared:
     return Prepared("mtnn_nn", _gemm_args(OP_NN, A, B, C, stream), (A, B, C))
 
 
+def prepare_gemm_ex(op, cfg, A, B, C, stream=None, splits=0) -> Prepared:
+    a = _gemm_args(op, A, B, C, stream)
+    return Prepared("mtnn_gemm_ex", (a[0], op, cfg, splits) + a[1:], (A, B, C))
+
+
 def prepare_tnn(A, B, C, workspace, stream=None) -> Prepared:
     pw, wb = _ws(workspace)
     return Prepared("mtnn_tnn", _gemm_args(OP_NT, A, B, C, stream) + (pw, wb), (A, B, C, workspace))

@@ -7,6 +7,32 @@
 
 namespace mtnn {
 
+// Division of a number below 2^31 by a divisor known on the host, as a multiply-high and a shift: with
+// s = ceil(log2 d) and mul = floor(2^(31+s) / d) + 1 (which fits 32 bits), floor(n / d) =
+// (n x mul) >> (31 + s) exactly for every n < 2^31 (the error mul d - 2^(31+s) is at most d, so n times
+// it stays below 2^(31+s)).  On wave-uniform operands this is two scalar instructions; an integer
+// division in the kernel would be some twenty vector instructions, which the fp32 matrix instructions
+// cannot overlap (they run on the same lanes).
+struct FastDiv {
+    unsigned mul;     // 0: the divisor is 1
+    unsigned shift;   // (31 + s) - 32
+};
+inline FastDiv make_fastdiv(unsigned d)
+{
+    FastDiv f = {0u, 0u};
+    if (d <= 1) return f;
+    unsigned s = 0;
+    while ((1ull << s) < d) ++s;
+    f.mul = (unsigned)(((1ull << (31 + s)) / d) + 1ull);
+    f.shift = s - 1;
+    return f;
+}
+__host__ __device__ inline int fast_div(int n, FastDiv f)
+{
+    if (f.mul == 0) return n;
+    return (int)((unsigned)(((unsigned long long)(unsigned)n * f.mul) >> 32) >> f.shift);
+}
+
 struct GemmParams {
     const float* A;
     const float* B;
@@ -15,7 +41,12 @@ struct GemmParams {
     long lda, ldb, ldc;
     int tiles_m, tiles_n;
     int group_m;      // C-tile rows per band (L2 locality)
-    int num_xcd;      // XCDs the hardware deals consecutive workgroup ids to (8 on MI355X)
+    int num_xcd;      // XCDs the hardware deals consecutive workgroup ids to (8 on MI355X); 1: no remapping
+    // what tile_of_block needs, worked out on the host (set_tile_order): the deal of tile ids to XCDs
+    // (the first xcd_tall XCDs take xcd_per ids, the others one fewer) and the bands of group_m tile rows
+    int xcd_per, xcd_tall;
+    int last_band, last_rows;   // index of the last band and its number of tile rows (<= group_m)
+    FastDiv fd_xcd, fd_band, fd_group, fd_last;   // divisions by num_xcd, group_m x tiles_n, group_m, last_rows
     // split-k: workgroup w handles C tile w % tiles and k range [split * k_per_split, ...) with
     // split = w / tiles; partial products go to `part` (splits dense M x N matrices), summed by
     // reduce_splits_kernel in split order.  splits == 1: results go straight to C.
@@ -30,6 +61,22 @@ struct GemmParams {
     long ldw;
     float lr;
 };
+
+// fills the fields tile_of_block reads from tiles_m, tiles_n, group_m and num_xcd
+inline void set_tile_order(GemmParams& p)
+{
+    const int total = p.tiles_m * p.tiles_n;
+    if (p.num_xcd < 1 || total < p.num_xcd) p.num_xcd = 1;
+    p.xcd_per = (total + p.num_xcd - 1) / p.num_xcd;
+    p.xcd_tall = total - (p.xcd_per - 1) * p.num_xcd;
+    const int bands = (p.tiles_m + p.group_m - 1) / p.group_m;
+    p.last_band = bands - 1;
+    p.last_rows = p.tiles_m - p.last_band * p.group_m;
+    p.fd_xcd = make_fastdiv((unsigned)p.num_xcd);
+    p.fd_band = make_fastdiv((unsigned)(p.group_m * p.tiles_n));
+    p.fd_group = make_fastdiv((unsigned)p.group_m);
+    p.fd_last = make_fastdiv((unsigned)p.last_rows);
+}
 
 // what a kernel instance does with its accumulators besides storing them
 constexpr int kEpiNone = 0;

@@ -119,28 +119,27 @@ __device__ __forceinline__ f32x4 load_n4(const float* __restrict__ B, long ldb, 
 
 // ---- workgroup id -> C tile -------------------------------------------------------------------
 
+// (All operands are wave-uniform and the divisions are multiply-high + shift with host-made
+// constants, so the whole mapping runs on the scalar unit.)
 __device__ __forceinline__ void tile_of_block(const GemmParams& p, int pid, int& tm, int& tn)
 {
-    const int total = p.tiles_m * p.tiles_n;
     // undo the round-robin deal to XCDs: XCD x receives ids x, x+X, x+2X, ...; give it the
     // contiguous range of logical ids [start(x), start(x+1))
     const int X = p.num_xcd;
-    if (X > 1 && total >= X) {
-        const int per = (total + X - 1) / X;
-        const int tall = total - (per - 1) * X;        // XCDs that get `per` ids (1..X)
-        const int x = pid % X;
-        const int local = pid / X;
-        pid = (x < tall) ? x * per + local
-                         : tall * per + (x - tall) * (per - 1) + local;
+    if (X > 1) {
+        const int local = fast_div(pid, p.fd_xcd);
+        const int x = pid - local * X;
+        pid = (x < p.xcd_tall) ? x * p.xcd_per + local
+                               : p.xcd_tall * p.xcd_per + (x - p.xcd_tall) * (p.xcd_per - 1) + local;
     }
     // bands of group_m tile rows, walked column by column inside a band
     const int band_sz = p.group_m * p.tiles_n;
-    const int band = pid / band_sz;
-    const int first_m = band * p.group_m;
-    const int rows_here = min(p.tiles_m - first_m, p.group_m);
+    const int band = fast_div(pid, p.fd_band);
     const int in_band = pid - band * band_sz;
-    tm = first_m + in_band % rows_here;
-    tn = in_band / rows_here;
+    const bool last = (band == p.last_band);
+    const int rows_here = last ? p.last_rows : p.group_m;
+    tn = fast_div(in_band, last ? p.fd_last : p.fd_group);
+    tm = band * p.group_m + (in_band - tn * rows_here);
 }
 
 // ---- epilogue: accumulators -> C -------------------------------------------------------------
@@ -187,11 +186,13 @@ __device__ __forceinline__ void store_tile(const f32x16 (&acc)[TM][TN], float* _
                                            const float (&bv)[TN], int relu)
 {
     if (row0 + TM * 32 <= M && col0 + TN * 32 <= N) {
+        // one address per lane, then wave-uniform row offsets (scalar multiplies) added to it
+        float* lane_base = C + (size_t)(row0 + lh * 4) * ldc + col0 + lr;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                float* dst = C + (size_t)(row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4)) * ldc + col0 + lr;
+                float* dst = lane_base + (size_t)(i * 32 + (r / 4) * 8 + (r % 4)) * ldc;
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     put<STREAM>(with_bias<BIAS, TN>(acc[i][j][r], bv, j, relu), dst + j * 32);
@@ -226,6 +227,7 @@ __device__ __forceinline__ void store_tile_interleaved(const f32x16 (&acc)[TM][T
 {
     typedef float vecN __attribute__((ext_vector_type(TN)));
     if (TN > 1 && aligned && row0 + TM * 32 <= M && col0 + TN * 32 <= N) {
+        float* lane_base = C + (size_t)(row0 + lh * 4) * ldc + col0 + TN * lr;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -233,7 +235,7 @@ __device__ __forceinline__ void store_tile_interleaved(const f32x16 (&acc)[TM][T
                 vecN v;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) v[j] = with_bias<BIAS, TN>(acc[i][j][r], bv, j, relu);
-                float* dst = C + (size_t)(row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4)) * ldc + col0 + TN * lr;
+                float* dst = lane_base + (size_t)(i * 32 + (r / 4) * 8 + (r % 4)) * ldc;
                 put<STREAM>(v, reinterpret_cast<vecN*>(dst));
                 if (BIAS && r % 4 == 3) __builtin_amdgcn_sched_barrier(0);
             }
@@ -266,6 +268,8 @@ __device__ __forceinline__ void store_tile_interleaved_sgd(const f32x16 (&acc)[T
     if (TN > 1 && aligned && row0 + TM * 32 <= M && col0 + TN * 32 <= N) {
         // eight rows at a time (their loads of W in flight together), so that the loads of the whole
         // tile are not all hoisted to the front at the cost of as many registers
+        float* w_base = W + (size_t)(row0 + lh * 4) * ldw + col0 + TN * lr_;
+        float* g_base = G + (size_t)(row0 + lh * 4) * ldg + col0 + TN * lr_;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -274,21 +278,21 @@ __device__ __forceinline__ void store_tile_interleaved_sgd(const f32x16 (&acc)[T
 #pragma unroll
                 for (int rr = 0; rr < 8; ++rr) {
                     const int r = h * 8 + rr;
-                    const size_t row = (size_t)(row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4));
-                    w[rr] = *reinterpret_cast<const vecN*>(W + row * ldw + col0 + TN * lr_);
+                    const size_t row = (size_t)(i * 32 + (r / 4) * 8 + (r % 4));      // wave-uniform
+                    w[rr] = *reinterpret_cast<const vecN*>(w_base + row * ldw);
                 }
 #pragma unroll
                 for (int rr = 0; rr < 8; ++rr) {
                     const int r = h * 8 + rr;
-                    const size_t row = (size_t)(row0 + i * 32 + (r / 4) * 8 + lh * 4 + (r % 4));
+                    const size_t row = (size_t)(i * 32 + (r / 4) * 8 + (r % 4));
                     vecN g;
 #pragma unroll
                     for (int j = 0; j < TN; ++j) {
                         g[j] = acc[i][j][r];
                         w[rr][j] = __builtin_fmaf(-lr, g[j], w[rr][j]);
                     }
-                    *reinterpret_cast<vecN*>(W + row * ldw + col0 + TN * lr_) = w[rr];
-                    __builtin_nontemporal_store(g, reinterpret_cast<vecN*>(G + row * ldg + col0 + TN * lr_));
+                    *reinterpret_cast<vecN*>(w_base + row * ldw) = w[rr];
+                    __builtin_nontemporal_store(g, reinterpret_cast<vecN*>(g_base + row * ldg));
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -329,6 +333,12 @@ __device__ __forceinline__ void store_tile_staged(const f32x16 (&acc)[TM][TN], f
     constexpr int PIECES = 16 * V;            // pieces per 16-row patch
     const int lr = lane & 31;
     const int lh = lane >> 5;
+    // lane-dependent parts once: where this lane writes in the patch, where it reads, and its address in C
+    float* wr = patch + (lh * 4) * S + lr;
+    const float* rd = patch + (lane / V) * S + (lane % V) * 4;
+    float* lane_base = C + (size_t)(row0 + lane / V) * ldc + col0 + (lane % V) * 4;
+    constexpr int ROWS_PER_T = 64 / V;                                      // patch rows one pass of 64 lanes covers
+    static_assert(64 % V == 0, "a pass of 64 lanes covers whole patch rows");
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -336,18 +346,15 @@ __device__ __forceinline__ void store_tile_staged(const f32x16 (&acc)[TM][TN], f
 #pragma unroll
             for (int rr = 0; rr < 8; ++rr) {
                 const int r = h * 8 + rr;                                   // rows 16h .. 16h+15 of the block
-                const int prow = (rr / 4) * 8 + lh * 4 + (rr % 4);
 #pragma unroll
-                for (int j = 0; j < TN; ++j) patch[prow * S + j * 32 + lr] = with_bias<BIAS, TN>(acc[i][j][r], bv, j, relu);
+                for (int j = 0; j < TN; ++j)
+                    wr[((rr / 4) * 8 + (rr % 4)) * S + j * 32] = with_bias<BIAS, TN>(acc[i][j][r], bv, j, relu);
             }
 #pragma unroll
             for (int t = 0; t < (PIECES + 63) / 64; ++t) {
-                const int idx = t * 64 + lane;
-                if (PIECES % 64 == 0 || idx < PIECES) {
-                    const int prow = idx / V;
-                    const int c4 = idx % V;
-                    const f32x4 v = *reinterpret_cast<const f32x4*>(&patch[prow * S + c4 * 4]);
-                    put<STREAM>(v, reinterpret_cast<f32x4*>(C + (size_t)(row0 + i * 32 + h * 16 + prow) * ldc + col0 + c4 * 4));
+                if (PIECES % 64 == 0 || t * 64 + lane < PIECES) {
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(rd + (t * ROWS_PER_T) * S);
+                    put<STREAM>(v, reinterpret_cast<f32x4*>(lane_base + (size_t)(i * 32 + h * 16 + t * ROWS_PER_T) * ldc));
                 }
             }
             if (BIAS) __builtin_amdgcn_sched_barrier(0);

@@ -97,6 +97,7 @@ int launch_gemm(hipStream_t s, const Geometry& geo, const Scratch& scratch, int 
     p.W = (kind == kEpiSgd) ? epi->W : nullptr;
     p.ldw = (kind == kEpiSgd) ? epi->ldw : 0;
     p.lr = (kind == kEpiSgd) ? epi->lr : 0.f;
+    set_tile_order(p);
     if (splits > 1) {
         int eff_splits = 1, kps = k;
         effective_splits(k, splits, &eff_splits, &kps);

@@ -54,7 +54,7 @@ __device__ __forceinline__ int swz(int row)
 // multiples of 4); otherwise the same 16-byte accesses are made at 4-byte alignment, which gfx950
 // allows for global memory.  GUARD (edge tiles): a group of four that lies across the matrix edge
 // is moved word by word, one that lies outside is skipped.
-template <int TR, int TC, bool NTL, bool GUARD, bool A16>
+template <int TR, int TC, bool NTL, bool GUARD, bool A16, bool STREAM>
 __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
                                                    uint32_t* tile, int rows, int cols, long ldin, long ldout,
                                                    int r0, int c0)
@@ -108,7 +108,8 @@ __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ 
         const int og = r0 + oq * 4;
         uint32_t* dst = out + (size_t)orow * ldout + og;
         if (!GUARD || (orow < cols && og + 3 < rows)) {
-            if (A16) __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(dst));
+            if (A16 && STREAM) __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(dst));
+            else if (A16) *reinterpret_cast<u32x4*>(dst) = w;
             else *reinterpret_cast<u32x4_a4*>(dst) = w;
         } else if (orow < cols && og < rows) {
             dst[0] = w.x;
@@ -118,7 +119,7 @@ __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ 
     }
 }
 
-template <int TR, int TC, bool VEC, bool NTL>
+template <int TR, int TC, bool VEC, bool NTL, bool STREAM>
 __global__ __launch_bounds__(TR_THREADS) void transpose_kernel(
     const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
     int rows, int cols, long ldin, long ldout, int tiles_r, int tiles_c)
@@ -130,12 +131,12 @@ __global__ __launch_bounds__(TR_THREADS) void transpose_kernel(
     const int c0 = tc * TC;
     // VEC: 16-byte aligned rows on both sides
     if ((r0 + TR <= rows) && (c0 + TC <= cols))
-        transpose_tile_vec<TR, TC, NTL, false, VEC>(in, out, tile, rows, cols, ldin, ldout, r0, c0);
+        transpose_tile_vec<TR, TC, NTL, false, VEC, STREAM>(in, out, tile, rows, cols, ldin, ldout, r0, c0);
     else
-        transpose_tile_vec<TR, TC, NTL, true, VEC>(in, out, tile, rows, cols, ldin, ldout, r0, c0);
+        transpose_tile_vec<TR, TC, NTL, true, VEC, STREAM>(in, out, tile, rows, cols, ldin, ldout, r0, c0);
 }
 
-template <int TR, int TC, bool VEC, bool NTL>
+template <int TR, int TC, bool VEC, bool NTL, bool STREAM>
 static int launch_transpose_t(hipStream_t s, int rows, int cols, const uint32_t* in, long ldin,
                               uint32_t* out, long ldout)
 {
@@ -144,7 +145,7 @@ static int launch_transpose_t(hipStream_t s, int rows, int cols, const uint32_t*
     const long long nblocks = (long long)tiles_c * tiles_r;
     if (nblocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
     constexpr size_t lds = (size_t)TR * TC * sizeof(uint32_t);
-    auto kern = transpose_kernel<TR, TC, VEC, NTL>;
+    auto kern = transpose_kernel<TR, TC, VEC, NTL, STREAM>;
     if (lds > 64 * 1024) {
         // opt in to the large LDS carve-out once per device
         static std::atomic<bool> raised[16] = {};
@@ -171,14 +172,20 @@ int launch_transpose(hipStream_t s, int rows, int cols, const float* in, long ld
     const uint32_t* pin = reinterpret_cast<const uint32_t*>(in);
     uint32_t* pout = reinterpret_cast<uint32_t*>(out);
     const long long elems = (long long)rows * cols;
-    if (elems >= (1LL << 26) && rows >= 256 && cols >= 64)
-        return vec ? launch_transpose_t<256, 64, true, true>(s, rows, cols, pin, ldin, pout, ldout)
-                   : launch_transpose_t<256, 64, false, true>(s, rows, cols, pin, ldin, pout, ldout);
-    if (elems > (1LL << 24) && cols >= 64)
-        return vec ? launch_transpose_t<128, 64, true, true>(s, rows, cols, pin, ldin, pout, ldout)
-                   : launch_transpose_t<128, 64, false, true>(s, rows, cols, pin, ldin, pout, ldout);
-    return vec ? launch_transpose_t<128, 32, true, false>(s, rows, cols, pin, ldin, pout, ldout)
-               : launch_transpose_t<128, 32, false, false>(s, rows, cols, pin, ldin, pout, ldout);
+    // Results are written past the caches only when every output row segment (TR words at a multiple of
+    // TR words within its row) is whole 128-byte lines, i.e. the rows of `out` start on lines.  Otherwise
+    // a segment shares its end lines with the neighbouring tiles' segments, and ordinary stores let the
+    // pieces meet in L2 instead of each going to memory as a partial line (4500 x 1500, whose output
+    // rows are 18000 bytes: 14.5 us streamed).
+    const bool whole_lines = vec && (ldout % 32 == 0) && ((reinterpret_cast<uintptr_t>(out) & 127) == 0);
+#define MTNN_TRANSPOSE(TR, TC, NTL)                                                                                   \
+    (vec ? (whole_lines ? launch_transpose_t<TR, TC, true, NTL, true>(s, rows, cols, pin, ldin, pout, ldout)            \
+                        : launch_transpose_t<TR, TC, true, NTL, false>(s, rows, cols, pin, ldin, pout, ldout))          \
+         : launch_transpose_t<TR, TC, false, NTL, false>(s, rows, cols, pin, ldin, pout, ldout))
+    if (elems >= (1LL << 26) && rows >= 256 && cols >= 64) return MTNN_TRANSPOSE(256, 64, true);
+    if (elems > (1LL << 24) && cols >= 64) return MTNN_TRANSPOSE(128, 64, true);
+    return MTNN_TRANSPOSE(128, 32, false);
+#undef MTNN_TRANSPOSE
 }
 
 // ---- in-place transpose of a square matrix -------------------------------------------------------

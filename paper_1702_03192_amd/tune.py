@@ -72,7 +72,7 @@ def collect(out_path, samples, min_batch_us, odd_ld):
                             while splits <= 32:
                                 if splits > 1 and (k // splits < 128 or m * n * splits * 4 > SCRATCH_BYTES):
                                     break
-                                t, _ = _time_batches(lambda: mt.mtnn_gemm_ex(op, cfg, A, B, C, splits=splits),
+                                t, _ = _time_batches(mt.prepare_gemm_ex(op, cfg, A, B, C, splits=splits),
                                                      stream, samples, min_batch_us)
                                 wr.writerow([op, m, n, k, cfg, splits, "%.9g" % t])
                                 splits *= 2

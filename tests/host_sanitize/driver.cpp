@@ -3,6 +3,7 @@
 // tests/test_sanitize_host.py).  Prints "ALL OK" and exits 0 when every check holds and the
 // sanitizers stayed silent.
 #include "../../include/mtnn.h"
+#include "gemm_config.h"
 
 #include <cmath>
 #include <cstdint>
@@ -79,6 +80,50 @@ static void cost_model()
     }
     CHECK(mtnn_gemm_choice(3, 4, 4, 4, 0, nullptr, nullptr) == MTNN_ERR_ARG);
     CHECK(mtnn_gemm_choice(1, 0, 4, 4, 0, nullptr, nullptr) == MTNN_ERR_DIM);
+}
+
+// the multiply-high division the kernels use for the tile mapping, against the machine's own division
+static void fast_division()
+{
+    const unsigned ds[] = {1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 63, 64, 65, 127, 255, 256, 257, 1000, 4095, 4096, 4097, 65535, 65536, 65537,
+                           1000003, (1u << 20) + 1, (1u << 30) - 1, 1u << 30, (1u << 30) + 1, 0x7ffffffeu, 0x7fffffffu};
+    unsigned s = 99;
+    for (unsigned d : ds) {
+        const mtnn::FastDiv f = mtnn::make_fastdiv(d);
+        const unsigned long long edge[] = {0, 1, d - 1ull, d, d + 1ull, 2ull * d - 1, 2ull * d, 3ull * d - 1, 0x7fffffffull, 0x7ffffffeull,
+                                           0x40000000ull, 0x3fffffffull};
+        for (unsigned long long n : edge) if (n <= 0x7fffffffull) CHECK(mtnn::fast_div((int)n, f) == (int)((unsigned)n / d));
+        for (int it = 0; it < 20000; ++it) {
+            s = s * 1664525u + 1013904223u;
+            const int n = (int)(s >> 1);
+            if (mtnn::fast_div(n, f) != (int)((unsigned)n / d)) { CHECK(!"fast_div differs"); break; }
+        }
+    }
+    // the tile order as the kernels compute it, against plain divisions, over many grids
+    for (int tiles_m : {1, 2, 3, 7, 8, 9, 16, 33, 128, 1000}) for (int tiles_n : {1, 2, 5, 8, 64, 129}) for (int xcd : {1, 8}) {
+        mtnn::GemmParams p = {};
+        p.tiles_m = tiles_m; p.tiles_n = tiles_n; p.group_m = tiles_m < 8 ? tiles_m : 8; p.num_xcd = xcd;
+        mtnn::set_tile_order(p);
+        const int total = tiles_m * tiles_n;
+        std::vector<char> seen(total, 0);
+        for (int pid0 = 0; pid0 < total; ++pid0) {
+            int pid = pid0;
+            if (p.num_xcd > 1) {
+                const int local = mtnn::fast_div(pid, p.fd_xcd), x = pid - local * p.num_xcd;
+                CHECK(local == pid / p.num_xcd);
+                pid = (x < p.xcd_tall) ? x * p.xcd_per + local : p.xcd_tall * p.xcd_per + (x - p.xcd_tall) * (p.xcd_per - 1) + local;
+            }
+            const int band_sz = p.group_m * p.tiles_n, band = mtnn::fast_div(pid, p.fd_band);
+            CHECK(band == pid / band_sz);
+            const int in_band = pid - band * band_sz;
+            const bool last = band == p.last_band;
+            const int rows_here = last ? p.last_rows : p.group_m;
+            const int tn = mtnn::fast_div(in_band, last ? p.fd_last : p.fd_group);
+            const int tm = band * p.group_m + (in_band - tn * rows_here);
+            CHECK(tn == in_band / rows_here && tm >= 0 && tm < tiles_m && tn >= 0 && tn < tiles_n);
+            if (tm >= 0 && tm < tiles_m && tn >= 0 && tn < tiles_n) { CHECK(!seen[tm * tiles_n + tn]); seen[tm * tiles_n + tn] = 1; }
+        }
+    }
 }
 
 static void selector(const char* tmpdir)
@@ -173,6 +218,7 @@ int main(int argc, char** argv)
     const char* tmpdir = argc > 1 ? argv[1] : "/tmp";
     abi_validation();
     cost_model();
+    fast_division();
     selector(tmpdir);
     oracle();
     if (g_failed) { std::printf("%d checks failed\n", g_failed); return 1; }
