@@ -337,6 +337,13 @@ MTNN_API int mtnn_copy_rows(void *stream, int rows, int cols, const float *in, f
  * write-once kernel such as the transpose can be compared with. */
 MTNN_API int mtnn_copy_bytes(void *stream, size_t bytes, const void *in, void *out);
 
+/* One workgroup per compute unit, two waves per SIMD: one issues n_mfma fp32 matrix instructions,
+ * the other n_valu fp32 vector multiply-adds (either count may be 0); `sink` is 512 floats of device
+ * memory that are never written in practice.  Timing the three combinations shows whether the two
+ * kinds of work overlap on this device (they do not: see csrc/probe.hip), which is what the kernels'
+ * instruction budget around the k loop rests on. */
+MTNN_API int mtnn_probe_lanes(void *stream, int n_mfma, int n_valu, float *sink);
+
 /* ---- misc ---------------------------------------------------------------------------------- */
 
 MTNN_API const char *mtnn_status_string(int status);

@@ -96,6 +96,7 @@ SIGNATURES = {
                                          _c_vp, _c_int, _c_flt]),
     "mtnn_copy_rows": (_c_int, [_c_vp, _c_int, _c_int, _c_vp, _c_vp]),
     "mtnn_copy_bytes": (_c_int, [_c_vp, _c_sz, _c_vp, _c_vp]),
+    "mtnn_probe_lanes": (_c_int, [_c_vp, _c_int, _c_int, _c_vp]),
     "mtnn_status_string": (ctypes.c_char_p, [_c_int]),
     "mtnn_last_hip_error": (_c_int, []),
     "mtnn_version": (_c_int, []),
@@ -571,6 +572,11 @@ def mtnn_copy_bytes(src, dst, stream=None):
         raise ValueError("size mismatch")
     _check(lib().mtnn_copy_bytes(_stream(stream), nbytes, src.data_ptr(), dst.data_ptr()), "mtnn_copy_bytes")
     return dst
+
+
+def mtnn_probe_lanes(n_mfma: int, n_valu: int, sink, stream=None):
+    """The overlap probe of csrc/probe.hip: n_mfma matrix instructions and n_valu vector multiply-adds per SIMD."""
+    _check(lib().mtnn_probe_lanes(_handle(stream) or None, n_mfma, n_valu, sink.data_ptr()), "mtnn_probe_lanes")
 
 
 def mtnn_gemm_default_splits(op: int, m: int, n: int, k: int) -> int:

@@ -18,25 +18,24 @@ namespace mtnn {
 
 const TileConfig kTileConfigs[] = {
     //  set   tile         waves stages    per CU   NN: eff, round      NT: eff, round       guarded kernel: NN, NT
-    // (0: NT carries NN's pair: since its epilogue stores straight from registers like NN's, the two measure
-    //  the same -- 143.4 TFLOP/s both at 8192 x 8192 x 1024, 122.2 / 122.3 at k = 256; its own fit, 0.943 and
-    //  13.3 us, dates from the staged epilogue)
-    MTNN_TILE(0, 256, 256, 32, 4, 2, 2, 16,   1,   0.949f, 13.8e-6f,   0.949f, 13.8e-6f,   0.871f, 12.7e-6f, 0.842f, 11.5e-6f),  // 0: 8 waves of 64 x 128, 128 KB of LDS
-    // (1: the fits put it level with configuration 0 inside the grid; beyond it the narrower tile
+    MTNN_TILE(0, 256, 256, 32, 4, 2, 2, 16,   1,   0.951f, 12.9e-6f,   0.948f, 12.4e-6f,   0.871f, 12.7e-6f, 0.842f, 11.5e-6f),  // 0: 8 waves of 64 x 128, 128 KB of LDS
+    // (1: the fits put it level with configuration 0 inside the grid (0.953 / 0.944); beyond it the narrower tile
     //  re-reads more of A and falls behind -- NN 135 against 148 TFLOP/s at 65536^3, NT 139 against 148 at
     //  65536 x 256 x 32768 and 146 against 149 at 16384^3 -- so both operations rate it just below)
-    MTNN_TILE(1, 256, 128, 16, 2, 2, 3, 16,   2,   0.943f, 11.9e-6f,   0.937f, 12.8e-6f,   0.840f, 9.8e-6f, 0.848f, 10.6e-6f),  // 1: 4 waves of 128 x 64, 72 KB
-    MTNN_TILE(2, 128, 128, 64, 4, 2, 2, 16,   1,   0.884f, 4.0e-6f,   0.886f, 3.7e-6f,   0.802f, 2.1e-6f, 0.776f, 2.0e-6f),   // 2: 8 waves of 32 x 64, 128 KB
-    MTNN_TILE(3, 64, 64, 64, 2, 2, 2, 16,     2,   0.886f, 2.9e-6f,   0.865f, 2.2e-6f,   0.688f, 1.1e-6f, 0.680f, 1.1e-6f),   // 3: 4 waves of 32 x 32, 64 KB
-    MTNN_TILE(4, 32, 256, 32, 1, 4, 2, 16,    2,   0.903f, 2.9e-6f,   0.892f, 3.0e-6f,   0.698f, 1.7e-6f, 0.621f, 2.0e-6f),   // 4: 4 waves of 32 x 64 (small m), 72 KB
-    MTNN_TILE(5, 256, 32, 32, 4, 1, 2, 16,    2,   0.869f, 3.9e-6f,   0.885f, 3.0e-6f,   0.567f, 1.9e-6f, 0.535f, 1.4e-6f),   // 5: 4 waves of 64 x 32 (small n), 72 KB
-    MTNN_TILE(6, 128, 256, 32, 2, 4, 2, 16,   1,   0.927f, 6.9e-6f,   0.926f, 6.8e-6f,   0.822f, 5.9e-6f, 0.795f, 4.0e-6f),   // 6: 8 waves of 64 x 64, 96 KB
-    MTNN_TILE(7, 256, 128, 32, 4, 2, 2, 16,   1,   0.920f, 7.1e-6f,   0.925f, 7.2e-6f,   0.837f, 4.8e-6f, 0.805f, 4.5e-6f),   // 7: 8 waves of 64 x 64, 96 KB
-    MTNN_TILE(8, 128, 64, 32, 2, 2, 2, 16,    2,   0.885f, 3.6e-6f,   0.910f, 2.7e-6f,   0.740f, 1.9e-6f, 0.728f, 2.0e-6f),   // 8: 4 waves of 64 x 32, 48 KB
-    MTNN_TILE(9, 64, 128, 32, 2, 2, 2, 16,    2,   0.904f, 2.9e-6f,   0.913f, 2.7e-6f,   0.783f, 2.0e-6f, 0.743f, 1.8e-6f),   // 9: 4 waves of 32 x 64, 48 KB
-    MTNN_TILE(10, 128, 128, 32, 2, 2, 2, 16,  2,   0.906f, 5.0e-6f,   0.933f, 5.3e-6f,   0.820f, 4.2e-6f, 0.789f, 4.3e-6f),   // 10: 4 waves of 64 x 64, 64 KB
-    MTNN_TILE(8, 128, 64, 32, 2, 2, 2, 16,    3,   0.839f, 3.4e-6f,   0.897f, 2.1e-6f,   0.753f, 2.1e-6f, 0.734f, 2.3e-6f),   // 11: as 8, three per CU (small k)
-    MTNN_TILE(9, 64, 128, 32, 2, 2, 2, 16,    3,   0.907f, 3.0e-6f,   0.898f, 2.4e-6f,   0.807f, 2.2e-6f, 0.745f, 1.9e-6f),   // 12: as 9, three per CU (small k)
+    MTNN_TILE(1, 256, 128, 16, 2, 2, 3, 16,   2,   0.945f, 10.8e-6f,   0.942f, 11.9e-6f,   0.840f, 9.8e-6f, 0.848f, 10.6e-6f),  // 1: 4 waves of 128 x 64, 72 KB
+    MTNN_TILE(2, 128, 128, 64, 4, 2, 2, 16,   1,   0.890f, 3.4e-6f,   0.890f, 3.1e-6f,   0.802f, 2.1e-6f, 0.776f, 2.0e-6f),   // 2: 8 waves of 32 x 64, 128 KB
+    // (3: the fit gives 2.0 / 1.2 us per round; with that the rule takes this tile for short-k products of a
+    //  single round where the three-per-CU tiles measure 5-10 % faster, so its rounds are rated a little dearer)
+    MTNN_TILE(3, 64, 64, 64, 2, 2, 2, 16,     2,   0.882f, 2.6e-6f,   0.854f, 1.9e-6f,   0.688f, 1.1e-6f, 0.680f, 1.1e-6f),   // 3: 4 waves of 32 x 32, 64 KB
+    MTNN_TILE(4, 32, 256, 32, 1, 4, 2, 16,    2,   0.901f, 2.2e-6f,   0.888f, 2.1e-6f,   0.698f, 1.7e-6f, 0.621f, 2.0e-6f),   // 4: 4 waves of 32 x 64 (small m), 72 KB
+    MTNN_TILE(5, 256, 32, 32, 4, 1, 2, 16,    2,   0.824f, 3.2e-6f,   0.883f, 2.4e-6f,   0.567f, 1.9e-6f, 0.535f, 1.4e-6f),   // 5: 4 waves of 64 x 32 (small n), 72 KB
+    MTNN_TILE(6, 128, 256, 32, 2, 4, 2, 16,   1,   0.934f, 6.2e-6f,   0.934f, 6.2e-6f,   0.822f, 5.9e-6f, 0.795f, 4.0e-6f),   // 6: 8 waves of 64 x 64, 96 KB
+    MTNN_TILE(7, 256, 128, 32, 4, 2, 2, 16,   1,   0.925f, 6.5e-6f,   0.928f, 6.4e-6f,   0.837f, 4.8e-6f, 0.805f, 4.5e-6f),   // 7: 8 waves of 64 x 64, 96 KB
+    MTNN_TILE(8, 128, 64, 32, 2, 2, 2, 16,    2,   0.912f, 3.3e-6f,   0.908f, 1.8e-6f,   0.740f, 1.9e-6f, 0.728f, 2.0e-6f),   // 8: 4 waves of 64 x 32, 48 KB
+    MTNN_TILE(9, 64, 128, 32, 2, 2, 2, 16,    2,   0.912f, 2.4e-6f,   0.912f, 1.9e-6f,   0.783f, 2.0e-6f, 0.743f, 1.8e-6f),   // 9: 4 waves of 32 x 64, 48 KB
+    MTNN_TILE(10, 128, 128, 32, 2, 2, 2, 16,  2,   0.932f, 4.7e-6f,   0.943f, 4.7e-6f,   0.820f, 4.2e-6f, 0.789f, 4.3e-6f),   // 10: 4 waves of 64 x 64, 64 KB
+    MTNN_TILE(8, 128, 64, 32, 2, 2, 2, 16,    3,   0.907f, 3.5e-6f,   0.901f, 1.9e-6f,   0.753f, 2.1e-6f, 0.734f, 2.3e-6f),   // 11: as 8, three per CU (small k)
+    MTNN_TILE(9, 64, 128, 32, 2, 2, 2, 16,    3,   0.915f, 2.6e-6f,   0.917f, 2.2e-6f,   0.807f, 2.2e-6f, 0.745f, 1.9e-6f),   // 12: as 9, three per CU (small k)
 };
 const int kNumTileConfigs = (int)(sizeof(kTileConfigs) / sizeof(kTileConfigs[0]));
 

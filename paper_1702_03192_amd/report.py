@@ -27,13 +27,50 @@ def roofline_seconds(m, n, k):
     return max(2.0 * m * n * k / (PEAK_TFLOPS * 1e12), 4.0 * (m * k + n * k + m * n) / (PEAK_GBS * 1e9))
 
 
+def probe_lanes(out_path):
+    """Times csrc/probe.hip's kernel with matrix work only, vector work only and both (HIP events, median of 9)."""
+    import torch
+    from . import binding as mt
+    torch.cuda.set_device(0)
+    mt.lib()
+    stream = torch.cuda.current_stream()
+    sink = torch.zeros(512, device="cuda")
+
+    def timed(nm, nv):
+        for _ in range(3):
+            mt.mtnn_probe_lanes(nm, nv, sink)
+        ts = []
+        for _ in range(9):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            mt.mtnn_probe_lanes(nm, nv, sink)
+            b.record(stream)
+            b.synchronize()
+            ts.append(a.elapsed_time(b) * 1e3)
+        return statistics.median(ts)
+
+    lines = ["| matrix instructions per SIMD | vector multiply-adds per SIMD | us | matrix alone + vector alone |", "|---|---|---|---|"]
+    for nm, nv in ((4096, 8192), (4096, 16384), (4096, 32768), (8192, 16384)):
+        t_m, t_v, t_b = timed(nm, 0), timed(0, nv), timed(nm, nv)
+        lines += [f"| {nm} | 0 | {t_m:.1f} | |", f"| 0 | {nv} | {t_v:.1f} | |", f"| {nm} | {nv} | {t_b:.1f} | {t_m + t_v:.1f} |"]
+    text = "\n".join(lines) + "\n"
+    with open(out_path, "w") as f:
+        f.write(text)
+    print(text)
+    return 0
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", required=True)
     ap.add_argument("--md", default=None)
     ap.add_argument("--samples", type=int, default=20)
     ap.add_argument("--grid-verify", action="store_true", help="time NT, TNN and auto on all 512 grid shapes")
+    ap.add_argument("--probe-lanes", action="store_true",
+                    help="only the overlap probe: fp32 matrix instructions against vector instructions of another wave")
     args = ap.parse_args(argv)
+    if args.probe_lanes:
+        return probe_lanes(args.out)
 
     import torch
     from . import binding as mt

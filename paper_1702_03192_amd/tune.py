@@ -1,7 +1,8 @@
-"""Where the cost model's numbers come from (gemm.hip: eff / round_s per configuration and operation).
+"""Where the cost model's numbers come from (gemm_cost.cpp: eff / round_s per configuration and operation).
 
   python -m paper_1702_03192_amd.tune collect --out <dir>/gemm_table.csv [--odd-ld]      (needs the GPU)
   python -m paper_1702_03192_amd.tune fit     --table <dir>/gemm_table.csv                (host only)
+  python -m paper_1702_03192_amd.tune extract --table <dir>/gemm_table.csv --out data/gemm_fit_rows_gfx950.csv   (host only)
   python -m paper_1702_03192_amd.tune even-cut --out <dir>/even_cut.csv                   (needs the GPU)
 
 collect: for every (m, n, k) of the grid {64, ..., 8192}^3, both operations, every tile configuration
@@ -15,14 +16,14 @@ fit: per configuration and operation, a least-squares fit (in relative error) of
     time = tile_units x 2 bm bn k / (eff x peak_per_CU) + rounds x round_s + 3 us
 (tile_units = tiles per CU, with a workgroup left alone at the end of a CU's share counted at its slower rate)
 over the shapes whose tiles fill all 256 CUs at the configuration's occupancy with no partial tiles
-and no split; prints the fitted (eff, round_s) in the order of the table in gemm.hip, and how far the
+and no split; prints the fitted (eff, round_s) in the order of the table in gemm_cost.cpp, and how far the
 library's compiled-in choice (mtnn_gemm_default_config / _splits) is from the best measured
 (configuration, split) pair of each shape.
 
 even-cut: on seeded shapes off the power-of-two grids (k % 4 = 0, at least 2^30 multiply-adds) and a few
 cubes, the NT time of the best unsplit or split ordinary launch among all configurations against the
 even cut (splits = EVEN_CUT) with the 64 x 128 and 128 x 128 two-per-CU configurations; fits the four
-weights of predicted_seconds_even_cut (gemm.hip) by least squares in relative error and reports where
+weights of predicted_seconds_even_cut (gemm_cost.cpp) by least squares in relative error and reports where
 the even cut wins and what the library's rule decides.
 """
 from __future__ import annotations
@@ -81,7 +82,7 @@ def collect(out_path, samples, min_batch_us, odd_ld):
 
 
 def tile_units(per_cu, occ, waves):
-    """A CU's share in tile times, as gemm.hip's cost model counts it: `per_cu` tiles worked through `occ`
+    """A CU's share in tile times, as gemm_cost.cpp's cost model counts it: `per_cu` tiles worked through `occ`
     at a time; one 4-wave workgroup left over at the end runs alone, at 0.85 of the rate (0.92 after rounds
     of three)."""
     if waves >= 8 or per_cu % occ != 1:
@@ -171,6 +172,33 @@ def fit(table_path):
           "collected without --odd-ld)")
 
 
+def extract(table_path, out_path):
+    """The part of a collected table that the numbers in the library rest on, small enough to keep under
+    version control: the rows `fit` uses (unsplit launches on shapes whose tiles fill every CU with no
+    partial tile), and per (operation, shape) the best measured (configuration, split) pair and the pair
+    the compiled-in rule chooses, from which `fit` recomputes how far the rule is from the best."""
+    from . import binding as mt
+    names = mt.gemm_configs()
+    table = load_table(table_path)
+    keep = set()
+    for (op, m, n, k), tab in table.items():
+        for c, nm in enumerate(names):
+            bm, bn, occ = _config_geometry(nm)
+            if (c, 1) in tab and m % bm == 0 and n % bn == 0 and (m // bm) * (n // bn) >= 256 * occ:
+                keep.add((op, m, n, k, c, 1))
+        best = min(tab, key=tab.get)
+        keep.add((op, m, n, k) + best)
+        chosen = (mt.mtnn_gemm_default_config(op, m, n, k), mt.mtnn_gemm_default_splits(op, m, n, k))
+        if chosen in tab:
+            keep.add((op, m, n, k) + chosen)
+    with open(out_path, "w", newline="") as f:
+        wr = csv.writer(f)
+        wr.writerow(["op", "m", "n", "k", "cfg", "splits", "seconds"])
+        for key in sorted(keep):
+            wr.writerow(list(key) + ["%.5g" % table[key[:4]][key[4:]]])
+    print(f"[tune] kept {len(keep)} of {sum(len(v) for v in table.values())} rows in {out_path}")
+
+
 def even_cut(out_path, samples, min_batch_us, count):
     import numpy as np
     import torch
@@ -219,7 +247,7 @@ def even_cut(out_path, samples, min_batch_us, count):
         wr.writeheader()
         wr.writerows(rows)
     # the four weights: time = a x k-loop + b x segments x round_s + c x fix-up bytes / 4e12 + d,
-    # with the NT k-loop rate and per-round time of the two configurations as compiled into gemm.hip
+    # with the NT k-loop rate and per-round time of the two configurations as compiled into gemm_cost.cpp
     compiled = {"64x128x32_w2x2_dma2_x2": (0.913, 2.7e-6), "128x128x32_w2x2_dma2_x2": (0.933, 5.3e-6)}
     X, y = [], []
     for r in rows:
@@ -263,6 +291,9 @@ def main(argv=None):
     c.add_argument("--odd-ld", action="store_true")
     f = sub.add_parser("fit")
     f.add_argument("--table", required=True)
+    x = sub.add_parser("extract")
+    x.add_argument("--table", required=True)
+    x.add_argument("--out", required=True)
     e = sub.add_parser("even-cut")
     e.add_argument("--out", required=True)
     e.add_argument("--samples", type=int, default=7)
@@ -271,6 +302,8 @@ def main(argv=None):
     args = ap.parse_args(argv)
     if args.cmd == "collect":
         collect(args.out, args.samples, args.min_batch_us, args.odd_ld)
+    elif args.cmd == "extract":
+        extract(args.table, args.out)
     elif args.cmd == "even-cut":
         even_cut(args.out, args.samples, args.min_batch_us, args.count)
     else:
