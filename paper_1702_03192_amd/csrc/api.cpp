@@ -288,15 +288,15 @@ int mtnn_tnn_inplace(void* stream, int m, int n, int k, const float* A, int lda,
 
 // Does TNN through in-place transposes promise to beat NT?  The cost model's estimates of the two
 // products, and two in-place transposes of B at their measured rates (8 bytes per word moved): the
-// square kernel, one pass of tile swaps, ~4.1 TB/s; the rectangular one, two or three passes with
-// index arithmetic per word, 0.2-0.7 TB/s (0.35 taken).
+// square kernel, one pass of tile swaps, ~4.1 TB/s; the rectangular one, two or three passes over the
+// buffer, 0.9-2.2 TB/s (1.2 taken, and three launches).
 static bool inplace_pays(int m, int n, int k)
 {
     const mtnn::Geometry geo = mtnn::geometry_or_nominal();
     const double t_nt = mtnn::gemm_predicted_seconds(geo, mtnn::OP_NT, m, n, k, kDefaultScratchBytes);
     const double t_nn = mtnn::gemm_predicted_seconds(geo, mtnn::OP_NN, m, n, k, kDefaultScratchBytes);
     const double bytes = 8.0 * (double)n * (double)k;
-    const double t_ip = (n == k) ? bytes / 4.1e12 + 3e-6 : bytes / 0.35e12 + 10e-6;
+    const double t_ip = (n == k) ? bytes / 4.1e12 + 3e-6 : bytes / 1.2e12 + 12e-6;
     return t_nt - t_nn > 2.0 * t_ip;
 }
 

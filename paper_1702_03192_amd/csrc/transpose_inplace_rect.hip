@@ -22,8 +22,18 @@
 //           l' = i' C + j', and sits in row (i + floor(j / b)) mod R.
 // Each pass loads its rows / column panel into LDS, synchronises, and writes back, so reads of a
 // row (panel) complete before its writes; different rows (panels) do not interact.
+//
+// The three passes take an R x C buffer to C x R while working on columns of R words.  Run backwards
+// (the inverse of pass 2, of pass 1, of pass 0: the same index formulas with the gather on the other
+// side of LDS) they take a C x R buffer to R x C, still working on columns of R words.  The launcher
+// takes whichever direction makes the columns the shorter dimension: a column panel in LDS is then as
+// wide as it can be (global accesses of up to 128 bytes per row of the panel) and there are many panels.
+// Column panels are dealt to the XCDs in contiguous ranges, so that the panels in flight on one XCD
+// share the cache lines they each use a few words of.  Divisions by R, C, b are multiply-high with
+// host-made constants.
 // Limits: R, C <= 32768 (a row, or one column of R words, must fit 128 KB of LDS).
 #include "mtnn_internal.h"
+#include "gemm_config.h"
 
 #include <atomic>
 
@@ -31,14 +41,20 @@ namespace mtnn {
 
 namespace {
 
-constexpr int kRectThreads = 256;
+constexpr int kRectThreads = 1024;
 constexpr unsigned kRectLdsWords = 32768;       // 128 KB
 
 struct RectGeom {
-    unsigned R, C, g, b;      // rows, cols, gcd, C / g
+    unsigned R, C, b;          // rows and columns of the view the passes work in, C / gcd(R, C)
+    FastDiv fdR, fdC, fdb;
 };
 
-// pass 1: one workgroup permutes `rows_per_wg` consecutive rows; scatter into LDS, linear write back
+__device__ __forceinline__ unsigned udiv(unsigned n, FastDiv f) { return (unsigned)fast_div((int)n, f); }
+
+// pass 1: one workgroup permutes `rows_per_wg` consecutive rows.  Forward: row r sends column j to
+// column jp(r, j), scattered into LDS and written back in order.  INVERSE: column j takes the word of
+// column jp(r, j), the rows copied to LDS in order and gathered from there.
+template <bool INVERSE>
 __global__ __launch_bounds__(kRectThreads) void rect_row_pass(uint32_t* __restrict__ X, RectGeom q, unsigned rows_per_wg)
 {
     extern __shared__ uint32_t buf[];
@@ -46,49 +62,72 @@ __global__ __launch_bounds__(kRectThreads) void rect_row_pass(uint32_t* __restri
     const unsigned nrows = min(rows_per_wg, q.R - r0);
     const unsigned total = nrows * q.C;
     uint32_t* base = X + (size_t)r0 * q.C;
+    if (INVERSE) {
+        for (unsigned e = threadIdx.x; e < total; e += kRectThreads) buf[e] = base[e];
+        __syncthreads();
+    }
     for (unsigned e = threadIdx.x; e < total; e += kRectThreads) {
-        const unsigned rr = e / q.C;
+        const unsigned rr = udiv(e, q.fdC);
         const unsigned j = e - rr * q.C;
         const unsigned r = r0 + rr;
-        const unsigned u = j / q.b;                              // rotation pass 0 applied to column j
+        const unsigned u = udiv(j, q.fdb);                       // rotation of pass 0 applied to column j
         const unsigned i = (r >= u) ? r - u : r + q.R - u;       // the row the word came from (u < g <= R)
-        const unsigned jp = (j * q.R + i) % q.C;               // j R + i < 2^30 + 2^15 within the size limits
-        buf[rr * q.C + jp] = base[e];
+        const unsigned t = j * q.R + i;                          // < 2^30 + 2^15 within the size limits
+        const unsigned jp = t - udiv(t, q.fdC) * q.C;
+        if (INVERSE) base[e] = buf[rr * q.C + jp];
+        else buf[rr * q.C + jp] = base[e];
     }
-    __syncthreads();
-    for (unsigned e = threadIdx.x; e < total; e += kRectThreads) base[e] = buf[e];
+    if (!INVERSE) {
+        __syncthreads();
+        for (unsigned e = threadIdx.x; e < total; e += kRectThreads) base[e] = buf[e];
+    }
 }
 
-// passes 0 and 2: one workgroup permutes a panel of `w` adjacent columns (all R rows) by a gather
-// whose source row depends on (output row, column).  FINAL = false: pass 0; true: pass 2.
-template <bool FINAL>
-__global__ __launch_bounds__(kRectThreads) void rect_col_pass(uint32_t* __restrict__ X, RectGeom q, unsigned w)
+// passes 0 and 2: one workgroup permutes a panel of w = 2^lw adjacent columns (all R rows) within its
+// columns.  The forward pass moves the word of row src(ip, jp) to row ip; FINAL = false: pass 0, true:
+// pass 2.  INVERSE moves the word of row ip to row src(ip, jp).
+template <bool FINAL, bool INVERSE>
+__global__ __launch_bounds__(kRectThreads) void rect_col_pass(uint32_t* __restrict__ X, RectGeom q, unsigned lw,
+                                                              unsigned panels, unsigned panels_per_xcd, unsigned num_xcd)
 {
     extern __shared__ uint32_t buf[];
-    const unsigned j0 = blockIdx.x * w;
-    const unsigned nw = min(w, q.C - j0);
-    const unsigned total = q.R * w;                              // panel slots, row-major with stride w
-    for (unsigned e = threadIdx.x; e < total; e += kRectThreads) {
-        const unsigned r = e / w, jj = e - r * w;
-        if (jj < nw) buf[e] = X[(size_t)r * q.C + j0 + jj];
-    }
-    __syncthreads();
-    for (unsigned e = threadIdx.x; e < total; e += kRectThreads) {
-        const unsigned ip = e / w, jj = e - ip * w;
-        if (jj >= nw) continue;
-        const unsigned jp = j0 + jj;
-        unsigned src;
+    // consecutive workgroup ids go to different XCDs: give each XCD a contiguous range of panels
+    const unsigned xcd = blockIdx.x % num_xcd;
+    const unsigned panel = xcd * panels_per_xcd + blockIdx.x / num_xcd;
+    if (blockIdx.x / num_xcd >= panels_per_xcd || panel >= panels) return;      // uniform per workgroup
+    const unsigned w = 1u << lw;
+    const unsigned j0 = panel << lw;
+    const unsigned jj = threadIdx.x & (w - 1);
+    const unsigned jp = j0 + jj;
+    const unsigned row0 = threadIdx.x >> lw, step = kRectThreads >> lw;
+    const bool live = jp < q.C;                                   // false: a column past the edge of the last panel
+    uint32_t* col = X + jp;
+    const unsigned u0 = FINAL ? 0u : udiv(jp, q.fdb);
+
+    auto source_row = [&](unsigned ip) -> unsigned {
         if (FINAL) {
             const unsigned l = ip * q.C + jp;                    // < R C <= 2^30
-            const unsigned j = l / q.R;
-            const unsigned i = l - j * q.R;
-            src = i + j / q.b;                                   // < R + g <= 2 R
+            const unsigned j = udiv(l, q.fdR);
+            unsigned src = (l - j * q.R) + udiv(j, q.fdb);       // < R + g <= 2 R
             if (src >= q.R) src -= q.R;
-        } else {
-            const unsigned u = jp / q.b;
-            src = (ip >= u) ? ip - u : ip + q.R - u;
+            return src;
         }
-        X[(size_t)ip * q.C + jp] = buf[src * w + jj];
+        return (ip >= u0) ? ip - u0 : ip + q.R - u0;
+    };
+
+    // every lane reaches the one barrier: lanes of one wave may differ in `live`
+    if (INVERSE) {
+        if (live)
+            for (unsigned ip = row0; ip < q.R; ip += step) buf[(source_row(ip) << lw) + jj] = col[(size_t)ip * q.C];
+        __syncthreads();
+        if (live)
+            for (unsigned r = row0; r < q.R; r += step) col[(size_t)r * q.C] = buf[(r << lw) + jj];
+    } else {
+        if (live)
+            for (unsigned r = row0; r < q.R; r += step) buf[(r << lw) + jj] = col[(size_t)r * q.C];
+        __syncthreads();
+        if (live)
+            for (unsigned ip = row0; ip < q.R; ip += step) col[(size_t)ip * q.C] = buf[(source_row(ip) << lw) + jj];
     }
 }
 
@@ -102,7 +141,7 @@ template <typename K>
 hipError_t allow_big_lds(K kern, size_t bytes, int slot)
 {
     if (bytes <= 64 * 1024) return hipSuccess;
-    static std::atomic<unsigned long long> raised[3] = {};       // bit per device, per kernel
+    static std::atomic<unsigned long long> raised[6] = {};       // bit per device, per kernel
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return hipGetLastError();
     const unsigned long long bit = (dev >= 0 && dev < 64) ? (1ull << dev) : 0;
@@ -111,6 +150,31 @@ hipError_t allow_big_lds(K kern, size_t bytes, int slot)
                                              (int)(kRectLdsWords * sizeof(uint32_t)));
     if (e == hipSuccess && bit) raised[slot].fetch_or(bit);
     return e;
+}
+
+struct ColLaunch {
+    unsigned lw, panels, per_xcd, num_xcd, grid;
+    size_t lds;
+};
+
+template <bool FINAL, bool INVERSE>
+hipError_t run_col_pass(hipStream_t s, uint32_t* p, const RectGeom& q, const ColLaunch& c, int slot)
+{
+    hipError_t e = allow_big_lds(rect_col_pass<FINAL, INVERSE>, c.lds, slot);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((rect_col_pass<FINAL, INVERSE>), dim3(c.grid), dim3(kRectThreads), c.lds, s, p, q, c.lw, c.panels,
+                       c.per_xcd, c.num_xcd);
+    return hipGetLastError();
+}
+
+template <bool INVERSE>
+hipError_t run_row_pass(hipStream_t s, uint32_t* p, const RectGeom& q, unsigned rpw, int slot)
+{
+    const size_t lds = (size_t)rpw * q.C * sizeof(uint32_t);
+    hipError_t e = allow_big_lds(rect_row_pass<INVERSE>, lds, slot);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(rect_row_pass<INVERSE>, dim3((q.R + rpw - 1) / rpw), dim3(kRectThreads), lds, s, p, q, rpw);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -124,34 +188,44 @@ int launch_transpose_inplace_rect(hipStream_t s, int rows, int cols, float* X)
 {
     if (rows <= 1 || cols <= 1) return 0;                        // a vector: both layouts are the same words
     if (!transpose_inplace_rect_supported(rows, cols)) return (int)hipErrorInvalidValue;
+    // forward: the buffer is R x C = rows x cols; backward: it is C x R with R = cols, C = rows.
+    // Either way the passes see an R x C view; R is the shorter dimension.
+    const bool inverse = rows > cols;
     RectGeom q;
-    q.R = (unsigned)rows;
-    q.C = (unsigned)cols;
-    q.g = gcd_u(q.R, q.C);
-    q.b = q.C / q.g;
+    q.R = (unsigned)(inverse ? cols : rows);
+    q.C = (unsigned)(inverse ? rows : cols);
+    const unsigned g = gcd_u(q.R, q.C);
+    q.b = q.C / g;
+    q.fdR = make_fastdiv(q.R);
+    q.fdC = make_fastdiv(q.C);
+    q.fdb = make_fastdiv(q.b);
     uint32_t* p = reinterpret_cast<uint32_t*>(X);
-    // column panels: as wide as LDS allows, at most 32 words (one 128-byte line per row)
-    unsigned w = 32;
-    while (w > 1 && (unsigned long long)q.R * w > kRectLdsWords) w >>= 1;
-    const unsigned panels = (q.C + w - 1) / w;
-    const size_t col_lds = (size_t)q.R * w * sizeof(uint32_t);
-    // rows per workgroup: about 8 K words of work each
-    unsigned rpw = 8192 / q.C;
+    // column panels: as wide as LDS allows, at most 32 words (one 128-byte line per row), and
+    // narrower (down to 32 bytes per row) while there are fewer than two panels per CU
+    ColLaunch c;
+    c.lw = 5;
+    while (c.lw > 0 && ((unsigned long long)q.R << c.lw) > kRectLdsWords) --c.lw;
+    const unsigned want_panels = 2u * (unsigned)geometry_or_nominal().cus;
+    while (c.lw > 3 && ((q.C + (1u << c.lw) - 1) >> c.lw) < want_panels) --c.lw;
+    c.panels = (q.C + (1u << c.lw) - 1) >> c.lw;
+    c.num_xcd = (unsigned)geometry_or_nominal().xcds;
+    if (c.num_xcd < 1 || c.panels < 4 * c.num_xcd) c.num_xcd = 1;
+    c.per_xcd = (c.panels + c.num_xcd - 1) / c.num_xcd;
+    c.grid = c.per_xcd * c.num_xcd;
+    c.lds = ((size_t)q.R << c.lw) * sizeof(uint32_t);
+    // rows per workgroup: about 16 K words of work each (two workgroups per CU)
+    unsigned rpw = 16384 / q.C;
     if (rpw < 1) rpw = 1;
-    const unsigned row_groups = (q.R + rpw - 1) / rpw;
-    const size_t row_lds = (size_t)rpw * q.C * sizeof(uint32_t);
     hipError_t e;
-    if (q.g > 1) {
-        if ((e = allow_big_lds(rect_col_pass<false>, col_lds, 0)) != hipSuccess) return (int)e;
-        hipLaunchKernelGGL(rect_col_pass<false>, dim3(panels), dim3(kRectThreads), col_lds, s, p, q, w);
-        if ((e = hipGetLastError()) != hipSuccess) return (int)e;
+    if (!inverse) {
+        if (g > 1 && (e = run_col_pass<false, false>(s, p, q, c, 0)) != hipSuccess) return (int)e;
+        if ((e = run_row_pass<false>(s, p, q, rpw, 1)) != hipSuccess) return (int)e;
+        return (int)run_col_pass<true, false>(s, p, q, c, 2);
     }
-    if ((e = allow_big_lds(rect_row_pass, row_lds, 1)) != hipSuccess) return (int)e;
-    hipLaunchKernelGGL(rect_row_pass, dim3(row_groups), dim3(kRectThreads), row_lds, s, p, q, rpw);
-    if ((e = hipGetLastError()) != hipSuccess) return (int)e;
-    if ((e = allow_big_lds(rect_col_pass<true>, col_lds, 2)) != hipSuccess) return (int)e;
-    hipLaunchKernelGGL(rect_col_pass<true>, dim3(panels), dim3(kRectThreads), col_lds, s, p, q, w);
-    return (int)hipGetLastError();
+    if ((e = run_col_pass<true, true>(s, p, q, c, 3)) != hipSuccess) return (int)e;
+    if ((e = run_row_pass<true>(s, p, q, rpw, 4)) != hipSuccess) return (int)e;
+    if (g > 1) return (int)run_col_pass<false, true>(s, p, q, c, 5);
+    return 0;
 }
 
 }  // namespace mtnn

@@ -21,6 +21,10 @@ PEAK_TFLOPS = 157.3
 PEAK_GBS = 8000.0
 
 TRANSPOSES = [(16384, 16384), (8192, 8192), (4096, 4096), (4096, 1024), (1024, 4096), (1024, 10), (4500, 1500)]
+INPLACE_TRANSPOSES = [(16384, 16384), (8192, 8192), (4096, 4096), (8192, 4096), (4096, 8192), (4096, 1024), (1024, 4096),
+                      (4500, 1500), (4099, 1009)]
+LAUNCH_PATH_GEMMS = [(64, 64, 64), (256, 256, 256), (512, 512, 512), (1000, 1000, 1000), (1024, 1024, 1024)]
+LAUNCH_PATH_TRANSPOSES = [(4096, 1024), (4500, 1500), (4096, 4096)]
 
 
 def roofline_seconds(m, n, k):
@@ -60,6 +64,51 @@ def probe_lanes(out_path):
     return 0
 
 
+def launch_path(out_path, calls=400):
+    """Short calls, to set the time per call (HIP events around `calls` back-to-back prepared launches on
+    one stream) beside the time inside the kernel (what a kernel trace of this same run reports per
+    dispatch): the difference is the launch path, host and GPU side."""
+    import torch
+    from . import binding as mt
+    torch.cuda.set_device(0)
+    mt.lib()
+    stream = torch.cuda.current_stream()
+    cfgs = mt.gemm_configs()
+    rows = []
+
+    def per_call(fn):
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(calls):
+            fn()
+        b.record(stream)
+        b.synchronize()
+        return a.elapsed_time(b) * 1e3 / calls
+
+    for m, n, k in LAUNCH_PATH_GEMMS:
+        A = torch.rand((m, k), device="cuda")
+        B = torch.rand((n, k), device="cuda")
+        C = torch.empty((m, n), device="cuda")
+        ws = torch.empty(mt.mtnn_tnn_workspace_bytes(n, k), dtype=torch.uint8, device="cuda")
+        for name, fn in (("mtnn_nt", mt.prepare_nt(A, B, C)), ("mtnn_auto", mt.prepare_auto(A, B, C, ws)),
+                         ("mtnn_nt, plain wrapper", lambda: mt.mtnn_nt(A, B, C))):
+            rows.append({"call": name, "shape": [m, n, k], "us_per_call": per_call(fn), "calls": calls + 20,
+                         "config": cfgs[mt.mtnn_gemm_default_config(mt.OP_NT, m, n, k)],
+                         "splits": mt.mtnn_gemm_default_splits(mt.OP_NT, m, n, k)})
+            print("[launch-path]", json.dumps(rows[-1]), flush=True)
+    for r, c in LAUNCH_PATH_TRANSPOSES:
+        X = torch.rand((r, c), device="cuda")
+        Y = torch.empty((c, r), device="cuda")
+        rows.append({"call": "mtnn_transpose", "shape": [r, c], "us_per_call": per_call(mt.prepare_transpose(X, Y)), "calls": calls + 20})
+        print("[launch-path]", json.dumps(rows[-1]), flush=True)
+    with open(out_path, "w") as f:
+        json.dump(rows, f, indent=1)
+    return 0
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", required=True)
@@ -68,9 +117,13 @@ def main(argv=None):
     ap.add_argument("--grid-verify", action="store_true", help="time NT, TNN and auto on all 512 grid shapes")
     ap.add_argument("--probe-lanes", action="store_true",
                     help="only the overlap probe: fp32 matrix instructions against vector instructions of another wave")
+    ap.add_argument("--launch-path", action="store_true",
+                    help="only the short calls, timed per call; run it under a kernel trace to get the time inside the kernels")
     args = ap.parse_args(argv)
     if args.probe_lanes:
         return probe_lanes(args.out)
+    if args.launch_path:
+        return launch_path(args.out)
 
     import torch
     from . import binding as mt
@@ -136,7 +189,8 @@ def main(argv=None):
         for shape, seed in zip(cfg["shapes"], cfg["seeds"]):
             named.append((cfg_name, shape, seed, cfg["dist"]))
     for shape in [(8192, 8192, 8192), (4096, 4096, 4096), (2048, 2048, 2048), (1024, 1024, 1024), (512, 512, 512),
-                  (64, 64, 64), (8192, 8192, 64), (64, 8192, 8192), (8192, 64, 8192), (8192, 8192, 1024)]:
+                  (64, 64, 64), (1000, 1000, 1000), (8192, 8192, 32), (8192, 8192, 64), (8192, 8192, 128), (64, 8192, 8192),
+                  (8192, 64, 8192), (8192, 8192, 1024)]:
         named.append(("config3", shape, 10000, "uniform"))
     for cfg_name, shape, seed, dist in named:
         row = time_shape(*shape, seed, dist, args.samples)
@@ -173,6 +227,24 @@ def main(argv=None):
         print(f"[report] transpose {rows}x{cols}: {pair_bytes / t / 1e9:.0f} GB/s on one buffer pair, "
               f"{pair_bytes / t_rot / 1e9:.0f} GB/s rotating over {nsets}", flush=True)
         del Xs, Ys, calls
+    # in-place transposes (square: tile-pair swaps; rectangular: two or three passes): one buffer each,
+    # sized like the B operands they would serve; GB/s counts each word read once and written once
+    report["inplace_transposes"] = []
+    for rows, cols in INPLACE_TRANSPOSES:
+        X = torch.rand(rows * cols, device="cuda")
+        dims = [rows, cols]
+
+        def flip():
+            if dims[0] == dims[1]:
+                mt.mtnn_transpose_inplace(X.view(rows, cols))
+            else:
+                mt.mtnn_transpose_inplace_rect(X, dims[0], dims[1])
+                dims.reverse()
+
+        t, _ = _time_batches(flip, stream, max(6, args.samples // 2), 2000.0)
+        report["inplace_transposes"].append({"rows": rows, "cols": cols, "t_us": t * 1e6, "gbs": 8.0 * rows * cols / t / 1e9})
+        print(f"[report] in-place transpose {rows}x{cols}: {t * 1e6:.1f} us, {8.0 * rows * cols / t / 1e9:.0f} GB/s", flush=True)
+        del X
     src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
     dst = torch.empty_like(src)
     t, _ = _time_batches(lambda: mt.mtnn_copy_bytes(src, dst), stream, args.samples, 2000.0)
@@ -246,6 +318,9 @@ def main(argv=None):
                 f.write(f"| {r['rows']} x {r['cols']} | {r['t_us']:.1f} | {r['gbs']:.0f} | {r['frac_of_peak']:.2f} | "
                         f"{'yes' if r['cache_resident_when_repeated'] else 'no'} | {r['buffer_pairs_rotated']} | "
                         f"{r['t_rotating_us']:.1f} | {r['gbs_rotating']:.0f} | {r['frac_of_peak_rotating']:.2f} |\n")
+            f.write("\n| in-place transpose rows x cols | us | GB/s (8 bytes per word) |\n|---|---|---|\n")
+            for r in report["inplace_transposes"]:
+                f.write(f"| {r['rows']} x {r['cols']} | {r['t_us']:.1f} | {r['gbs']:.0f} |\n")
             f.write(f"\ncopy kernel, 1 GiB: {report['copy_1gib_gbs']:.0f} GB/s\n\n")
             fc = report["fc_step"]
             f.write(f"FC step {fc['dims']} batch {fc['batch']} ({fc['gemm_flop'] / 1e9:.1f} GFLOP of GEMM work): "
