@@ -16,7 +16,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmtnn.so")
 
 # (the kernel instances first: they take longest, and the pool starts sources in this order)
-SOURCES = ["gemm_inst_a.hip", "gemm_inst_b.hip", "gemm_inst_c.hip", "gemm_inst_d.hip", "gemm_launch.hip", "transpose.hip", "transpose_inplace_rect.hip",
+SOURCES = ["gemm_inst_a.hip", "gemm_inst_b.hip", "gemm_inst_c.hip", "gemm_inst_d.hip", "gemm_inst_e.hip", "gemm_launch.hip", "transpose.hip", "transpose_inplace_rect.hip",
            "fc.hip", "static_scratch.hip", "probe.hip", "api.cpp", "selector.cpp", "gemm_cost.cpp", "device.cpp"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-Wno-unused-parameter", "-Wno-inline-asm", "-ffp-contract=off",

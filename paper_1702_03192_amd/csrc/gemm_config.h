@@ -98,12 +98,13 @@ struct KernelSet {
     GemmKernel sk[2];         // the pipelined kernel with the work cut evenly over a fixed grid, [op]
     void (*fix)(GemmParams, int);   // ... and its fix-up kernel
 };
-constexpr int kNumKernelSets = 11;
+constexpr int kNumKernelSets = 12;
 // each fills the entries of the geometries it instantiates (gemm_inst_*.hip)
 void fill_kernel_sets_a(KernelSet* table);
 void fill_kernel_sets_b(KernelSet* table);
 void fill_kernel_sets_c(KernelSet* table);
 void fill_kernel_sets_d(KernelSet* table);
+void fill_kernel_sets_e(KernelSet* table);
 
 // One tile configuration: a geometry, how many workgroups a CU should hold, and the cost model's
 // numbers for it.
@@ -112,7 +113,8 @@ struct TileConfig {
     int bm, bn, bk;
     int gbk;                          // k slab of the guarded kernel that serves what the pipelined one cannot
     int nstage;
-    int threads;
+    int threads;                      // of the pipelined kernel
+    int threads_guarded;              // of the guarded kernel (the same unless the pipelined one runs two sets of waves)
     int waves_n;
     int max_wg;                       // workgroups per CU the launch allows (it sizes its LDS request to that)
     int kernel_set;                   // index into the KernelSet table

@@ -12,9 +12,11 @@
 namespace mtnn {
 
 // pipelined kernel with NS slab buffers, and the guarded kernel (slab GBK) that serves what it cannot
-#define MTNN_TILE(SET, BM, BN, BK, WMV, WNV, NS, GBK, MAXWG, EFF_NN, RND_NN, EFF_NT, RND_NT, GEFF_NN, GRND_NN, GEFF_NT, GRND_NT) \
-    { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV "_dma" #NS "_x" #MAXWG, BM, BN, BK, GBK, NS, WMV * WNV * 64, WNV, MAXWG, SET,     \
+#define MTNN_TILE_KS(SET, BM, BN, BK, WMV, WNV, KS, KSNAME, NS, GBK, MAXWG, EFF_NN, RND_NN, EFF_NT, RND_NT, GEFF_NN, GRND_NN, GEFF_NT, GRND_NT) \
+    { #BM "x" #BN "x" #BK "_w" #WMV "x" #WNV KSNAME "_dma" #NS "_x" #MAXWG, BM, BN, BK, GBK, NS, WMV * WNV * 64 * KS, WMV * WNV * 64, WNV, MAXWG, SET, \
       BK != 16, {EFF_NN, EFF_NT}, {RND_NN, RND_NT}, {GEFF_NN, GEFF_NT}, {GRND_NN, GRND_NT} }
+#define MTNN_TILE(SET, BM, BN, BK, WMV, WNV, NS, GBK, MAXWG, EFF_NN, RND_NN, EFF_NT, RND_NT, GEFF_NN, GRND_NN, GEFF_NT, GRND_NT) \
+    MTNN_TILE_KS(SET, BM, BN, BK, WMV, WNV, 1, "", NS, GBK, MAXWG, EFF_NN, RND_NN, EFF_NT, RND_NT, GEFF_NN, GRND_NN, GEFF_NT, GRND_NT)
 
 const TileConfig kTileConfigs[] = {
     //  set   tile         waves stages    per CU   NN: eff, round      NT: eff, round       guarded kernel: NN, NT
@@ -36,6 +38,9 @@ const TileConfig kTileConfigs[] = {
     MTNN_TILE(10, 128, 128, 32, 2, 2, 2, 16,  2,   0.932f, 4.7e-6f,   0.943f, 4.7e-6f,   0.820f, 4.2e-6f, 0.789f, 4.3e-6f),   // 10: 4 waves of 64 x 64, 64 KB
     MTNN_TILE(8, 128, 64, 32, 2, 2, 2, 16,    3,   0.907f, 3.5e-6f,   0.901f, 1.9e-6f,   0.753f, 2.1e-6f, 0.734f, 2.3e-6f),   // 11: as 8, three per CU (small k)
     MTNN_TILE(9, 64, 128, 32, 2, 2, 2, 16,    3,   0.915f, 2.6e-6f,   0.917f, 2.2e-6f,   0.807f, 2.2e-6f, 0.745f, 1.9e-6f),   // 12: as 9, three per CU (small k)
+    // (13: fitted 2.7 / 1.7 us per round, 0.7 / 0.5 above configuration 3's fit; rated that much above
+    //  configuration 3's compiled-in figures, so that the two keep their measured order)
+    MTNN_TILE_KS(11, 64, 64, 64, 2, 2, 2, "k2", 2, 16,  2,   0.884f, 3.3e-6f,   0.879f, 2.4e-6f,   0.688f, 1.1e-6f, 0.680f, 1.1e-6f),   // 13: as 3 with two sets of 4 waves, each on half of every slab's k
 };
 const int kNumTileConfigs = (int)(sizeof(kTileConfigs) / sizeof(kTileConfigs[0]));
 
@@ -152,7 +157,17 @@ Choice choose(const Geometry& geo, int op, int m, int n, int k, bool allow_split
                 if ((size_t)m * n * splits * sizeof(float) > scratch_bytes) break;
                 if (k / splits < 2 * kSplitQuantum) break;
             }
-            double t = predicted_seconds(geo, kTileConfigs[c], o, m, n, k, splits, pipelined);
+            const TileConfig& tc = kTileConfigs[c];
+            if (tc.threads != tc.threads_guarded) {
+                // two sets of waves on one tile: for launches that give a CU one workgroup at most, with
+                // enough k per workgroup to pay for the hand-over at the end.  Measured on the grid: where
+                // the rule takes it the time falls by 1-5 % on average (up to 13 %) for 512 to 2048 k per
+                // workgroup; with less k the hand-over costs what the second set gains, with more the
+                // older configurations' deeper splits are as good.
+                const long long wgs = (long long)((m + tc.bm - 1) / tc.bm) * ((n + tc.bn - 1) / tc.bn) * splits;
+                if (!pipelined || wgs > geo.cus || k / splits < 512 || k / splits > 2048) continue;
+            }
+            double t = predicted_seconds(geo, tc, o, m, n, k, splits, pipelined);
             if (epi) {
                 const bool fuses = (epi_kind == kEpiBiasAct) ? (splits > 1 || kTileConfigs[c].has_fused)
                                                              : (splits == 1 && o == 0 && kTileConfigs[c].has_fused);

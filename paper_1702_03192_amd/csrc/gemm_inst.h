@@ -10,15 +10,16 @@ namespace mtnn {
 // epilogue's arithmetic makes the compiler move all 128 accumulators from AGPRs to VGPRs in one block
 // at the loop exit, and the registers that takes no longer allow the two workgroups per CU the
 // configuration is rated for (its launches run the plain kernel and the separate pass instead).
-template <int BM, int BN, int BK, int WMV, int WNV, bool NT, int NS, int EPI>
+template <int BM, int BN, int BK, int WMV, int WNV, bool NT, int NS, int EPI, int KS>
 constexpr GemmKernel epilogue_kernel()
 {
     if constexpr (BK == 16) return nullptr;
-    else return &gemm_dma_kernel<BM, BN, BK, WMV, WNV, NT, NS, EPI>;
+    else return &gemm_dma_kernel<BM, BN, BK, WMV, WNV, NT, NS, EPI, KS>;
 }
 
-// tile BM x BN, pipelined slab BK with NS buffers, WMV x WNV waves, guarded kernel's slab GBK
-template <int BM, int BN, int BK, int WMV, int WNV, int NS, int GBK>
+// tile BM x BN, pipelined slab BK with NS buffers, WMV x WNV waves (KS sets of them in the pipelined
+// kernel), guarded kernel's slab GBK
+template <int BM, int BN, int BK, int WMV, int WNV, int NS, int GBK, int KS = 1>
 KernelSet make_kernel_set()
 {
     KernelSet s;
@@ -26,13 +27,13 @@ KernelSet make_kernel_set()
     s.kern[0][1] = gemm_kernel<BM, BN, GBK, WMV, WNV, false, true>;
     s.kern[1][0] = gemm_kernel<BM, BN, GBK, WMV, WNV, true, false>;
     s.kern[1][1] = gemm_kernel<BM, BN, GBK, WMV, WNV, true, true>;
-    s.dma[0] = gemm_dma_kernel<BM, BN, BK, WMV, WNV, false, NS>;
-    s.dma[1] = gemm_dma_kernel<BM, BN, BK, WMV, WNV, true, NS>;
-    s.dma_bias[0] = epilogue_kernel<BM, BN, BK, WMV, WNV, false, NS, kEpiBiasAct>();
-    s.dma_bias[1] = epilogue_kernel<BM, BN, BK, WMV, WNV, true, NS, kEpiBiasAct>();
-    s.dma_sgd = epilogue_kernel<BM, BN, BK, WMV, WNV, false, NS, kEpiSgd>();
-    s.sk[0] = gemm_streamk_kernel<BM, BN, BK, WMV, WNV, false, NS>;
-    s.sk[1] = gemm_streamk_kernel<BM, BN, BK, WMV, WNV, true, NS>;
+    s.dma[0] = gemm_dma_kernel<BM, BN, BK, WMV, WNV, false, NS, kEpiNone, KS>;
+    s.dma[1] = gemm_dma_kernel<BM, BN, BK, WMV, WNV, true, NS, kEpiNone, KS>;
+    s.dma_bias[0] = epilogue_kernel<BM, BN, BK, WMV, WNV, false, NS, kEpiBiasAct, KS>();
+    s.dma_bias[1] = epilogue_kernel<BM, BN, BK, WMV, WNV, true, NS, kEpiBiasAct, KS>();
+    s.dma_sgd = epilogue_kernel<BM, BN, BK, WMV, WNV, false, NS, kEpiSgd, KS>();
+    s.sk[0] = gemm_streamk_kernel<BM, BN, BK, WMV, WNV, false, NS, KS>;
+    s.sk[1] = gemm_streamk_kernel<BM, BN, BK, WMV, WNV, true, NS, KS>;
     s.fix = streamk_fixup_kernel<BM, BN>;
     return s;
 }

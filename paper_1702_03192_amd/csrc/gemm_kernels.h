@@ -595,15 +595,24 @@ __device__ __forceinline__ void lds_barrier()
 // C tile (tm, tn).  The whole workgroup calls it; it leaves no copies in flight, and its last LDS
 // accesses (the epilogue's staging) are this wave's own, so a caller that runs several segments
 // needs one workgroup barrier between them.
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE, int EPI = kEpiNone>
+//
+// KS = 2: the workgroup has two sets of WAVES_M x WAVES_N waves.  Both sets work on the whole tile;
+// of every slab, set 0 multiplies the first half of the k range and set 1 the second half, and at the
+// end set 0 adds set 1's accumulators (handed over through LDS) to its own and stores.  A tile that
+// has a CU to itself then keeps two waves per SIMD busy instead of one, which hides each wave's waits
+// for its fragment reads and barriers behind the other's matrix instructions.
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE, int EPI = kEpiNone, int KS = 1>
 __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView& w, const int tm, const int tn)
 {
-    constexpr int NW = WAVES_M * WAVES_N;
+    static_assert(KS == 1 || KS == 2, "one or two sets of waves");
+    constexpr int NWT = WAVES_M * WAVES_N;            // waves per set
+    constexpr int NW = NWT * KS;
     constexpr int WM = BM / WAVES_M;
     constexpr int WN = BN / WAVES_N;
     constexpr int TM = WM / 32;
     constexpr int TN = WN / 32;
     constexpr int KK = BK / 8;                        // fragment steps per slab
+    constexpr int KKG = KK / KS;                      // ... and per set of waves
     constexpr int CPR = BK / 4;                       // 16-byte chunks per [row][k] row
     constexpr int RPL = (CPR >= 16) ? 1 : 16 / CPR;   // rows per 256 bytes of LDS
     constexpr int NCH = BN / 4;                       // chunks per [k][n] row (NN)
@@ -620,7 +629,8 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
     constexpr int A_LOADS = (A_BLOCKS + NI - 1) / NI;
     constexpr int B_LOADS = (B_BLOCKS + NI - 1) / NI;
     constexpr int LPS = A_LOADS + B_LOADS;            // copies per issuing wave per slab
-    static_assert(KK >= 2 && KK % 2 == 0, "an even number of fragment steps per slab (register ping-pong)");
+    static_assert(KK % KS == 0 && KKG >= 2 && KKG % 2 == 0, "an even number of fragment steps per slab and set (register ping-pong)");
+    static_assert(KS == 1 || NWT * TM * TN * 1024 <= NSTAGE * STAGE_WORDS, "the accumulators of one set must fit the slab buffers");
     static_assert(A_WORDS % 256 == 0 && B_WORDS % 256 == 0, "slabs must be whole 1 KB blocks");
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "2..4 slab buffers");
     static_assert(LPS * 2 <= 63, "vmcnt is 6 bits");
@@ -633,8 +643,13 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int lr = lane & 31;
     const int lh = lane >> 5;
-    const int wm0 = (wave / WAVES_N) * WM;
-    const int wn0 = (wave % WAVES_N) * WN;
+    const int kg = (KS > 1) ? wave / NWT : 0;         // which set of waves: which half of each slab's k range
+    const int wpos = (KS > 1) ? wave % NWT : wave;    // position of the wave's block of the tile
+    const int wm0 = (wpos / WAVES_N) * WM;
+    const int wn0 = (wpos % WAVES_N) * WN;
+    // chunk index of the set's first k inside a [row][k] row: one bit above the chunk indices the
+    // set's fragment steps run through, so it can be folded into the row's XOR swizzle
+    const int kgc = kg * (CPR / KS);
 
     const int m0 = tm * BM;
     const int n0 = tn * BN;
@@ -763,7 +778,7 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // fragment reads of step kk from buffer `stage`
+    // fragment reads of this set's step kk from buffer `stage`
     auto read_frags = [&](int stage, int kk, f32x4 (&af)[TM], f32x4 (&bf)[TN]) {
         const float* as = lds + stage * STAGE_WORDS;
         const float* bs = as + A_WORDS;
@@ -771,13 +786,13 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row = wm0 + i * 32 + lr;
-            af[i] = *reinterpret_cast<const f32x4*>(&as[row * BK + ((c ^ ((row / RPL) % CPR)) * 4)]);
+            af[i] = *reinterpret_cast<const f32x4*>(&as[row * BK + ((c ^ ((row / RPL) % CPR) ^ kgc) * 4)]);
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             if (NT) {
                 const int row = wn0 + j * 32 + lr;
-                bf[j] = *reinterpret_cast<const f32x4*>(&bs[row * BK + ((c ^ ((row / RPL) % CPR)) * 4)]);
+                bf[j] = *reinterpret_cast<const f32x4*>(&bs[row * BK + ((c ^ ((row / RPL) % CPR) ^ kgc) * 4)]);
             }
         }
         if (!NT) {
@@ -785,7 +800,7 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
             // (one 128-, 64- or 32-bit LDS load) and uses them for its TN blocks, so block j of lane l
             // works on column wn0 + TN * l + j; the epilogue stores with the same mapping.
             typedef float vecN __attribute__((ext_vector_type(TN)));
-            const int krow = kk * 8 + lh * 4;                 // rows krow..krow+3 share (krow>>2)&1
+            const int krow = (kg * KKG + kk) * 8 + lh * 4;    // rows krow..krow+3 share (krow>>2)&1
             const int sw = (NCH >= 16) ? (((krow >> 2) & 1) << 3) : 0;
             const int col = wn0 + TN * lr;
             const float* q = &bs[krow * BN + (((col >> 2) ^ sw) << 2) + (col & 3)];
@@ -824,9 +839,9 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
     for (int s = 0; s < num_slabs; ++s) {
         const int next_stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
+        for (int kk = 0; kk < KKG; ++kk) {
             const int cur = kk & 1;
-            if (kk + 1 < KK) {
+            if (kk + 1 < KKG) {
                 read_frags(stage, kk + 1, af[cur ^ 1], bf[cur ^ 1]);
             } else {
                 // every fragment read of slab s has been issued: after the barrier its buffer is free
@@ -850,6 +865,32 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[cur][i][q], bf[cur][j][q], acc[i][j], 0, 0, 0);
         }
         stage = next_stage;
+    }
+
+    if constexpr (KS > 1) {
+        // set 1 hands its accumulators to set 0 through the slab buffers (free once every wave has passed
+        // the first barrier): register r of block (i, j) of the wave at position wpos, lane by lane
+        float* red = lds + (size_t)wpos * (TM * TN * 1024) + lane;
+        lds_barrier();
+        if (kg != 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) red[((i * TN + j) * 16 + r) * 64] = acc[i][j][r];
+        }
+        lds_barrier();
+        if (kg == 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] += red[((i * TN + j) * 16 + r) * 64];
+        }
+        lds_barrier();        // the sums are in registers: LDS may be reused (store patches, the next segment's copies)
+        if (kg != 0) return;
     }
 
     // epilogue: interior tiles of a 16-byte-aligned C go through wave-private LDS patches (the slab
@@ -879,7 +920,7 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
         else
             store_tile_interleaved<TM, TN, BIAS, false>(acc, w.C, w.ldc, M, N, m0 + wm0, n0 + wn0, lr, lh, c_vec, bv, relu);
     } else {
-        lds_barrier();
+        if constexpr (KS == 1) lds_barrier();       // (KS = 2: every wave has passed the barriers above)
         if (c_vec && m0 + BM <= M && n0 + BN <= N) {
             if (stream)
                 store_tile_staged<TM, TN, BIAS, true>(acc, w.C, w.ldc, m0 + wm0, n0 + wn0, lane, lds + wave * (16 * (WN + 8)), bv, relu);
@@ -893,13 +934,13 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
     }
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE, int EPI = kEpiNone>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_dma_kernel(GemmParams p)
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE, int EPI = kEpiNone, int KS = 1>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64 * KS) void gemm_dma_kernel(GemmParams p)
 {
     const WorkView w = work_view(p, NT);
     int tm, tn;
     tile_of_block(p, w.pid, tm, tn);
-    dma_segment<BM, BN, BK, WAVES_M, WAVES_N, NT, NSTAGE, EPI>(p, w, tm, tn);
+    dma_segment<BM, BN, BK, WAVES_M, WAVES_N, NT, NSTAGE, EPI, KS>(p, w, tm, tn);
 }
 
 // ---- even split of the whole k x tiles work over a fixed number of workgroups -------------------
@@ -927,8 +968,8 @@ __device__ __forceinline__ int streamk_piece_of_block(int block, int groups, int
     return (block % num_xcd) * (groups / num_xcd) + block / num_xcd;
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_streamk_kernel(GemmParams p)
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, bool NT, int NSTAGE, int KS = 1>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64 * KS) void gemm_streamk_kernel(GemmParams p)
 {
     const StreamKCut cut = {p.tiles_m * p.tiles_n * p.sk_units_per_tile, p.sk_units_per_tile, (int)gridDim.x};
     const int piece = streamk_piece_of_block((int)blockIdx.x, cut.groups, p.num_xcd);
@@ -963,7 +1004,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_streamk_kernel(Gem
         }
         if (!first) lds_barrier();
         first = false;
-        dma_segment<BM, BN, BK, WAVES_M, WAVES_N, NT, NSTAGE>(q, w, tm, tn);
+        dma_segment<BM, BN, BK, WAVES_M, WAVES_N, NT, NSTAGE, kEpiNone, KS>(q, w, tm, tn);
         u += s1 - s0;
     }
 }

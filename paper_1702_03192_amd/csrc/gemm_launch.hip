@@ -23,6 +23,7 @@ static const KernelSet* kernel_sets()
         fill_kernel_sets_b(table);
         fill_kernel_sets_c(table);
         fill_kernel_sets_d(table);
+        fill_kernel_sets_e(table);
     });
     return table;
 }
@@ -171,7 +172,7 @@ int launch_gemm(hipStream_t s, const Geometry& geo, const Scratch& scratch, int 
         const hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), geo.device, geo.lds_per_cu);
         if (e != hipSuccess) return (int)e;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(c.threads), lds, s, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(dma_ok ? c.threads : c.threads_guarded), lds, s, p);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return (int)err;
     if (p.splits > 1) {

@@ -92,16 +92,16 @@ def tile_units(per_cu, occ, waves):
 
 
 def _config_waves(name):
-    g = re.match(r"\d+x\d+x\d+_w(\d+)x(\d+)_", name)
-    return int(g.group(1)) * int(g.group(2))
+    g = re.match(r"\d+x\d+x\d+_w(\d+)x(\d+)(?:k(\d+))?_", name)          # (k2: two sets of waves per workgroup)
+    return int(g.group(1)) * int(g.group(2)) * int(g.group(3) or 1)
 
 
 def _config_geometry(name):
     """(bm, bn, workgroups per CU the launch allows, LDS bytes of the pipelined kernel) from a configuration name."""
-    g = re.match(r"(\d+)x(\d+)x(\d+)_w(\d+)x(\d+)_dma(\d+)_x(\d+)", name)
-    bm, bn, bk, wm, wn, ns, max_wg = map(int, g.groups())
+    g = re.match(r"(\d+)x(\d+)x(\d+)_w(\d+)x(\d+)(?:k(\d+))?_dma(\d+)_x(\d+)", name)
+    bm, bn, bk, wm, wn, ks, ns, max_wg = (int(v or 1) for v in g.groups())
     ring = ns * (bm + bn) * bk * 4
-    patches = wm * wn * 16 * (bn // wn + 8) * 4
+    patches = ks * wm * wn * 16 * (bn // wn + 8) * 4
     occ = max(1, min((160 * 1024) // max(ring, patches), max_wg))
     return bm, bn, occ
 
