@@ -98,7 +98,7 @@ struct KernelSet {
     GemmKernel sk[2];         // the pipelined kernel with the work cut evenly over a fixed grid, [op]
     void (*fix)(GemmParams, int);   // ... and its fix-up kernel
 };
-constexpr int kNumKernelSets = 12;
+constexpr int kNumKernelSets = 14;
 // each fills the entries of the geometries it instantiates (gemm_inst_*.hip)
 void fill_kernel_sets_a(KernelSet* table);
 void fill_kernel_sets_b(KernelSet* table);

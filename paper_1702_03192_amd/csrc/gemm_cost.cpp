@@ -41,6 +41,8 @@ const TileConfig kTileConfigs[] = {
     // (13: fitted 2.7 / 1.7 us per round, 0.7 / 0.5 above configuration 3's fit; rated that much above
     //  configuration 3's compiled-in figures, so that the two keep their measured order)
     MTNN_TILE_KS(11, 64, 64, 64, 2, 2, 2, "k2", 2, 16,  2,   0.884f, 3.3e-6f,   0.879f, 2.4e-6f,   0.688f, 1.1e-6f, 0.680f, 1.1e-6f),   // 13: as 3 with two sets of 4 waves, each on half of every slab's k
+    MTNN_TILE_KS(12, 32, 256, 32, 1, 4, 2, "k2", 2, 16, 2,   0.897f, 3.1e-6f,   0.880f, 2.8e-6f,   0.698f, 1.7e-6f, 0.621f, 2.0e-6f),   // 14: as 4 with two sets of 4 waves
+    MTNN_TILE_KS(13, 256, 32, 32, 4, 1, 2, "k2", 2, 16, 2,   0.862f, 4.3e-6f,   0.873f, 2.7e-6f,   0.567f, 1.9e-6f, 0.535f, 1.4e-6f),   // 15: as 5 with two sets of 4 waves
 };
 const int kNumTileConfigs = (int)(sizeof(kTileConfigs) / sizeof(kTileConfigs[0]));
 
@@ -107,7 +109,10 @@ static double predicted_seconds(const Geometry& geo, const TileConfig& c, int op
     t += round_cost * (double)rounds;
     // HBM floor: operands once, result once
     const double bytes = 4.0 * ((double)m * k + (double)n * k + (double)m * n);
-    if (t < bytes / 5.0e12) t = bytes / 5.0e12;
+    // (one workgroup per CU streaming a skinny operand: 3 % faster with two sets of waves than with one,
+    //  (32, 8192, 8192) 49.3 against 50.8 us, (8192, 32, 8192) 49.4 against 51.8)
+    const double stream_rate = (c.threads != c.threads_guarded) ? 5.15e12 : 5.0e12;
+    if (t < bytes / stream_rate) t = bytes / stream_rate;
     if (splits > 1) t += 2.0e-6 + 0.3e-6 * splits + 4.0 * (double)m * n * (splits + 2) / 4.0e12;
     return t + 3.0e-6;
 }
@@ -164,8 +169,13 @@ Choice choose(const Geometry& geo, int op, int m, int n, int k, bool allow_split
                 // the rule takes it the time falls by 1-5 % on average (up to 13 %) for 512 to 2048 k per
                 // workgroup; with less k the hand-over costs what the second set gains, with more the
                 // older configurations' deeper splits are as good.
-                const long long wgs = (long long)((m + tc.bm - 1) / tc.bm) * ((n + tc.bn - 1) / tc.bn) * splits;
+                // The 32-row and 32-column tiles of this kind serve products that are one such tile high or
+                // wide (m or n <= 32: 3-6 % faster than their 4-wave twins); for anything larger the other
+                // tiles are better and the model, fitted on full grids, would overrate these.
+                const long long tiles_m = (m + tc.bm - 1) / tc.bm, tiles_n = (n + tc.bn - 1) / tc.bn;
+                const long long wgs = tiles_m * tiles_n * splits;
                 if (!pipelined || wgs > geo.cus || k / splits < 512 || k / splits > 2048) continue;
+                if ((tc.bm < 64 && tiles_m > 1) || (tc.bn < 64 && tiles_n > 1)) continue;
             }
             double t = predicted_seconds(geo, tc, o, m, n, k, splits, pipelined);
             if (epi) {

@@ -14,7 +14,7 @@ from gpu_util import Guarded, check_gemm, dev_matrix
 
 pytestmark = pytest.mark.gpu
 
-NCFG = 14
+NCFG = 16
 
 
 def sync():
@@ -354,7 +354,7 @@ def test_huge_leading_dimensions(case):
 
 
 @pytest.mark.parametrize("op", [mt.OP_NT, mt.OP_NN], ids=["NT", "NN"])
-@pytest.mark.parametrize("cfg", [10, 11, 12, 13])
+@pytest.mark.parametrize("cfg", [10, 11, 12, 13, 14, 15])
 def test_several_workgroups_per_cu_on_a_full_grid(op, cfg):
     """Configurations that put two or three workgroups on a CU, on a grid large enough that every CU
     really holds that many (768+ tiles), with a ragged last slab."""
@@ -366,7 +366,7 @@ def test_several_workgroups_per_cu_on_a_full_grid(op, cfg):
 
 
 @pytest.mark.parametrize("op", [mt.OP_NT, mt.OP_NN], ids=["NT", "NN"])
-@pytest.mark.parametrize("cfg", [3, 6, 8, 9, 10, 11, 12, 13])
+@pytest.mark.parametrize("cfg", [3, 6, 8, 9, 10, 11, 12, 13, 14, 15])
 def test_even_cut_against_oracle(op, cfg):
     """splits = EVEN_CUT: all tiles' k ranges cut into equal pieces over a fixed grid, cut tiles
     finished by the fix-up kernel; ragged m, n edges and a ragged last k unit."""
