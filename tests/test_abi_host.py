@@ -270,6 +270,30 @@ def test_choice_respects_the_scratch_capacity():
     assert saw_split
 
 
+def test_two_wave_set_configurations_are_chosen_where_a_cu_holds_one_workgroup():
+    """Configurations whose workgroups run two sets of waves on one tile ("k2" in the name) are for
+    launches of at most one workgroup per CU with 512-2048 k each; the 32-row / 32-column ones only for
+    products one tile high / wide."""
+    names = mt.gemm_configs()
+    k2 = lambda op, m, n, k: "k2" in names[mt.mtnn_gemm_choice(op, m, n, k)[0]]
+    for op in (0, 1):
+        assert k2(op, 1024, 1024, 1024) and k2(op, 2048, 512, 1024)          # 256 tiles of 64 x 64
+        assert k2(op, 32, 8192, 8192) and k2(op, 8192, 32, 8192)             # one tile high / wide, split-k
+        assert names[mt.mtnn_gemm_choice(op, 32, 8192, 8192)[0]].startswith("32x256")
+        assert names[mt.mtnn_gemm_choice(op, 8192, 32, 8192)[0]].startswith("256x32")
+        assert not k2(op, 8192, 8192, 8192) and not k2(op, 4096, 4096, 1024)  # many workgroups per CU
+        assert not k2(op, 1024, 1024, 64) and not k2(op, 256, 256, 256)      # too little k per workgroup
+        assert not k2(op, 64, 8192, 8192)                                    # two tiles high: not the skinny tile
+    import numpy as np
+    rng = np.random.default_rng(1702)
+    for m, n, k in np.exp(rng.uniform(np.log(16.0), np.log(2.0 ** 14), size=(300, 3))).astype(np.int64):
+        for op in (0, 1):
+            c, s = mt.mtnn_gemm_choice(op, int(m), int(n), int(k))
+            if "k2" in names[c]:
+                bm, bn = (int(v) for v in names[c].split("x")[:2])
+                assert s >= 1 and -(-int(m) // bm) * -(-int(n) // bn) * s <= 256 and 512 <= int(k) // s <= 2048
+
+
 def test_tnn_inplace_rejects_b_overlapping_a(L):
     """B is written by the in-place path, so the Gram product A x A^T (A == B) must be refused."""
     assert L.mtnn_tnn_inplace(None, 8, 8, 8, A, 8, A, 8, C, 8) == 4

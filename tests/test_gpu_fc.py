@@ -303,6 +303,9 @@ FORWARD_CASES = [
     (200, 328, 1000, 0, 0, 0, True),       # ragged tiles, operands still in 16-byte chunks
     (256, 512, 260, 4, 8, 4, True),        # padded leading dimensions (multiples of 4)
     (64, 128, 8192, 0, 0, 0, True),        # split-k: the reduction kernel carries the epilogue
+    (1024, 1024, 1024, 0, 0, 0, True),     # one 64 x 64 tile per CU: the configuration with two sets of waves per workgroup
+    (1000, 1000, 1000, 0, 0, 0, True),     # ... with ragged edge tiles
+    (32, 8192, 4096, 0, 0, 0, True),       # one tile high: split-k over the two-wave-set 32 x 256 tile
     (100, 37, 51, 0, 0, 0, False),         # nothing aligned: guarded kernel + separate pass
     (96, 130, 64, 0, 0, 3, True),          # n % 4 != 0 with a padded Y: word-wise stores (NT); not for the NN product of TNN
     (5, 7, 0, 0, 0, 0, False),             # k = 0: Y = act(b) in every row
@@ -378,6 +381,7 @@ UPDATE_CASES = [
     (200, 328, 260, 0, 0, 0, 0, True),      # ragged tiles
     (256, 512, 64, 4, 4, 8, 4, True),       # padded leading dimensions
     (10, 1024, 4096, 0, 0, 0, 0, True),     # small m n, long k: fused only if the rule does not split it
+    (1024, 1024, 1024, 0, 0, 0, 0, True),   # one 64 x 64 tile per CU: two sets of waves per workgroup, update in set 0's epilogue
     (4096, 4096, 1024, 0, 0, 0, 0, True),   # config 5's weight gradients (the plain product would take the 16-wide-slab configuration)
     (100, 37, 51, 0, 0, 0, 0, False),       # unaligned: separate pass
     (64, 128, 96, 0, 0, 0, 3, None),        # W rows not 16-byte aligned: fused kernel, word-wise update
