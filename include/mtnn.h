@@ -191,6 +191,9 @@ MTNN_API int mtnn_model_margin(const double *x, int nfeat, double *margin);
  * mtnn_nt / mtnn_nn choose both per shape with a fixed cost model.  These calls run a given
  * configuration (cfg in [0, count), or -1 for the model's choice) and split count (1..32, or 0 for
  * the model's choice when cfg is -1 and no split when cfg is given).  op: 0 = NN, 1 = NT.
+ * A configuration's name reads BMxBNxBK_wMxN[k2]_dmaS_xP: the C tile, the k slab, M x N waves per
+ * workgroup ("k2": two such sets of waves on the same tile, each on half of every slab's k range),
+ * S slab buffers, at most P workgroups per CU.
  *
  * Scratch.  A split launch keeps its partial products (m x n x splits floats) in scratch memory that
  * the CALLER owns and registers per stream: mtnn_set_scratch(stream, ptr, bytes) lends the library
