@@ -161,6 +161,16 @@ int launch_gemm(hipStream_t s, const Geometry& geo, const Scratch& scratch, int 
         // piling three on some CUs and one on others.
         long long per_cu_wgs = (total + geo.cus - 1) / geo.cus;
         int want = occ;
+        if (p.k_per_split <= c.bk && c.threads == c.threads_guarded) {
+            // The whole k range is one slab: only the first slab buffer is ever touched, so the request
+            // shrinks to it (or to the epilogue's patches) and a CU may hold more workgroups -- as many as
+            // the registers allow, four for these kernels -- which hides more of the one global -> LDS
+            // round trip each workgroup waits for ((8192, 8192, 32) NT: 65 -> 61 us on 128 x 64 tiles).
+            const size_t ring1 = (size_t)(c.bm + c.bn) * c.bk * sizeof(float);
+            const size_t patches = (size_t)(c.threads / 64) * 16 * (size_t)(c.bn / c.waves_n + 8) * sizeof(float);
+            lds = ring1 > patches ? ring1 : patches;
+            want = 5;
+        }
         if (per_cu_wgs < want) want = (int)per_cu_wgs;
         if (want < 1) want = 1;
         const size_t share = ((size_t)geo.lds_per_cu / (size_t)want) & ~(size_t)1023;
