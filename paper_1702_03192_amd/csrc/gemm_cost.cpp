@@ -186,6 +186,11 @@ Choice choose(const Geometry& geo, int op, int m, int n, int k, bool allow_split
                 const bool fuses = (epi_kind == kEpiBiasAct) ? (splits > 1 || kTileConfigs[c].has_fused)
                                                              : (splits == 1 && o == 0 && kTileConfigs[c].has_fused);
                 if (!fuses) t += pass_s;
+                // the fused update reads and writes W next to the store of dW: 8 m n bytes more, which a
+                // workgroup that has its CU to itself cannot overlap with anything ((4096, 4096, 1024):
+                // +24 us on 256 x 256 tiles, +16 us on 128 x 128 tiles two per CU, over a 241 us product)
+                else if (epi_kind == kEpiSgd)
+                    t += 8.0 * (double)m * (double)n / (tc.wg_per_cu(geo.lds_per_cu) == 1 ? 5.3e12 : 8.0e12);
             }
             if (t < best_t * 0.999) { best_t = t; best = Choice{c, splits}; }
         }
