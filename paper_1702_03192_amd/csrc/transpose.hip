@@ -184,6 +184,12 @@ int launch_transpose(hipStream_t s, int rows, int cols, const float* in, long ld
          : launch_transpose_t<TR, TC, false, NTL, false>(s, rows, cols, pin, ldin, pout, ldout))
     if (elems >= (1LL << 26) && rows >= 256 && cols >= 64) return MTNN_TRANSPOSE(256, 64, true);
     if (elems > (1LL << 24) && cols >= 64) return MTNN_TRANSPOSE(128, 64, true);
+    // Output rows that do not start on lines, a few million words: the 128 x 64 tile (input row pieces of
+    // 256 bytes, so three lines touched per piece instead of two per 128 bytes) measures ahead of
+    // 128 x 32 from the caches (4100^2 26.0 -> 22.5 us, 4097 x 4095 27.2 -> 24.0, 4500 x 1500 12.4 -> 11.1,
+    // 2500 x 3300 14.8 -> 13.3) and level with it from HBM; aligned shapes of this size keep 128 x 32
+    // (4096 x 1024 from the caches 4.7 us against 5.2).
+    if (!whole_lines && elems >= (1LL << 22) && cols >= 64) return MTNN_TRANSPOSE(128, 64, false);
     return MTNN_TRANSPOSE(128, 32, false);
 #undef MTNN_TRANSPOSE
 }
