@@ -119,14 +119,26 @@ __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ 
     }
 }
 
+// xcds > 1 (launches of a few million words whose output rows do not start on cache lines): workgroup ids, which the hardware
+// deals round robin to the XCDs, are renumbered so that each XCD works on one contiguous run of the
+// tile order (the first xcd_tall XCDs take xcd_per tiles, the others one fewer).  Tiles that are
+// neighbours in the matrix then mostly run on the same XCD, and the cache lines two tiles share at
+// their common edge -- input row pieces and output row segments both end inside lines there -- meet
+// in that XCD's L2 instead of being fetched twice and written back as two partial lines.
 template <int TR, int TC, bool VEC, bool NTL, bool STREAM>
 __global__ __launch_bounds__(TR_THREADS) void transpose_kernel(
     const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
-    int rows, int cols, long ldin, long ldout, int tiles_r, int tiles_c)
+    int rows, int cols, long ldin, long ldout, int tiles_r, int tiles_c, int xcds, int xcd_per, int xcd_tall)
 {
     extern __shared__ uint32_t tile[];                   // TR * TC words
-    const int tr = blockIdx.x % tiles_r;
-    const int tc = (blockIdx.x / tiles_r + tr) % tiles_c;   // for each tile row a rotation of the columns
+    int pid = (int)blockIdx.x;
+    if (xcds > 1) {
+        const int local = pid / xcds;
+        const int x = pid - local * xcds;
+        pid = (x < xcd_tall) ? x * xcd_per + local : xcd_tall * xcd_per + (x - xcd_tall) * (xcd_per - 1) + local;
+    }
+    const int tr = pid % tiles_r;
+    const int tc = (pid / tiles_r + tr) % tiles_c;          // for each tile row a rotation of the columns
     const int r0 = tr * TR;
     const int c0 = tc * TC;
     // VEC: 16-byte aligned rows on both sides
@@ -158,8 +170,20 @@ static int launch_transpose_t(hipStream_t s, int rows, int cols, const uint32_t*
             if (dev >= 0 && dev < 16) raised[dev] = true;
         }
     }
+    int xcds = 1, xcd_per = 0, xcd_tall = 0;
+    // (only up to 3 x 2^22 words: measured from the caches 4500 x 1500 11.1 -> 9.6 us, 2500 x 3300 13.3 -> 11.4,
+    // 2743 x 3061 13.8 -> 11.8, from HBM 16.6 -> 15.2 / 19.4 -> 18.2 / 20.2 -> 18.8; beyond that the XCDs each
+    // streaming a region of their own lose more in memory than the shared lines gain: 8200^2 from HBM 123 -> 144 us)
+    if (!STREAM && (long long)rows * cols <= (3LL << 22)) {
+        Geometry geo;
+        if (current_geometry(&geo) && geo.xcds > 1 && nblocks >= geo.xcds) {
+            xcds = geo.xcds;
+            xcd_per = (int)((nblocks + xcds - 1) / xcds);
+            xcd_tall = (int)(nblocks - (long long)(xcd_per - 1) * xcds);
+        }
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(TR_THREADS), lds, s,
-                       in, out, rows, cols, ldin, ldout, tiles_r, tiles_c);
+                       in, out, rows, cols, ldin, ldout, tiles_r, tiles_c, xcds, xcd_per, xcd_tall);
     return (int)hipGetLastError();
 }
 
