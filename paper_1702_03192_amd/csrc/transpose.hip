@@ -119,7 +119,7 @@ __device__ __forceinline__ void transpose_tile_vec(const uint32_t* __restrict__ 
     }
 }
 
-// xcds > 1 (launches of a few million words whose output rows do not start on cache lines): workgroup ids, which the hardware
+// xcds > 1 (launches of 2^21 to 3 x 2^22 words whose output rows do not start on cache lines): workgroup ids, which the hardware
 // deals round robin to the XCDs, are renumbered so that each XCD works on one contiguous run of the
 // tile order (the first xcd_tall XCDs take xcd_per tiles, the others one fewer).  Tiles that are
 // neighbours in the matrix then mostly run on the same XCD, and the cache lines two tiles share at
@@ -174,7 +174,9 @@ static int launch_transpose_t(hipStream_t s, int rows, int cols, const uint32_t*
     // (only up to 3 x 2^22 words: measured from the caches 4500 x 1500 11.1 -> 9.6 us, 2500 x 3300 13.3 -> 11.4,
     // 2743 x 3061 13.8 -> 11.8, from HBM 16.6 -> 15.2 / 19.4 -> 18.2 / 20.2 -> 18.8; beyond that the XCDs each
     // streaming a region of their own lose more in memory than the shared lines gain: 8200^2 from HBM 123 -> 144 us)
-    if (!STREAM && (long long)rows * cols <= (3LL << 22)) {
+    // (and from 2^21 words: a grid of a few hundred tiles is one partial round either way, and 1000^2 measured
+    // 3.4 -> 3.7 us with the renumbering)
+    if (!STREAM && (long long)rows * cols <= (3LL << 22) && (long long)rows * cols >= (1LL << 21)) {
         Geometry geo;
         if (current_geometry(&geo) && geo.xcds > 1 && nblocks >= geo.xcds) {
             xcds = geo.xcds;
