@@ -67,31 +67,38 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
-def build_host_sanitized(out_dir: str) -> str:
-    """AddressSanitizer + UBSan build (g++, host only) of the library's host sources and the C oracle
-    with the driver under tests/host_sanitize/; returns the executable.  The kernel launchers are
+def build_host_sanitized(out_dir: str, kind: str = "address") -> str:
+    """Sanitizer build (g++, host only) of the library's host sources with a driver under
+    tests/host_sanitize/; returns the executable.  kind "address": AddressSanitizer + UBSan, with the C
+    oracle and driver.cpp; kind "thread": ThreadSanitizer with driver_threads.cpp (several threads on the
+    process-wide state; the oracle, which uses OpenMP, is left out).  The kernel launchers are
     replaced by stand-ins that are never reached without a GPU."""
+    assert kind in ("address", "thread")
     root = os.path.dirname(HERE)
     drv = os.path.join(root, "tests", "host_sanitize")
-    exe = os.path.join(out_dir, "host_sanitize")
-    san = ["-fsanitize=address,undefined", "-fno-omit-frame-pointer", "-g", "-O1"]
+    exe = os.path.join(out_dir, "host_sanitize_" + kind)
+    san = (["-fsanitize=address,undefined"] if kind == "address" else ["-fsanitize=thread"]) + ["-fno-omit-frame-pointer", "-g", "-O1"]
     cxx = ["g++", "-std=c++17", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-I" + CSRC, "-Wall", "-Wno-unused-parameter",
            "-Wno-deprecated-declarations"] + san
     objs = []
     for src in ["api.cpp", "selector.cpp", "device.cpp", "gemm_cost.cpp"]:
-        obj = os.path.join(out_dir, src + ".o")
+        obj = os.path.join(out_dir, kind + "_" + src + ".o")
         subprocess.run(cxx + ["-c", os.path.join(CSRC, src), "-o", obj], check=True)
         objs.append(obj)
-    for src in ["stubs.cpp", "driver.cpp"]:
-        obj = os.path.join(out_dir, src + ".o")
+    for src in ["stubs.cpp", "driver.cpp" if kind == "address" else "driver_threads.cpp"]:
+        obj = os.path.join(out_dir, kind + "_" + src + ".o")
         subprocess.run(cxx + ["-c", os.path.join(drv, src), "-o", obj], check=True)
         objs.append(obj)
-    oobj = os.path.join(out_dir, "oracle.o")
-    subprocess.run(["gcc", "-std=c99", "-fopenmp", "-Wall", "-Wextra"] + san + ["-c", os.path.join(root, "oracle", "mtnn_oracle.c"), "-o", oobj],
-                   check=True)
+    extra = []
+    if kind == "address":
+        oobj = os.path.join(out_dir, "oracle.o")
+        subprocess.run(["gcc", "-std=c99", "-fopenmp", "-Wall", "-Wextra"] + san + ["-c", os.path.join(root, "oracle", "mtnn_oracle.c"), "-o", oobj],
+                       check=True)
+        objs.append(oobj)
+        extra = ["-fopenmp"]
     hip_lib_dir = _torch_lib_dir() or "/opt/rocm/lib"
-    subprocess.run(["g++"] + san + ["-fopenmp", "-o", exe] + objs + [oobj, "-L" + hip_lib_dir, "-l:libamdhip64.so",
-                                                                      "-Wl,-rpath," + hip_lib_dir, "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    subprocess.run(["g++"] + san + extra + ["-pthread", "-o", exe] + objs + ["-L" + hip_lib_dir, "-l:libamdhip64.so",
+                                                                              "-Wl,-rpath," + hip_lib_dir, "-Wl,-rpath,/opt/rocm/lib"], check=True)
     return exe
 
 
