@@ -62,6 +62,26 @@ def lub(p_mtnn, p_nt, p_tnn):
     return (p_mtnn - best) / best
 
 
+def tnn_pays(t_transpose, t_nt, t_nn):
+    """Eq. 4 (Section III): TNN is the faster way exactly when the transpose costs less than what the
+    NN product saves over the NT product, T_transpose < T_NT - T_NN (strict: a tie stays with NT)."""
+    return t_transpose < t_nt - t_nn
+
+
+def ratio_statistics(t_nt, t_nn, t_tnn):
+    """The case counts the paper reads off its Fig. 1-3, for lists of per-shape times (P ~ 1 / t):
+    share of shapes with P_NN > P_NT and with P_NN >= 2 P_NT (Section II), share with
+    P_TNN / P_NT < 1 and the largest ratio either way (Section III)."""
+    n = len(t_nt)
+    nn_faster = sum(1 for a, b in zip(t_nt, t_nn) if b < a)
+    nn_twice = sum(1 for a, b in zip(t_nt, t_nn) if a >= 2.0 * b)
+    nt_ahead = sum(1 for a, c in zip(t_nt, t_tnn) if a < c)          # P_TNN / P_NT < 1
+    return {"nn_faster_than_nt": nn_faster / n, "nn_twice_nt": nn_twice / n,
+            "tnn_over_nt_below_1": nt_ahead / n,
+            "max_tnn_over_nt": max(a / c for a, c in zip(t_nt, t_tnn)),
+            "max_nt_over_tnn": max(c / a for a, c in zip(t_nt, t_tnn))}
+
+
 def selection_metrics(p_nt, p_tnn, predicted):
     """Table VII for a list of shapes.  P_MTNN is the performance of whichever algorithm was predicted.
 

@@ -119,6 +119,44 @@ def selection_metrics(t_nt: Sequence[float], t_tnn: Sequence[float], shapes, pre
             "accuracy": correct / n}
 
 
+def nt_tnn_statistics(rows) -> Dict[str, object]:
+    """What Sections II and III of the paper read off their figures, on one of our timing tables (rows
+    with t_nt, t_nn, t_transpose and t_tnn, the last timed as one mtnn_tnn call):
+
+      * Fig. 1 / 2: the share of shapes on which the NN kernel beats the NT kernel, and by 2x or more;
+      * Fig. 3: the share of shapes with P_TNN / P_NT below 1, the largest ratio either way, and the
+        distribution of log2(P_TNN / P_NT) in bins of a quarter;
+      * Eq. 4: on how many shapes T_transpose < T_NT - T_NN holds for the separately timed parts, and on
+        how many that agrees with the label of the directly timed pair (t_tnn < t_nt) -- i.e. whether
+        TNN's time is the sum of its two parts.
+    """
+    import math
+    n = len(rows)
+    nn_faster = sum(1 for r in rows if r["t_nn"] < r["t_nt"])
+    nn_twice = sum(1 for r in rows if r["t_nt"] >= 2.0 * r["t_nn"])
+    below = sum(1 for r in rows if r["t_nt"] < r["t_tnn"])
+    best_tnn = max(rows, key=lambda r: r["t_nt"] / r["t_tnn"])
+    best_nt = max(rows, key=lambda r: r["t_tnn"] / r["t_nt"])
+    eq4 = [r["t_transpose"] < r["t_nt"] - r["t_nn"] for r in rows]
+    direct = [r["t_tnn"] < r["t_nt"] for r in rows]
+    hist: Dict[str, int] = {}
+    for r in rows:
+        b = math.floor(math.log2(r["t_nt"] / r["t_tnn"]) * 4.0) / 4.0
+        key = "%+.2f" % b
+        hist[key] = hist.get(key, 0) + 1
+    additivity = [(r["t_transpose"] + r["t_nn"]) / r["t_tnn"] for r in rows]
+    return {"shapes": n,
+            "nn_faster_than_nt": nn_faster / n, "nn_twice_nt": nn_twice / n,
+            "tnn_over_nt_below_1": below / n,
+            "max_tnn_over_nt": best_tnn["t_nt"] / best_tnn["t_tnn"],
+            "max_tnn_over_nt_shape": (best_tnn["m"], best_tnn["n"], best_tnn["k"]),
+            "max_nt_over_tnn": best_nt["t_tnn"] / best_nt["t_nt"],
+            "max_nt_over_tnn_shape": (best_nt["m"], best_nt["n"], best_nt["k"]),
+            "eq4_holds": sum(eq4), "eq4_agrees_with_direct_label": sum(int(a == b) for a, b in zip(eq4, direct)),
+            "parts_over_whole_median": sorted(additivity)[n // 2],
+            "log2_tnn_over_nt_histogram": dict(sorted(hist.items(), key=lambda kv: float(kv[0])))}
+
+
 def _fit_predict(train_shapes, train_labels, test_shapes) -> List[int]:
     from . import binding as mt
     mt.mtnn_train_selector(train_shapes, train_labels)

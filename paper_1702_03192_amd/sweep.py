@@ -208,7 +208,14 @@ def main(argv=None):
                    help="one or more timing tables; the model is fitted on their union (default: the shipped tables)")
     t.add_argument("--model", required=True)
     t.add_argument("--report", default=None)
+    st = sub.add_parser("stats", help="the case counts of the paper's Sections II / III and Eq. 4 on stored tables (host only)")
+    st.add_argument("--csv", nargs="+", default=None, help="timing tables (default: the shipped ones, one report each)")
     args = ap.parse_args(argv)
+    if args.cmd == "stats":
+        from . import selector_data as sd
+        for path in (args.csv or sd.TRAINING_TABLES):
+            print(os.path.basename(path), json.dumps(sd.nt_tnn_statistics(sd.load_sweep(path))))
+        return 0
     if args.cmd == "collect":
         collect(args.out, args.samples, args.min_batch_us, args.limit, args.grid, args.budget_s, args.mem_limit_gib)
     else:

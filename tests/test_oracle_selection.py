@@ -181,3 +181,22 @@ def test_stratified_split_keeps_proportions_and_is_seeded():
     assert sum(1 for i in te if lab[i] == 1) == 20
     assert S.stratified_split(lab, seed=7) == (tr, te)
     assert S.stratified_split(lab, seed=8)[1] != te
+
+
+def test_eq4_and_ratio_statistics_on_a_hand_table():
+    # Eq. 4 (Section III): TNN pays exactly when the transpose costs less than NN saves over NT.
+    assert S.tnn_pays(1.0, 10.0, 8.0) is True            # 1 < 10 - 8
+    assert S.tnn_pays(2.0, 10.0, 8.0) is False           # a tie stays with NT
+    assert S.tnn_pays(0.5, 8.0, 9.0) is False            # NT already faster than NN: never
+    # four shapes, times chosen so that every count can be read off by eye:
+    #   t_nt   t_nn   t_tnn    NN faster?  NN twice?  NT ahead of TNN?  P_TNN/P_NT  P_NT/P_TNN
+    #   10      4      5        yes         yes        no                2.0         0.5
+    #   10      8     12        yes         no         yes               0.833       1.2
+    #    6      7      9        no          no         yes               0.667       1.5
+    #    8      8      8        no          no         no (tie)          1.0         1.0
+    st = S.ratio_statistics([10.0, 10.0, 6.0, 8.0], [4.0, 8.0, 7.0, 8.0], [5.0, 12.0, 9.0, 8.0])
+    assert st == {"nn_faster_than_nt": 0.5, "nn_twice_nt": 0.25, "tnn_over_nt_below_1": 0.5,
+                  "max_tnn_over_nt": 2.0, "max_nt_over_tnn": 1.5}
+    # consistency with the label rule: "P_TNN / P_NT below 1" counts the strict NT wins, a subset of the +1 labels
+    labels = [S.label_from_times(a, c) for a, c in zip([10.0, 10.0, 6.0, 8.0], [5.0, 12.0, 9.0, 8.0])]
+    assert labels == [-1, 1, 1, 1]

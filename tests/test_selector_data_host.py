@@ -81,3 +81,27 @@ def test_sweep_table_round_trip(tmp_path):
                      "t_tnn_alloc": "3e-05", "nt_cfg": "a", "nn_cfg": "b"})
     rows = sd.load_sweep(str(p))
     assert rows[0]["m"] == 64 and rows[0]["t_tnn"] == 2.5e-05 and rows[0]["nt_cfg"] == "a"
+
+
+def test_nt_tnn_statistics_match_the_oracle_and_a_hand_table():
+    # the hand table of the oracle's own pin, with transposes that make t_tnn = t_transpose + t_nn on three rows
+    rows = [{"m": 64, "n": 64, "k": 64, "t_nt": 10.0, "t_nn": 4.0, "t_tnn": 5.0, "t_transpose": 1.0},
+            {"m": 128, "n": 64, "k": 64, "t_nt": 10.0, "t_nn": 8.0, "t_tnn": 12.0, "t_transpose": 4.0},
+            {"m": 64, "n": 128, "k": 64, "t_nt": 6.0, "t_nn": 7.0, "t_tnn": 9.0, "t_transpose": 2.0},
+            {"m": 64, "n": 64, "k": 128, "t_nt": 8.0, "t_nn": 8.0, "t_tnn": 8.0, "t_transpose": 1.0}]
+    got = sd.nt_tnn_statistics(rows)
+    ref = S.ratio_statistics([r["t_nt"] for r in rows], [r["t_nn"] for r in rows], [r["t_tnn"] for r in rows])
+    for key, val in ref.items():
+        assert got[key] == pytest.approx(val, rel=1e-12), key
+    assert got["max_tnn_over_nt_shape"] == (64, 64, 64) and got["max_nt_over_tnn_shape"] == (64, 128, 64)
+    # Eq. 4 holds on the first row only (1 < 10 - 4); the directly timed pair says TNN on the first row only: 4 of 4 agree
+    eq4 = [S.tnn_pays(r["t_transpose"], r["t_nt"], r["t_nn"]) for r in rows]
+    assert eq4 == [True, False, False, False]
+    assert got["eq4_holds"] == 1 and got["eq4_agrees_with_direct_label"] == 4
+    # log2(P_TNN / P_NT) = 1, -0.263, -0.585, 0 -> bins of a quarter, lower edge
+    assert got["log2_tnn_over_nt_histogram"] == {"-0.75": 1, "-0.50": 1, "+0.00": 1, "+1.00": 1}
+    # the shipped tables carry the columns the statistics need
+    for path in sd.TRAINING_TABLES:
+        st = sd.nt_tnn_statistics(sd.load_sweep(path))
+        assert st["shapes"] >= 384 and 0.0 <= st["nn_faster_than_nt"] <= 1.0
+        assert 0.9 < st["parts_over_whole_median"] < 1.1          # TNN's time is the sum of its two parts
