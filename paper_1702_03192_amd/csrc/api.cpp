@@ -321,7 +321,7 @@ int mtnn_auto3(void* stream, int mode, int m, int n, int k, const float* A, int 
         const bool can_ip = m > 0 && n > 0 && k > 0 && mtnn_tnn_inplace_supported(n, k, ldb) &&
                             !overlap(span(B, n, k, ldb), span(A, m, k, lda));
         path = (m > 0 && n > 0 && k > 0) ? mtnn_select3(m, n, k, room ? 1 : 0, can_ip ? 1 : 0) : 1;
-        if (path == -1 && !room) path = 1;       // (MTNN_FORCE may name TNN where there is no room for it)
+        if (path == -1 && !room) path = 1;       // (the memory rule once more: never TNN without room for B^T)
     }
     if (chosen) *chosen = path;
     if (path == -2) return mtnn_tnn_inplace(stream, m, n, k, A, lda, B, ldb, C, ldc);
