@@ -1086,23 +1086,43 @@ __global__ __launch_bounds__(256) void streamk_fixup_kernel(GemmParams p, int gr
 
 // C[i][j] = part[0][i][j] + part[1][i][j] + ... in split order (fixed, so results are reproducible)
 // EPI = kEpiBiasAct: ... then the column's bias and the clamp, as in the fused epilogue of the kernel
-template <int EPI>
+// V = 4: four consecutive columns per lane (N and ldc multiples of 4, C 16-byte aligned), else one.
+// The partial products of up to eight splits are loaded before any is added, so that a lane waits for
+// one round trip to memory per eight splits instead of one per split (the additions keep their order).
+constexpr int kReduceBatch = 8;
+
+template <int EPI, int V>
 __global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ part, int splits,
                                                             int M, int N, float* __restrict__ C, long ldc,
                                                             const float* __restrict__ bias, int relu)
 {
+    typedef float vecV __attribute__((ext_vector_type(V)));
     const long long total = (long long)M * N;
-    for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total;
-         e += (long long)gridDim.x * blockDim.x) {
-        float acc = part[e];
-        for (int s = 1; s < splits; ++s) acc += part[(size_t)s * total + e];
+    const long long groups = total / V;
+    for (long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x; g < groups;
+         g += (long long)gridDim.x * blockDim.x) {
+        const long long e = g * V;
+        vecV acc = *reinterpret_cast<const vecV*>(part + e);
+        for (int s0 = 1; s0 < splits; s0 += kReduceBatch) {
+            vecV v[kReduceBatch];
+#pragma unroll
+            for (int u = 0; u < kReduceBatch; ++u)
+                if (s0 + u < splits) v[u] = *reinterpret_cast<const vecV*>(part + (size_t)(s0 + u) * total + e);
+#pragma unroll
+            for (int u = 0; u < kReduceBatch; ++u)
+                if (s0 + u < splits) acc += v[u];
+        }
         const long long i = e / N;
         const long long j = e - i * N;
         if (EPI == kEpiBiasAct) {
-            acc += bias[j];
-            if (relu) acc = acc > 0.f ? acc : 0.f;
+#pragma unroll
+            for (int c = 0; c < V; ++c) {
+                float x = acc[c] + bias[j + c];
+                if (relu) x = x > 0.f ? x : 0.f;
+                acc[c] = x;
+            }
         }
-        C[(size_t)i * ldc + j] = acc;
+        *reinterpret_cast<vecV*>(C + (size_t)i * ldc + j) = acc;
     }
 }
 }  // namespace mtnn
