@@ -120,7 +120,7 @@ static double predicted_seconds(const Geometry& geo, const TileConfig& c, int op
     // one slab buffer only); measured at k <= 32 the 64 x 128 tiles lead there by 3-6 % for both
     // operations ((8192, 8192, 32) NT 55.9 us against 59.3 on 128 x 64 tiles, NN 60.0 against 64.8).
     if (pipelined && splits == 1 && k <= c.bk && c.bm == 64 && c.bn == 128) t *= 0.95;
-    if (splits > 1) t += 2.0e-6 + 0.3e-6 * ((splits + 7) / 8) + 4.0 * (double)m * n * (splits + 2) / 4.0e12;
+    if (splits > 1) t += 2.3e-6 + 0.3e-6 * ((splits + 7) / 8) + 4.0 * (double)m * n * (splits + 2) / 4.0e12;
     return t + 3.0e-6;
 }
 

@@ -186,20 +186,15 @@ int launch_gemm(hipStream_t s, const Geometry& geo, const Scratch& scratch, int 
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return (int)err;
     if (p.splits > 1) {
-        // four columns per lane where rows of C and of the partial products keep 16-byte alignment
-        const bool vec4 = (n % 4 == 0) && (ldc % 4 == 0) && ((reinterpret_cast<uintptr_t>(C) & 15) == 0) &&
-                          ((reinterpret_cast<uintptr_t>(p.part) & 15) == 0);
-        const long long groups = (long long)m * n / (vec4 ? 4 : 1);
-        long long blocks = (groups + 255) / 256;
+        const long long elems = (long long)m * n;
+        long long blocks = (elems + 255) / 256;
         if (blocks > 2048) blocks = 2048;
-        const dim3 grid((unsigned)blocks), block(256);
-        if (fuse_reduce) {
-            if (vec4) hipLaunchKernelGGL((reduce_splits_kernel<kEpiBiasAct, 4>), grid, block, 0, s, p.part, p.splits, m, n, C, ldc, p.bias, p.relu);
-            else hipLaunchKernelGGL((reduce_splits_kernel<kEpiBiasAct, 1>), grid, block, 0, s, p.part, p.splits, m, n, C, ldc, p.bias, p.relu);
-        } else {
-            if (vec4) hipLaunchKernelGGL((reduce_splits_kernel<kEpiNone, 4>), grid, block, 0, s, p.part, p.splits, m, n, C, ldc, nullptr, 0);
-            else hipLaunchKernelGGL((reduce_splits_kernel<kEpiNone, 1>), grid, block, 0, s, p.part, p.splits, m, n, C, ldc, nullptr, 0);
-        }
+        if (fuse_reduce)
+            hipLaunchKernelGGL(reduce_splits_kernel<kEpiBiasAct>, dim3((unsigned)blocks), dim3(256), 0, s,
+                               p.part, p.splits, m, n, C, ldc, p.bias, p.relu);
+        else
+            hipLaunchKernelGGL(reduce_splits_kernel<kEpiNone>, dim3((unsigned)blocks), dim3(256), 0, s,
+                               p.part, p.splits, m, n, C, ldc, nullptr, 0);
         err = hipGetLastError();
     }
     if (err == hipSuccess && (fuse_main || fuse_reduce)) {
