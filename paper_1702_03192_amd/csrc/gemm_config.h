@@ -53,6 +53,7 @@ struct GemmParams {
     int splits;
     int k_per_split;  // a multiple of every configuration's k slab
     float* part;
+    int part_cached;  // split-k: the partial products are small enough to be written with ordinary stores
     int sk_units_per_tile;   // gemm_streamk_kernel: k units (of kSplitQuantum) per tile
     // fused epilogues (read only by the kernel instances built for them)
     const float* bias;       // kEpiBiasAct: C = act(A x B + bias[column])

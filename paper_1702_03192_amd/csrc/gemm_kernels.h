@@ -895,7 +895,9 @@ __device__ __forceinline__ void dma_segment(const GemmParams& p, const WorkView&
 
     // epilogue: interior tiles of a 16-byte-aligned C go through wave-private LDS patches (the slab
     // buffers are free once every wave has passed this barrier)
-    const bool stream = whole_lines(w.C, w.ldc);
+    // (split-k partial products of a few MB are read back at once by the kernel that adds them: ordinary
+    //  stores, so that they are still in the caches then)
+    const bool stream = !(p.splits > 1 && p.part_cached) && whole_lines(w.C, w.ldc);
     // kEpiBiasAct: the bias of the lane's column of each block (the block -> column mapping of the stores),
     // added, and the clamp applied, as each value is stored: the same two operations on the same fp32
     // values as a separate pass over C
