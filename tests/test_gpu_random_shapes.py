@@ -121,3 +121,53 @@ def test_random_tnn_and_auto_against_oracle(i):
     got = out.cpu().numpy()
     check_gemm(got[0], C, S, k, f"tnn {m}x{n}x{k}")
     check_gemm(got[1], C, S, k, f"auto {m}x{n}x{k}")
+
+
+@pytest.mark.parametrize("i", range(60))
+def test_random_layer_products_with_fused_epilogues(i):
+    """The two layer products of the training step on random shapes and paddings: Y = act(X W^T + b) through
+    every forward mode, and dW = A B with W = fma(-lr, dW, W), against the fp64 oracle products with the bias,
+    clamp and update applied in float64."""
+    import torch
+    from gpu_util import Guarded, dev_matrix, tol
+    (m, n, k), r = _dims(3, i, 700, count=3)
+    pads = (0, 0, 0) if r[0] % 2 else (4 * int(r[1] % 3), int(r[2] % 5), 4 * int(r[3] % 2))
+    relu = bool(r[1] % 2)
+    mode = (1, -1, 0)[int(r[2] % 3)]
+    print(f"case {i}: {m}x{n}x{k} pads{pads} relu{relu} mode{mode}", flush=True)
+    X, W = I.nt_operands(m, n, k, 7700 + i, "normal")
+    b = (I.uniform_pm1(7700 + i, 2, 1, n)[0] * np.float32(np.sqrt(k))).astype(np.float32)
+    C, S = oracle.nt_ref(X, W, with_bound=True)
+    want = C + b.astype(np.float64)[None, :]
+    if relu:
+        want = np.maximum(want, 0.0)
+    dX, dW_ = dev_matrix(X, k + pads[0]), dev_matrix(W, k + pads[1])
+    db = torch.from_numpy(b).cuda()
+    ws = torch.empty(max(mt.mtnn_tnn_workspace_bytes(n, k), 256), dtype=torch.uint8, device="cuda")
+    out = Guarded(m, n, n + pads[2])
+    chosen = mt.mtnn_fc_layer_forward(dX, dW_, db, out.view, relu, mode, ws)
+    torch.cuda.synchronize()
+    assert chosen in (1, -1) and (mode == 0 or chosen == mode)
+    got, intact = out.host()
+    assert intact
+    # the clamp is 1-Lipschitz and the bias one more rounding: the product's bound plus an ulp of the sum
+    bound = tol(k) * S + 2.0 ** -23 * (np.abs(C) + np.abs(b)[None, :])
+    assert float((np.abs(got.astype(np.float64) - want) - bound).max()) <= 0
+
+    # the weight gradient of the same layer: dW = dY^T X (an NN product: (n x m) x (m x k)), W updated in its epilogue
+    lr = np.float32(0.03)
+    A = np.ascontiguousarray(I.normal01(7800 + i, 0, n, m))          # dY^T
+    Bm = X                                                            # m x k
+    G, Sg = oracle.nn_ref(A, Bm, with_bound=True)
+    W0 = W.copy()
+    dA, dB = dev_matrix(A, m + pads[0]), dev_matrix(Bm, k + pads[0])
+    g_out = Guarded(n, k, k + pads[2])
+    w_dev = torch.from_numpy(W0.copy()).cuda()
+    mt.mtnn_fc_weight_grad_sgd(dA, dB, g_out.view, w_dev, float(lr))
+    torch.cuda.synchronize()
+    g, g_ok = g_out.host()
+    assert g_ok
+    assert float((np.abs(g.astype(np.float64) - G) - tol(m) * Sg).max()) <= 0
+    w_want = W0.astype(np.float64) - float(lr) * G
+    w_bound = float(lr) * tol(m) * Sg + 2.0 ** -23 * (np.abs(W0) + float(lr) * np.abs(G))
+    assert float((np.abs(w_dev.cpu().numpy().astype(np.float64) - w_want) - w_bound).max()) <= 0
