@@ -23,7 +23,8 @@ PEAK_GBS = 8000.0
 TRANSPOSES = [(16384, 16384), (8192, 8192), (4096, 4096), (4096, 1024), (1024, 4096), (1024, 10), (4500, 1500)]
 INPLACE_TRANSPOSES = [(16384, 16384), (8192, 8192), (4096, 4096), (8192, 4096), (4096, 8192), (4096, 1024), (1024, 4096),
                       (4500, 1500), (4099, 1009)]
-LAUNCH_PATH_GEMMS = [(64, 64, 64), (256, 256, 256), (512, 512, 512), (1000, 1000, 1000), (1024, 1024, 1024)]
+LAUNCH_PATH_GEMMS = [(64, 64, 64), (256, 256, 256), (512, 512, 512), (1000, 1000, 1000), (1024, 1024, 1024),
+                     (64, 64, 8192), (128, 128, 4096)]      # the last two: divided 32 ways over k
 LAUNCH_PATH_TRANSPOSES = [(4096, 1024), (4500, 1500), (4096, 4096)]
 
 
